@@ -1,0 +1,180 @@
+/*
+ * rlgen -- generation hot path of asynchronous online-DPO RLHF on one MI355X (gfx950).
+ *
+ * The method (paper, Section 3 and Appendix D, Algorithm 1, procedure Generate) spends most of
+ * its run time drawing K completions per prompt from the current policy pi_theta at a sampling
+ * temperature (0.7 in Appendix A.1-A.3) and needs, for every drawn token, log pi(y_t | x, y_<t):
+ * the per-token terms of log pi_theta(y|x) in the Online DPO objective (Section 2.1) and of
+ * pi_old in the importance ratio of Appendix B, Eq. 1.  This library is that computation for a
+ * GPT-NeoX-shaped (Pythia) or Llama-shaped decoder, written as hand-made HIP kernels.
+ *
+ * Conventions
+ *  - Plain C ABI.  Every pointer is a DEVICE pointer unless its comment says HOST.
+ *  - The caller owns all memory, including the workspace.  The library allocates no device
+ *    memory; rlgen_destroy frees only host-side state.
+ *  - rlgen_generate / rlgen_score enqueue work on the stream given to the call and return; outputs
+ *    are valid once the caller has synchronised that stream.  HOST arrays are read before return.
+ *  - One context serves one call at a time (calls on one context must not overlap).
+ *  - Every function returns RLGEN_OK (0) or a negative RLGEN_ERR_* code.  A call rejected by host
+ *    validation launches nothing and writes nothing.  Conditions only the device can see (a token
+ *    id outside [0, vocab), a uniform outside [0, 1)) clamp the value, never read out of bounds,
+ *    and set a sticky flag reported by rlgen_status.
+ *  - Arithmetic: weights, GEMM inputs and the KV cache are bf16; accumulation, the residual
+ *    stream, normalisation statistics, softmax and log-sum-exp are fp32 (fp64 for the CDF scan).
+ */
+#ifndef RLGEN_H
+#define RLGEN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define RLGEN_OK                  0
+#define RLGEN_ERR_NULL           -1   /* a required pointer is null                         */
+#define RLGEN_ERR_BAD_CFG        -2   /* inconsistent or unsupported model configuration    */
+#define RLGEN_ERR_BAD_ARG        -3   /* a per-call argument is out of its domain           */
+#define RLGEN_ERR_CAPACITY       -4   /* the call exceeds max_seqs / max_kv_tokens / max_seq_len / max_batch_tokens */
+#define RLGEN_ERR_WORKSPACE      -5   /* workspace too small or misaligned                  */
+#define RLGEN_ERR_UNIMPLEMENTED  -6
+#define RLGEN_ERR_DEVICE         -7   /* a HIP call failed, or a device-detected input fault */
+
+#define RLGEN_ARCH_NEOX   0  /* LayerNorm+bias, parallel residual, GELU (erf), biased linears   */
+#define RLGEN_ARCH_LLAMA  1  /* RMSNorm, sequential residual, SwiGLU, no biases, grouped KV heads */
+
+#define RLGEN_DTYPE_F32   0  /* tensors supplied as fp32; rounded to bf16 (nearest even) on load */
+#define RLGEN_DTYPE_BF16  1  /* tensors supplied as bf16                                          */
+
+typedef struct rlgen_ctx rlgen_ctx; /* opaque */
+
+typedef struct {
+  int32_t arch;            /* RLGEN_ARCH_*                                                     */
+  int32_t n_layers;
+  int32_t d_model;         /* = n_q_heads * head_dim; multiple of 32                            */
+  int32_t n_q_heads;
+  int32_t n_kv_heads;      /* divides n_q_heads; = n_q_heads for NeoX                            */
+  int32_t head_dim;        /* multiple of 16, at most 256                                        */
+  int32_t d_ffn;           /* multiple of 32                                                     */
+  int32_t vocab;
+  int32_t rotary_dim;      /* even, <= head_dim: first rotary_dim dims of each head are rotated  */
+  float   rope_theta;      /* 10000 for the Pythia shapes, 500000 for the Llama-3.1 shape        */
+  float   norm_eps;
+  int32_t weight_dtype;    /* RLGEN_DTYPE_*: element type of every tensor in rlgen_weights       */
+  int32_t max_seqs;        /* capacity: sequences alive in one call (prompts * k)                */
+  int32_t max_seq_len;     /* capacity: longest prompt_len + max_new, or scored sequence         */
+  int64_t max_kv_tokens;   /* capacity: sum over sequences of (prompt_len + max_new) rounded up
+                              to a multiple of 32                                                */
+  int32_t max_batch_tokens;/* rows processed at once by prefill / score; >= max_seq_len;
+                              0 selects a default                                                */
+  int32_t reserved;
+} rlgen_model_cfg;
+
+/* Per-layer tensors, row-major, linear layers stored [out, in] and applied as y = W x + b.
+ * Pointers marked (NeoX) are null for Llama and vice versa. */
+typedef struct {
+  const void *norm1_g, *norm1_b;  /* [d]; _b (NeoX)                                     */
+  const void *norm2_g, *norm2_b;  /* [d]; _b (NeoX)                                     */
+  const void *wq, *wk, *wv;       /* [Hq*h, d], [Hkv*h, d], [Hkv*h, d]                  */
+  const void *bq, *bk, *bv;       /* (NeoX)                                             */
+  const void *wo, *bo;            /* [d, Hq*h]; bo (NeoX)                               */
+  const void *w_up, *b_up;        /* [F, d]; b_up (NeoX)                                */
+  const void *w_gate;             /* [F, d] (Llama)                                     */
+  const void *w_down, *b_down;    /* [d, F]; b_down (NeoX)                              */
+} rlgen_layer_weights;
+
+typedef struct {
+  const void *embed_in;                      /* [V, d]                                    */
+  const void *final_norm_g, *final_norm_b;   /* [d]; _b (NeoX)                            */
+  const void *lm_head;                       /* [V, d], no bias, not tied to embed_in     */
+  const rlgen_layer_weights *layers;         /* HOST array of n_layers entries            */
+} rlgen_weights;
+
+/* Bytes of workspace rlgen_create needs for this configuration (its private bf16 copy of the
+ * weights, the KV cache, activations and sampler partials), or 0 if cfg is null or invalid. */
+size_t rlgen_workspace_bytes(const rlgen_model_cfg *cfg);
+
+/* Builds a context for one policy (Algorithm 1: "update generation model theta <- theta_i").
+ * cfg, weights: HOST structs holding DEVICE tensor pointers.  workspace: DEVICE, 256-byte aligned,
+ * at least rlgen_workspace_bytes(cfg); it must stay alive, and must not be written by the caller,
+ * until rlgen_destroy.  The weight tensors are converted/copied on `hip_stream` (a hipStream_t, or
+ * null for the default stream); once that stream has been synchronised the library no longer reads
+ * them.  *out receives the context.  Errors: NULL, BAD_CFG, WORKSPACE, DEVICE. */
+int rlgen_create(const rlgen_model_cfg *cfg, const rlgen_weights *weights, void *workspace,
+                 size_t workspace_bytes, void *hip_stream, rlgen_ctx **out);
+
+/* Replaces the policy's weights in place with a new theta_i of the same shape (Algorithm 1,
+ * procedure Generate, first line; Section 5.2 notes that this hand-off is on the critical path). */
+int rlgen_update_weights(rlgen_ctx *ctx, const rlgen_weights *weights, void *hip_stream);
+
+/* y ~ pi_theta(. | x): k completions of exactly max_new tokens per prompt by inverse-CDF sampling
+ * from softmax(z / temperature), plus the log-probability of each emitted token under that same
+ * distribution (Section 2.1; Algorithm 1, procedure Generate; temperature: Appendix A.1).
+ *
+ *  prompts        [B, prompt_stride] int32, right-padded; cells at or beyond prompt_lens[b] are never read
+ *  prompt_lens    HOST [B] int32, each >= 1
+ *  uniforms       [B, k, max_new] fp32 in [0, 1): the random numbers of the draw.  Token t of sample
+ *                 (b, j) is the first vocabulary index whose cumulative probability, accumulated in
+ *                 ascending index order, exceeds uniforms[b, j, t] (if rounding leaves none, the last
+ *                 index with positive probability)
+ *  forced         nullable [B, k, max_new] int32: an entry >= 0 replaces the drawn token (used by
+ *                 parity tests to keep two implementations on one trajectory); its log-prob is reported
+ *  tokens         out [B, k, max_new] int32
+ *  token_logprobs out [B, k, max_new] fp32 = log softmax(z / temperature)[token]
+ *
+ * The k samples of one prompt share one prompt pass.  Errors: NULL, BAD_ARG (B, k, max_new < 1,
+ * prompt_len < 1, prompt_stride < max prompt_len, temperature not finite or <= 0), CAPACITY, DEVICE. */
+int rlgen_generate(rlgen_ctx *ctx, const int32_t *prompts, const int32_t *prompt_lens, int32_t B,
+                   int32_t prompt_stride, int32_t k, int32_t max_new, float temperature,
+                   const float *uniforms, const int32_t *forced, int32_t *tokens,
+                   float *token_logprobs, void *hip_stream);
+
+/* Teacher-forced log-probabilities, the terms of log pi(y | x) in the DPO objective (Section 2.1)
+ * and of the ratio in Appendix B, Eq. 1:
+ *   out[n, t] = log softmax(z_{t-1} / temperature)[seqs[n, t]]   for max(1, score_from[n]) <= t < seq_lens[n]
+ *   out[n, t] = 0                                                 elsewhere in [0, stride)
+ *  seqs [N, stride] int32 right-padded; seq_lens HOST [N]; score_from HOST [N] or null (= 1).
+ * Errors: NULL, BAD_ARG, CAPACITY, DEVICE. */
+int rlgen_score(rlgen_ctx *ctx, const int32_t *seqs, const int32_t *seq_lens,
+                const int32_t *score_from, int32_t N, int32_t stride, float temperature,
+                float *token_logprobs, void *hip_stream);
+
+/* Raw (temperature 1) logits at the last position of each sequence, [N, vocab] fp32.  The product
+ * path never writes logits to memory; this entry point exists so that tests can bound them. */
+int rlgen_debug_logits(rlgen_ctx *ctx, const int32_t *seqs, const int32_t *seq_lens, int32_t N,
+                       int32_t stride, float *logits, void *hip_stream);
+
+/* The final-norm + LM-head + sampling stage alone (the last line of procedure Generate applied to
+ * given residual rows): hidden [R, d] fp32, uniforms [R], forced nullable [R] -> tokens [R],
+ * token_logprobs [R].  R <= max_batch_tokens. */
+int rlgen_debug_sample(rlgen_ctx *ctx, const float *hidden, int32_t R, float temperature,
+                       const float *uniforms, const int32_t *forced, int32_t *tokens,
+                       float *token_logprobs, void *hip_stream);
+
+/* Consumers of the log-probs (Section 2.1, DPO objective).  seq_logprob[n] = sum of
+ * token_logprobs[n, t] over from[n] <= t < lens[n] (from, lens: DEVICE [N] int32). */
+int rlgen_sequence_logprob(const float *token_logprobs, const int32_t *from, const int32_t *lens,
+                           int32_t N, int32_t stride, float *seq_logprob, void *hip_stream);
+/* loss[p] = -log sigmoid(beta * ((pol_pos[p] - ref_pos[p]) - (pol_neg[p] - ref_neg[p]))), all [P] fp32. */
+int rlgen_dpo_loss(const float *pol_pos, const float *ref_pos, const float *pol_neg,
+                   const float *ref_neg, int32_t P, float beta, float *loss, void *hip_stream);
+
+/* Per-phase device times of the last rlgen_generate / rlgen_score on this context, in ms (any
+ * pointer may be null).  Synchronises the events it reads.  decode_attn_ms / decode_attn_launches
+ * cover the decode-attention kernel alone and are filled only while profiling is on. */
+int rlgen_get_timings(rlgen_ctx *ctx, float *prefill_ms, float *decode_ms, float *decode_attn_ms,
+                      int32_t *decode_attn_launches);
+int rlgen_set_profiling(rlgen_ctx *ctx, int32_t on);
+
+/* Synchronises `hip_stream` and returns RLGEN_ERR_DEVICE if a kernel has flagged a bad token id or
+ * uniform since the context was created (sticky), else RLGEN_OK. */
+int rlgen_status(rlgen_ctx *ctx, void *hip_stream);
+
+const char *rlgen_strerror(int code);
+void rlgen_destroy(rlgen_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RLGEN_H */

@@ -236,14 +236,21 @@ def sample_inverse_cdf(logp, u):
     return tok, min(u - lower, upper - u)
 
 
+def cdf_bucket(logp, tok):
+    """[C_{tok-1}, C_tok]: the interval of uniforms that the ascending-order CDF maps to `tok`."""
+    C = np.cumsum(np.exp(logp))
+    return (float(C[tok - 1]) if tok > 0 else 0.0), float(C[tok])
+
+
 def generate(dec: Decoder, prompt, k, max_new, temperature, uniforms, forced=None,
-             return_final_logits=False):
+             return_final_logits=False, buckets=None):
     """K completions of `max_new` tokens for one prompt (Algorithm 1, procedure Generate).
 
     uniforms: [k, max_new]; forced: optional [k, max_new] ints, entries >= 0 replace the draw.
     Returns tokens [k, max_new] int32, logprobs [k, max_new] float32 (of the emitted token under
     softmax(z / T)), margins [k, max_new] float64 (of the oracle's own draw).  The prompt is
-    processed once; each sample continues from a copy of its KV cache."""
+    processed once; each sample continues from a copy of its KV cache.  If `buckets` is a float64
+    array [k, max_new, 2] it receives the CDF interval of every emitted token."""
     uniforms = np.asarray(uniforms)
     assert uniforms.shape == (k, max_new)
     base = KVCache(dec.m.n_layers)
@@ -261,6 +268,8 @@ def generate(dec: Decoder, prompt, k, max_new, temperature, uniforms, forced=Non
             if forced is not None and forced[j][t] >= 0:
                 tok = int(forced[j][t])
             toks[j, t], lps[j, t] = tok, logp[tok]
+            if buckets is not None:
+                buckets[j, t] = cdf_bucket(logp, tok)
             if t + 1 < max_new or return_final_logits:
                 x = dec.forward([tok], cache)
         if return_final_logits:

@@ -1,0 +1,167 @@
+// Softmax attention over the per-sequence bf16 KV cache, for the decode step (one query per
+// sequence and query head: the bandwidth-bound part of generation) and for causal prefill.
+//
+// One wave owns 16 "columns" (queries) and streams one (sequence, kv head) K/V stream in
+// super-blocks of 32 keys.  The matrix cores serve as dot-product engines fed straight from global
+// memory: no LDS, no cross-lane reduction over head_dim.
+//   S^T[key, col] = sum_d K[key, d] q[col, d]       2 x ceil(h/32) MFMA 16x16x32 per super-block
+//   O^T[d, col]  += sum_key V^T[d, key] P^T[key, col]   h/16 MFMA 16x16x32 per super-block
+// The cache layout (see KvLayout) makes every operand fragment one 16-byte load per lane and every
+// load instruction one contiguous kilobyte per wave.  The K rows of a super-block are assigned to
+// MFMA rows so that the score registers of lane group g (keys 8g..8g+7) are exactly the B-operand
+// fragment P^T the second product needs: probabilities never leave registers.
+// Decode with one kv head serving G query heads (grouped-query attention) puts the G heads in the
+// columns, so K/V are read once per group; with G = 1 the query is replicated over the columns.
+#include "kernels.h"
+
+namespace {
+
+template <int HD, bool DECODE>
+__global__ __launch_bounds__(256) void attention_kernel(AttnArgs a) {
+  constexpr int NCH = HD / 8;            // 16-byte chunks per key row
+  constexpr int KSTEPS = (HD + 31) / 32; // MFMA steps over head_dim for the scores
+  constexpr int VT = HD / 16;            // 16-row tiles of V^T / O^T
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int c = lane & 15, g = lane >> 4;
+  const int Hkv = a.lay.Hkv, G = a.Hq / Hkv;
+  const int job = blockIdx.x * 4 + wave;
+
+  int cache_seq, kvh, qrow, qhead, qpos, maxkeys;
+  bool store_col;
+  if constexpr (DECODE) {
+    if (job >= a.S * Hkv) return;
+    const int s = job / Hkv;
+    kvh = job - s * Hkv;
+    cache_seq = s;
+    const int ctx = a.ctx_base[s] + a.ctx_add;
+    qrow = s;
+    qhead = kvh * G + (c % G);
+    qpos = ctx - 1;
+    maxkeys = ctx;
+    store_col = c < G;
+  } else {
+    if (job >= a.njobs * a.Hq) return;
+    const AttnJob jb = a.jobs[job / a.Hq];
+    qhead = job % a.Hq;
+    kvh = qhead / G;
+    cache_seq = jb.cache_seq;
+    const int tok = jb.qblock * 16 + c;
+    store_col = tok < jb.len;
+    qpos = min(tok, jb.len - 1);
+    qrow = jb.row0 + qpos;
+    maxkeys = min(jb.qblock * 16 + 16, jb.len);
+  }
+  const int cap = a.kv_cap[cache_seq];
+  const long long off = a.kv_off[cache_seq];
+  const uint16_t* __restrict__ kst = a.kv + a.lay.k_stream(off, cap, kvh);
+  const uint16_t* __restrict__ vst = a.kv + a.lay.v_stream(off, cap, kvh);
+
+  // query fragments (B operand): lane (c, g) holds q[col c][32 i + 8 g .. + 7]
+  bf16x8 qf[KSTEPS];
+  {
+    const uint16_t* qp = a.q + (size_t)qrow * a.q_ld + qhead * HD;
+#pragma unroll
+    for (int i = 0; i < KSTEPS; ++i) {
+      const int d0 = 32 * i + 8 * g;
+      if (d0 < HD) qf[i] = *(const bf16x8*)(qp + d0);
+      else
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qf[i][e] = (bf16_t)0.f;
+    }
+  }
+
+  f32x4 o[VT];
+#pragma unroll
+  for (int t = 0; t < VT; ++t) o[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m = -INFINITY, lsum = 0.f;
+
+  const int nsb = (maxkeys + 31) >> 5;
+  for (int sb = 0; sb < nsb; ++sb) {
+    const uint16_t* kb = kst + (size_t)sb * 32 * HD;
+    const uint16_t* vb = vst + (size_t)sb * 32 * HD;
+    bf16x8 kf[2][KSTEPS], vf[VT];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int i = 0; i < KSTEPS; ++i) {
+        const int chunk = 4 * i + g;
+        if (chunk < NCH) kf[t][i] = *(const bf16x8*)(kb + (((t * NCH + chunk) * 16 + c) << 3));
+        else
+#pragma unroll
+          for (int e = 0; e < 8; ++e) kf[t][i][e] = (bf16_t)0.f;
+      }
+#pragma unroll
+    for (int t = 0; t < VT; ++t) vf[t] = *(const bf16x8*)(vb + ((((t * 4 + g) * 16) + c) << 3));
+
+    f32x4 sc[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      sc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int i = 0; i < KSTEPS; ++i) sc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[t][i], qf[i], sc[t], 0, 0, 0);
+    }
+    // lane (c, g) now holds the scores of keys 32 sb + 8 g + 4 t + j against column c
+    float p[8];
+    float bmax = -INFINITY;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int key = sb * 32 + 8 * g + 4 * t + j;
+        const float v = key <= qpos ? sc[t][j] * a.scale : -INFINITY;
+        p[4 * t + j] = v;
+        bmax = fmaxf(bmax, v);
+      }
+    bmax = fmaxf(bmax, __shfl_xor(bmax, 16, WAVE));
+    bmax = fmaxf(bmax, __shfl_xor(bmax, 32, WAVE));
+    const float mnew = fmaxf(m, bmax);      // finite from the first super-block on: key 0 is visible to every column
+    const float alpha = __expf(m - mnew);
+    m = mnew;
+    float psum = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      p[e] = __expf(p[e] - mnew);
+      psum += p[e];
+    }
+    lsum = lsum * alpha + psum;
+    bf16x8 pf;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) pf[e] = (bf16_t)p[e];
+#pragma unroll
+    for (int t = 0; t < VT; ++t) {
+      o[t] *= alpha;
+      o[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[t], pf, o[t], 0, 0, 0);
+    }
+  }
+  lsum += __shfl_xor(lsum, 16, WAVE);
+  lsum += __shfl_xor(lsum, 32, WAVE);
+  const float inv = 1.0f / lsum;
+  if (store_col) {
+    uint16_t* op = a.out + (size_t)qrow * a.out_ld + qhead * HD;
+#pragma unroll
+    for (int t = 0; t < VT; ++t) {
+      u32x2 w;
+      w[0] = pack_bf16x2(o[t][0] * inv, o[t][1] * inv);
+      w[1] = pack_bf16x2(o[t][2] * inv, o[t][3] * inv);
+      *(u32x2*)(op + 16 * t + 4 * g) = w;
+    }
+  }
+}
+
+template <bool DECODE>
+hipError_t dispatch(const AttnArgs& a, int jobs, hipStream_t s) {
+  if (jobs <= 0) return hipSuccess;
+  dim3 grid((jobs + 3) / 4), block(256);
+  switch (a.lay.h) {
+#define CASE(H) case H: hipLaunchKernelGGL((attention_kernel<H, DECODE>), grid, block, 0, s, a); break;
+    CASE(16) CASE(32) CASE(48) CASE(64) CASE(80) CASE(96) CASE(112) CASE(128) CASE(256)
+#undef CASE
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t rl_attention_decode(const AttnArgs& a, hipStream_t s) { return dispatch<true>(a, a.S * a.lay.Hkv, s); }
+hipError_t rl_attention_prefill(const AttnArgs& a, hipStream_t s) { return dispatch<false>(a, a.njobs * a.Hq, s); }

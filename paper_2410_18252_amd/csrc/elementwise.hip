@@ -1,0 +1,260 @@
+// Small memory-bound kernels around the GEMMs: weight conversion, embedding gather, LayerNorm /
+// RMSNorm, rotary embedding + KV-cache write, and the consumers of the log-probs.
+#include "kernels.h"
+
+namespace {
+
+constexpr int TPB = 256;
+inline int blocks_for(size_t n, int per = TPB) { return (int)((n + per - 1) / per); }
+
+__global__ void to_bf16_kernel(uint16_t* dst, const void* src, int src_is_bf16, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride)
+    dst[i] = src_is_bf16 ? ((const uint16_t*)src)[i] : f32_to_bf16_bits(((const float*)src)[i]);
+}
+__global__ void to_f32_kernel(float* dst, const void* src, int src_is_bf16, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride)
+    dst[i] = src_is_bf16 ? bf16_bits_to_f32(((const uint16_t*)src)[i]) : ((const float*)src)[i];
+}
+__global__ void pack_gate_up_kernel(uint16_t* dst, const void* gate, const void* up, int src_is_bf16, int F, int d) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t n = (size_t)2 * F * d, stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) {
+    const int row = (int)(i / d), col = (int)(i % d);
+    const int blk = row >> 5, in = row & 31;
+    const void* src = (blk & 1) ? up : gate;
+    const size_t si = (size_t)((blk >> 1) * 32 + in) * d + col;
+    dst[i] = src_is_bf16 ? ((const uint16_t*)src)[si] : f32_to_bf16_bits(((const float*)src)[si]);
+  }
+}
+__global__ void rope_table_kernel(float2* tab, int max_pos, int r, double theta) {
+  const int half = r / 2;
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= max_pos * half) return;
+  const int pos = i / half, k = i % half;
+  const double ang = (double)pos * pow(theta, -2.0 * (double)k / (double)r);
+  tab[i] = make_float2((float)cos(ang), (float)sin(ang));
+}
+__global__ void fill_zero_kernel(u32x4* p, size_t n16) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n16; i += stride) p[i] = u32x4{0, 0, 0, 0};
+}
+
+__global__ void embed_kernel(float* x, const uint16_t* E, const int* tokens, const int* tok_index, int rows, int d,
+                             int vocab, unsigned* status) {
+  const int row = blockIdx.x;
+  int tok = tokens[tok_index ? tok_index[row] : row];
+  if (tok < 0 || tok >= vocab) {
+    if (threadIdx.x == 0) atomicOr(status, RLGEN_FAULT_TOKEN);
+    tok = min(max(tok, 0), vocab - 1);
+  }
+  const uint16_t* e = E + (size_t)tok * d;
+  float* xr = x + (size_t)row * d;
+  for (int i = threadIdx.x * 8; i < d; i += blockDim.x * 8) {
+    const u32x4 v = *(const u32x4*)(e + i);
+    f32x4 lo, hi;
+    lo[0] = __uint_as_float(v[0] << 16); lo[1] = __uint_as_float(v[0] & 0xffff0000u);
+    lo[2] = __uint_as_float(v[1] << 16); lo[3] = __uint_as_float(v[1] & 0xffff0000u);
+    hi[0] = __uint_as_float(v[2] << 16); hi[1] = __uint_as_float(v[2] & 0xffff0000u);
+    hi[2] = __uint_as_float(v[3] << 16); hi[3] = __uint_as_float(v[3] & 0xffff0000u);
+    *(f32x4*)(xr + i) = lo;
+    *(f32x4*)(xr + i + 4) = hi;
+  }
+}
+
+// One wave per row; the row lives in registers (d <= 64 * 4 * NV).  Mean, then variance of the
+// centred values (two passes over registers), all in fp32.
+template <int NV>
+__global__ __launch_bounds__(256) void norm_kernel(const float* x, const int* row_index, int rows, int d, float eps,
+                                                   const float* g1, const float* b1, uint16_t* out1,
+                                                   const float* g2, const float* b2, uint16_t* out2) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const float* xr = x + (size_t)(row_index ? row_index[row] : row) * d;
+  f32x4 v[NV];
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int col = (i * 64 + lane) * 4;
+    v[i] = col < d ? *(const f32x4*)(xr + col) : f32x4{0.f, 0.f, 0.f, 0.f};
+    sum += v[i][0] + v[i][1] + v[i][2] + v[i][3];
+  }
+  const bool rms = (b1 == nullptr);
+  const float mean = rms ? 0.f : wave_sum(sum) / (float)d;
+  float sq = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int col = (i * 64 + lane) * 4;
+    if (col < d) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        v[i][e] -= mean;
+        sq += v[i][e] * v[i][e];
+      }
+    }
+  }
+  const float rstd = rsqrtf(wave_sum(sq) / (float)d + eps);
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int col = (i * 64 + lane) * 4;
+    if (col >= d) continue;
+    const f32x4 ga = *(const f32x4*)(g1 + col);
+    f32x4 ba = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (!rms) ba = *(const f32x4*)(b1 + col);
+    u32x2 w;
+    w[0] = pack_bf16x2(v[i][0] * rstd * ga[0] + ba[0], v[i][1] * rstd * ga[1] + ba[1]);
+    w[1] = pack_bf16x2(v[i][2] * rstd * ga[2] + ba[2], v[i][3] * rstd * ga[3] + ba[3]);
+    *(u32x2*)(out1 + (size_t)row * d + col) = w;
+    if (out2) {
+      const f32x4 gb = *(const f32x4*)(g2 + col);
+      f32x4 bb = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (b2) bb = *(const f32x4*)(b2 + col);
+      w[0] = pack_bf16x2(v[i][0] * rstd * gb[0] + bb[0], v[i][1] * rstd * gb[1] + bb[1]);
+      w[1] = pack_bf16x2(v[i][2] * rstd * gb[2] + bb[2], v[i][3] * rstd * gb[3] + bb[3]);
+      *(u32x2*)(out2 + (size_t)row * d + col) = w;
+    }
+  }
+}
+
+// One thread per (row, head slot, 8-dim chunk).  Head slots: Hq query heads, Hkv key heads, Hkv
+// value heads.  The pair (i, i + r/2) of the first r dims is rotated by the row's position.
+__global__ void rope_kv_kernel(RopeArgs a) {
+  const int nch = a.h >> 3;
+  const int slots = a.Hq + 2 * a.Hkv;
+  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t total = (size_t)a.rows * slots * nch;
+  if (idx >= total) return;
+  const int chunk = (int)(idx % nch);
+  const int slot = (int)((idx / nch) % slots);
+  const int row = (int)(idx / ((size_t)nch * slots));
+  const float* src = a.qkv + (size_t)row * slots * a.h + (size_t)slot * a.h;
+  const int pos = a.pos[row] + a.pos_add;
+  const int half = a.r >> 1;
+  float v[8];
+  const bool is_v = slot >= a.Hq + a.Hkv;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int dim = chunk * 8 + e;
+    float x = src[dim];
+    if (!is_v && dim < a.r) {
+      const int i = dim < half ? dim : dim - half;
+      const float2 cs = a.table[(size_t)pos * half + i];
+      const float partner = src[dim < half ? dim + half : dim - half];
+      x = dim < half ? x * cs.x - partner * cs.y : x * cs.x + partner * cs.y;
+    }
+    v[e] = x;
+  }
+  if (slot < a.Hq) {
+    u32x4 w;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) w[e] = pack_bf16x2(v[2 * e], v[2 * e + 1]);
+    *(u32x4*)(a.q + (size_t)row * a.Hq * a.h + slot * a.h + chunk * 8) = w;
+    return;
+  }
+  const int s0 = a.dst_seq[row];
+  for (int cpy = 0; cpy < a.ncopy; ++cpy) {
+    const int s = s0 + cpy;
+    const long long off = a.kv_off[s];
+    const int cap = a.kv_cap[s];
+    if (!is_v) {
+      uint16_t* st = a.kv + a.lay.k_stream(off, cap, slot - a.Hq);
+      u32x4 w;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) w[e] = pack_bf16x2(v[2 * e], v[2 * e + 1]);
+      *(u32x4*)(st + a.lay.k_elem(pos, chunk * 8)) = w;
+    } else {
+      uint16_t* st = a.kv + a.lay.v_stream(off, cap, slot - a.Hq - a.Hkv);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) st[a.lay.v_elem(pos, chunk * 8 + e)] = f32_to_bf16_bits(v[e]);
+    }
+  }
+}
+
+__global__ void sequence_logprob_kernel(const float* tlp, const int* from, const int* lens, int N, int stride, float* out) {
+  const int n = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (n >= N) return;
+  float acc = 0.f;
+  for (int t = max(from[n], 0) + lane; t < min(lens[n], stride); t += 64) acc += tlp[(size_t)n * stride + t];
+  acc = wave_sum(acc);
+  if (lane == 0) out[n] = acc;
+}
+__global__ void dpo_loss_kernel(const float* pp, const float* rp, const float* pn, const float* rn, int P, float beta, float* loss) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= P) return;
+  const float x = beta * ((pp[i] - rp[i]) - (pn[i] - rn[i]));
+  // -log sigmoid(x) = max(-x, 0) + log1p(exp(-|x|))
+  loss[i] = fmaxf(-x, 0.f) + log1pf(expf(-fabsf(x)));
+}
+
+}  // namespace
+
+hipError_t rl_to_bf16(uint16_t* dst, const void* src, int src_is_bf16, size_t n, hipStream_t s) {
+  if (!n) return hipSuccess;
+  hipLaunchKernelGGL(to_bf16_kernel, dim3(min(blocks_for(n), 65536)), dim3(TPB), 0, s, dst, src, src_is_bf16, n);
+  return hipGetLastError();
+}
+hipError_t rl_to_f32(float* dst, const void* src, int src_is_bf16, size_t n, hipStream_t s) {
+  if (!n) return hipSuccess;
+  hipLaunchKernelGGL(to_f32_kernel, dim3(min(blocks_for(n), 65536)), dim3(TPB), 0, s, dst, src, src_is_bf16, n);
+  return hipGetLastError();
+}
+hipError_t rl_pack_gate_up(uint16_t* dst, const void* gate, const void* up, int src_is_bf16, int F, int d, hipStream_t s) {
+  hipLaunchKernelGGL(pack_gate_up_kernel, dim3(min(blocks_for((size_t)2 * F * d), 65536)), dim3(TPB), 0, s, dst, gate, up,
+                     src_is_bf16, F, d);
+  return hipGetLastError();
+}
+hipError_t rl_rope_table(float2* tab, int max_pos, int rotary_dim, float theta, hipStream_t s) {
+  const int n = max_pos * (rotary_dim / 2);
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(rope_table_kernel, dim3(blocks_for(n)), dim3(TPB), 0, s, tab, max_pos, rotary_dim, (double)theta);
+  return hipGetLastError();
+}
+hipError_t rl_fill_zero(void* p, size_t bytes, hipStream_t s) {
+  if (!bytes) return hipSuccess;
+  if (bytes % 16 != 0 || ((uintptr_t)p) % 16 != 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(min(blocks_for(bytes / 16), 262144)), dim3(TPB), 0, s, (u32x4*)p, bytes / 16);
+  return hipGetLastError();
+}
+hipError_t rl_embed(float* x, const uint16_t* E, const int* tokens, const int* tok_index, int rows, int d, int vocab,
+                    unsigned* status, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  hipLaunchKernelGGL(embed_kernel, dim3(rows), dim3(128), 0, s, x, E, tokens, tok_index, rows, d, vocab, status);
+  return hipGetLastError();
+}
+hipError_t rl_norm(const float* x, const int* row_index, int rows, int d, float eps, const float* g1, const float* b1,
+                   uint16_t* out1, const float* g2, const float* b2, uint16_t* out2, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  const dim3 grid((rows + 3) / 4), block(256);
+  const int nv = (d + 255) / 256;
+#define NORM(NV) hipLaunchKernelGGL((norm_kernel<NV>), grid, block, 0, s, x, row_index, rows, d, eps, g1, b1, out1, g2, b2, out2)
+  if (nv <= 1) NORM(1);
+  else if (nv <= 2) NORM(2);
+  else if (nv <= 4) NORM(4);
+  else if (nv <= 8) NORM(8);
+  else if (nv <= 16) NORM(16);
+  else if (nv <= 32) NORM(32);
+  else return hipErrorInvalidValue;
+#undef NORM
+  return hipGetLastError();
+}
+hipError_t rl_rope_kv(const RopeArgs& a, hipStream_t s) {
+  const size_t total = (size_t)a.rows * (a.Hq + 2 * a.Hkv) * (a.h >> 3);
+  if (!total) return hipSuccess;
+  hipLaunchKernelGGL(rope_kv_kernel, dim3(blocks_for(total)), dim3(TPB), 0, s, a);
+  return hipGetLastError();
+}
+hipError_t rl_sequence_logprob(const float* tlp, const int* from, const int* lens, int N, int stride, float* out, hipStream_t s) {
+  if (N <= 0) return hipSuccess;
+  hipLaunchKernelGGL(sequence_logprob_kernel, dim3((N + 3) / 4), dim3(256), 0, s, tlp, from, lens, N, stride, out);
+  return hipGetLastError();
+}
+hipError_t rl_dpo_loss(const float* pp, const float* rp, const float* pn, const float* rn, int P, float beta, float* loss, hipStream_t s) {
+  if (P <= 0) return hipSuccess;
+  hipLaunchKernelGGL(dpo_loss_kernel, dim3(blocks_for(P)), dim3(TPB), 0, s, pp, rp, pn, rn, P, beta, loss);
+  return hipGetLastError();
+}

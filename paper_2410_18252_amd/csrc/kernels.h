@@ -1,0 +1,129 @@
+// Host-callable launchers of the rlgen kernels.  Everything here is internal to librlgen.so.
+#pragma once
+#include "common.h"
+
+// ------------------------------------------------------------------ KV cache layout
+// One stream per (layer, sequence, kv head): `cap` keys (a multiple of 32) of head_dim bf16 each,
+// K stream then V stream, cut into super-blocks of 32 keys.  Inside a super-block the elements are
+// ordered so that every MFMA operand fragment the attention kernel needs is one 16-byte unit and
+// every wave-wide load instruction reads one contiguous kilobyte:
+//   K super-block: [t = 0..1][chunk = 0..h/8-1][r = 0..15][8 head dims]
+//                  holding key 8 (r / 4) + 4 t + r % 4, head dims 8 chunk .. 8 chunk + 7
+//   V super-block: [tile = 0..h/16-1][g = 0..3][r = 0..15][8 keys]
+//                  holding head dim 16 tile + r, keys 8 g .. 8 g + 7
+// Streams of a sequence: K of head 0..Hkv-1, then V of head 0..Hkv-1; sequences follow each other
+// at token offsets kv_off[s]; layers are max_kv_tokens * Hkv * h * 2 elements apart.
+struct KvLayout {
+  int Hkv, h;
+  long long layer_stride;  // elements between layers
+  __host__ __device__ long long seq_base(long long kv_off) const { return 2LL * kv_off * Hkv * h; }
+  __host__ __device__ long long k_stream(long long kv_off, int cap, int head) const {
+    return seq_base(kv_off) + (long long)head * cap * h;
+  }
+  __host__ __device__ long long v_stream(long long kv_off, int cap, int head) const {
+    return seq_base(kv_off) + (long long)(Hkv + head) * cap * h;
+  }
+  // element offset of (key, dim) inside a K stream / V stream
+  __host__ __device__ long long k_elem(int key, int dim) const {
+    const int sb = key >> 5, kk = key & 31;
+    const int r = 4 * (kk >> 3) + (kk & 3), t = (kk >> 2) & 1;
+    return (long long)sb * 32 * h + (((t * (h >> 3) + (dim >> 3)) * 16 + r) << 3) + (dim & 7);
+  }
+  __host__ __device__ long long v_elem(int key, int dim) const {
+    const int sb = key >> 5, kk = key & 31;
+    return (long long)sb * 32 * h + (((((dim >> 4) * 4 + (kk >> 3)) * 16) + (dim & 15)) << 3) + (kk & 7);
+  }
+};
+
+// ------------------------------------------------------------------ GEMM
+enum { EPI_F32 = 0, EPI_RESID = 1, EPI_GELU_BF16 = 2, EPI_SWIGLU_BF16 = 3, EPI_LMHEAD = 4 };
+struct GemmArgs {
+  const void* A; int lda;       // [M, K] bf16
+  const void* W; int ldw;       // [N, K] bf16
+  int M, N, K;
+  const float* bias;            // [N] or null
+  void* out; int ldo;           // EPI_F32 / EPI_RESID: fp32 [M, N]; *_BF16: bf16
+  // EPI_LMHEAD only
+  float temperature;
+  float2* partial;              // [M, ceil(N/64)] (max, sum exp) of the tempered logits per 64 columns
+  const int* target;            // nullable [M]: column whose tempered logit is captured
+  float* target_logit;          // [M]
+};
+hipError_t rl_gemm(const GemmArgs& g, int epi, hipStream_t s);
+
+// ------------------------------------------------------------------ attention
+struct AttnJob { int cache_seq, row0, len, qblock; };   // prefill: 16 queries [16 qblock, 16 qblock + 16) of one sequence
+struct AttnArgs {
+  const uint16_t* q; int q_ld;        // bf16 [rows, Hq * h], rotated
+  uint16_t* out; int out_ld;          // bf16 [rows, Hq * h]
+  const uint16_t* kv;                 // this layer's cache base
+  KvLayout lay;
+  const int* kv_off; const int* kv_cap;  // per cache sequence
+  int Hq;
+  float scale;
+  // decode: one query row per sequence, keys 0 .. ctx_base[s] + ctx_add - 1
+  const int* ctx_base; int ctx_add; int S;
+  // prefill
+  const AttnJob* jobs; int njobs;
+};
+hipError_t rl_attention_decode(const AttnArgs& a, hipStream_t s);
+hipError_t rl_attention_prefill(const AttnArgs& a, hipStream_t s);
+
+// ------------------------------------------------------------------ element-wise and small kernels
+// dst bf16 <- src (fp32 rounded to nearest even, or bf16 copied); n elements
+hipError_t rl_to_bf16(uint16_t* dst, const void* src, int src_is_bf16, size_t n, hipStream_t s);
+// dst fp32 <- src (fp32 copied, or bf16 expanded); n elements
+hipError_t rl_to_f32(float* dst, const void* src, int src_is_bf16, size_t n, hipStream_t s);
+// gate/up rows interleaved in blocks of 32 rows: dst [2F, d] bf16
+hipError_t rl_pack_gate_up(uint16_t* dst, const void* gate, const void* up, int src_is_bf16, int F, int d, hipStream_t s);
+// cos/sin table [max_pos, r/2] (float2), angles pos * theta^(-2i/r) evaluated in fp64
+hipError_t rl_rope_table(float2* tab, int max_pos, int rotary_dim, float theta, hipStream_t s);
+hipError_t rl_fill_zero(void* p, size_t bytes, hipStream_t s);
+
+// x[row, :] = float(E[tok[row]]), tok gathered as tokens[tok_index[row]] ; flags a bad id
+hipError_t rl_embed(float* x, const uint16_t* E, const int* tokens, const int* tok_index, int rows, int d,
+                    int vocab, unsigned* status, hipStream_t s);
+// LayerNorm / RMSNorm of fp32 rows into bf16.  out2/g2/b2 nullable (second normalisation of the same
+// row with other gains, NeoX); b1 null selects RMSNorm.  row_index nullable: source row of output row i.
+hipError_t rl_norm(const float* x, const int* row_index, int rows, int d, float eps, const float* g1,
+                   const float* b1, uint16_t* out1, const float* g2, const float* b2, uint16_t* out2,
+                   hipStream_t s);
+
+// Rotary + KV write.  qkv fp32 [rows, (Hq + 2 Hkv) h] (bias already added) ->
+//   q bf16 [rows, Hq h] rotated; k (rotated) and v written to the cache of `ncopy` consecutive cache
+//   sequences starting at dst_seq[row].
+struct RopeArgs {
+  const float* qkv; int rows;
+  int Hq, Hkv, h, r;
+  const float2* table;           // [max_pos, r/2]
+  const int* pos;                // [rows] position of each row in its sequence
+  const int* dst_seq;            // [rows] first cache sequence receiving the row's k, v
+  int ncopy;
+  int pos_add;                   // added to pos[] (decode step)
+  uint16_t* q;                   // out
+  uint16_t* kv; KvLayout lay; const int* kv_off; const int* kv_cap;
+};
+hipError_t rl_rope_kv(const RopeArgs& a, hipStream_t s);
+
+// Sampling phase 2 (after the EPI_LMHEAD GEMM): per row, combine the per-64-column partials into
+// log Z, find the column group where the CDF crosses u, recompute that group's 64 logits from hfin and
+// the LM head, scan it, and emit token and log-prob.  forced nullable.  Output index out_index[row].
+struct SampleArgs {
+  const float2* partial; int ngroups;
+  const uint16_t* hfin; int d;          // bf16 [R, d] rows fed to the LM head GEMM
+  const uint16_t* lm_head; int vocab;   // bf16 [V, d]
+  float temperature;
+  const float* uniforms; const int* forced; const int* io_index;  // value index of row i: io_index[i] * io_stride + io_add
+  int io_stride, io_add;
+  int* tokens; float* logprobs;         // written at the same index
+  int* next_token;                      // nullable [R]: copy of the emitted token for the next decode step
+  int R;
+  unsigned* status;
+};
+hipError_t rl_sample(const SampleArgs& a, hipStream_t s);
+// Scoring phase 2: out[out_index[i]] = target_logit[i] - log Z(i)
+hipError_t rl_score_finalize(const float2* partial, int ngroups, const float* target_logit, const int* out_index,
+                             float* out, int R, hipStream_t s);
+
+hipError_t rl_sequence_logprob(const float* tlp, const int* from, const int* lens, int N, int stride, float* out, hipStream_t s);
+hipError_t rl_dpo_loss(const float* pp, const float* rp, const float* pn, const float* rn, int P, float beta, float* loss, hipStream_t s);

@@ -1,0 +1,691 @@
+// Host side of librlgen.so: configuration checks, workspace carving, weight packing and the
+// scheduler that turns rlgen_generate / rlgen_score into kernel launches on the caller's stream.
+// No device memory is allocated here; the only host allocations are the context and one pinned
+// staging buffer for per-call sequence metadata.
+#include "../../include/rlgen.h"
+#include "kernels.h"
+
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+namespace {
+
+constexpr size_t ALIGN = 256;
+inline size_t align_up(size_t v, size_t a = ALIGN) { return (v + a - 1) / a * a; }
+inline int round32(int v) { return (v + 31) & ~31; }
+
+struct SeqMeta {       // one per sequence of a call, consumed by expand_kernel
+  int row0;            // first row of the sequence in its chunk's packed activations
+  int len;             // tokens processed by the prompt / scoring pass
+  int src_off;         // offset of the sequence's first token in the caller's token array
+  int cache_seq;       // cache sequence that receives (the first copy of) its keys and values
+  int job0;            // first attention job of the sequence within its chunk
+  int lm0;             // first LM-head row of the sequence within its chunk (scoring)
+  int score_from;      // first scored position
+  int out_off;         // offset of the sequence's row in the output array (scoring)
+};
+
+struct LayerW {
+  float *n1g, *n1b, *n2g, *n2b, *bqkv, *bo, *bup, *bdown;
+  uint16_t *wqkv, *wo, *wup, *wdown;
+};
+
+struct Carve {
+  size_t off = 0;
+  template <typename T> T* take(char* base, size_t count) {
+    T* p = base ? (T*)(base + off) : nullptr;
+    off = align_up(off + count * sizeof(T));
+    return p;
+  }
+};
+
+}  // namespace
+
+struct rlgen_ctx {
+  rlgen_model_cfg cfg;
+  int R;          // activation rows
+  int LM;         // rows per LM-head pass
+  int ngroups;
+  size_t need;
+  char* ws;
+  // weights
+  uint16_t *embed, *lm_head;
+  float *fng, *fnb;
+  std::vector<LayerW> layers;
+  float2* rope;
+  uint16_t* kv;
+  KvLayout lay;
+  unsigned* status;
+  // per-call metadata (device)
+  SeqMeta* d_meta;
+  int *d_kv_off, *d_kv_cap, *d_ctx_base, *d_iota, *d_lastrow;
+  int *d_tok_index, *d_pos, *d_dst_seq, *d_lm_row, *d_target, *d_out_index, *d_next_token;
+  AttnJob* d_jobs;
+  // activations
+  float *x, *qkv, *target_logit;
+  uint16_t *n1, *n2, *q, *attn, *act, *hfin;
+  float2* partial;
+  // host staging (pinned)
+  char* h_stage;
+  size_t stage_bytes;
+  hipEvent_t ev_meta;
+  bool meta_pending;
+  // timings
+  hipEvent_t ev_start, ev_mid, ev_end;
+  bool timed;
+  bool profiling;
+  std::vector<hipEvent_t> prof_events;
+  size_t prof_used;
+};
+
+namespace {
+
+int check_cfg(const rlgen_model_cfg* c) {
+  if (!c) return RLGEN_ERR_NULL;
+  if (c->arch != RLGEN_ARCH_NEOX && c->arch != RLGEN_ARCH_LLAMA) return RLGEN_ERR_BAD_CFG;
+  if (c->n_layers < 1 || c->d_model < 32 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->head_dim < 16 ||
+      c->d_ffn < 32 || c->vocab < 2)
+    return RLGEN_ERR_BAD_CFG;
+  if (c->d_model != c->n_q_heads * c->head_dim) return RLGEN_ERR_BAD_CFG;
+  if (c->n_q_heads % c->n_kv_heads != 0 || c->n_q_heads / c->n_kv_heads > 16) return RLGEN_ERR_BAD_CFG;
+  if (c->arch == RLGEN_ARCH_NEOX && c->n_kv_heads != c->n_q_heads) return RLGEN_ERR_BAD_CFG;
+  const int h = c->head_dim;
+  if (!(h == 256 || (h % 16 == 0 && h <= 128))) return RLGEN_ERR_BAD_CFG;
+  if (c->d_model % 32 != 0 || c->d_ffn % 32 != 0 || c->d_model > 8192) return RLGEN_ERR_BAD_CFG;
+  if (c->rotary_dim < 0 || c->rotary_dim % 2 != 0 || c->rotary_dim > h) return RLGEN_ERR_BAD_CFG;
+  if (!(c->rope_theta > 0.f) || !std::isfinite(c->rope_theta)) return RLGEN_ERR_BAD_CFG;
+  if (!(c->norm_eps > 0.f) || !std::isfinite(c->norm_eps)) return RLGEN_ERR_BAD_CFG;
+  if (c->weight_dtype != RLGEN_DTYPE_F32 && c->weight_dtype != RLGEN_DTYPE_BF16) return RLGEN_ERR_BAD_CFG;
+  if (c->max_seqs < 1 || c->max_seq_len < 2 || c->max_kv_tokens < round32(c->max_seq_len)) return RLGEN_ERR_BAD_CFG;
+  if (c->max_kv_tokens > (1LL << 30) || c->max_seqs > (1 << 20) || c->max_seq_len > (1 << 20)) return RLGEN_ERR_BAD_CFG;
+  if (c->max_batch_tokens != 0 && c->max_batch_tokens < c->max_seq_len) return RLGEN_ERR_BAD_CFG;
+  if (c->max_batch_tokens > (1 << 22)) return RLGEN_ERR_BAD_CFG;
+  return RLGEN_OK;
+}
+
+// Lays the workspace out; with base == nullptr only the size is computed.
+size_t carve(rlgen_ctx* c, char* base) {
+  const rlgen_model_cfg& m = c->cfg;
+  const size_t d = m.d_model, F = m.d_ffn, V = m.vocab, h = m.head_dim;
+  const size_t qd = (size_t)m.n_q_heads * h, kvd = (size_t)m.n_kv_heads * h, nqkv = qd + 2 * kvd;
+  const bool llama = m.arch == RLGEN_ARCH_LLAMA;
+  int mbt = m.max_batch_tokens ? m.max_batch_tokens : 16384;
+  if (mbt < m.max_seq_len) mbt = m.max_seq_len;
+  c->R = mbt > m.max_seqs ? mbt : m.max_seqs;
+  c->LM = c->R < 4096 ? c->R : 4096;
+  if (c->LM < m.max_seqs) c->LM = m.max_seqs;
+  c->ngroups = (int)((V + 63) / 64);
+  const size_t R = c->R, LM = c->LM, S = m.max_seqs;
+
+  Carve k;
+  c->status = k.take<unsigned>(base, 64);
+  c->embed = k.take<uint16_t>(base, V * d);
+  c->lm_head = k.take<uint16_t>(base, V * d);
+  c->fng = k.take<float>(base, d);
+  c->fnb = k.take<float>(base, d);
+  c->layers.resize(m.n_layers);
+  for (auto& L : c->layers) {
+    L.n1g = k.take<float>(base, d); L.n1b = k.take<float>(base, d);
+    L.n2g = k.take<float>(base, d); L.n2b = k.take<float>(base, d);
+    L.wqkv = k.take<uint16_t>(base, nqkv * d); L.bqkv = k.take<float>(base, nqkv);
+    L.wo = k.take<uint16_t>(base, d * qd); L.bo = k.take<float>(base, d);
+    L.wup = k.take<uint16_t>(base, (llama ? 2 : 1) * F * d); L.bup = k.take<float>(base, F);
+    L.wdown = k.take<uint16_t>(base, d * F); L.bdown = k.take<float>(base, d);
+  }
+  c->rope = k.take<float2>(base, (size_t)m.max_seq_len * (m.rotary_dim / 2 > 0 ? m.rotary_dim / 2 : 1));
+  c->lay.Hkv = m.n_kv_heads;
+  c->lay.h = m.head_dim;
+  c->lay.layer_stride = 2LL * m.max_kv_tokens * m.n_kv_heads * m.head_dim;
+  c->kv = k.take<uint16_t>(base, (size_t)c->lay.layer_stride * m.n_layers);
+  c->d_meta = k.take<SeqMeta>(base, S);
+  c->d_kv_off = k.take<int>(base, S); c->d_kv_cap = k.take<int>(base, S);
+  c->d_ctx_base = k.take<int>(base, S); c->d_iota = k.take<int>(base, S);
+  c->d_lastrow = k.take<int>(base, S); c->d_next_token = k.take<int>(base, S);
+  c->d_tok_index = k.take<int>(base, R); c->d_pos = k.take<int>(base, R); c->d_dst_seq = k.take<int>(base, R);
+  c->d_lm_row = k.take<int>(base, R); c->d_target = k.take<int>(base, R); c->d_out_index = k.take<int>(base, R);
+  c->d_jobs = k.take<AttnJob>(base, R / 16 + S + 1);
+  c->x = k.take<float>(base, R * d);
+  c->n1 = k.take<uint16_t>(base, R * d);
+  c->n2 = k.take<uint16_t>(base, R * d);
+  c->qkv = k.take<float>(base, R * nqkv);
+  c->q = k.take<uint16_t>(base, R * qd);
+  c->attn = k.take<uint16_t>(base, R * qd);
+  c->act = k.take<uint16_t>(base, R * F);
+  c->hfin = k.take<uint16_t>(base, LM * d);
+  c->partial = k.take<float2>(base, LM * (size_t)c->ngroups);
+  c->target_logit = k.take<float>(base, LM);
+  return k.off;
+}
+
+#define HIPCHK(expr) do { if ((expr) != hipSuccess) return RLGEN_ERR_DEVICE; } while (0)
+
+int pack_weights(rlgen_ctx* c, const rlgen_weights* w, hipStream_t st) {
+  const rlgen_model_cfg& m = c->cfg;
+  const bool llama = m.arch == RLGEN_ARCH_LLAMA;
+  const int bf = m.weight_dtype == RLGEN_DTYPE_BF16;
+  const size_t d = m.d_model, F = m.d_ffn, V = m.vocab, h = m.head_dim;
+  const size_t qd = (size_t)m.n_q_heads * h, kvd = (size_t)m.n_kv_heads * h;
+  if (!w || !w->embed_in || !w->final_norm_g || !w->lm_head || !w->layers) return RLGEN_ERR_NULL;
+  if (!llama && !w->final_norm_b) return RLGEN_ERR_NULL;
+  for (int l = 0; l < m.n_layers; ++l) {
+    const rlgen_layer_weights& s = w->layers[l];
+    if (!s.norm1_g || !s.norm2_g || !s.wq || !s.wk || !s.wv || !s.wo || !s.w_up || !s.w_down) return RLGEN_ERR_NULL;
+    if (llama ? !s.w_gate : (!s.norm1_b || !s.norm2_b || !s.bq || !s.bk || !s.bv || !s.bo || !s.b_up || !s.b_down))
+      return RLGEN_ERR_NULL;
+  }
+  HIPCHK(rl_to_bf16(c->embed, w->embed_in, bf, V * d, st));
+  HIPCHK(rl_to_bf16(c->lm_head, w->lm_head, bf, V * d, st));
+  HIPCHK(rl_to_f32(c->fng, w->final_norm_g, bf, d, st));
+  if (!llama) HIPCHK(rl_to_f32(c->fnb, w->final_norm_b, bf, d, st));
+  for (int l = 0; l < m.n_layers; ++l) {
+    const rlgen_layer_weights& s = w->layers[l];
+    LayerW& L = c->layers[l];
+    HIPCHK(rl_to_f32(L.n1g, s.norm1_g, bf, d, st));
+    HIPCHK(rl_to_f32(L.n2g, s.norm2_g, bf, d, st));
+    HIPCHK(rl_to_bf16(L.wqkv, s.wq, bf, qd * d, st));
+    HIPCHK(rl_to_bf16(L.wqkv + qd * d, s.wk, bf, kvd * d, st));
+    HIPCHK(rl_to_bf16(L.wqkv + (qd + kvd) * d, s.wv, bf, kvd * d, st));
+    HIPCHK(rl_to_bf16(L.wo, s.wo, bf, d * qd, st));
+    HIPCHK(rl_to_bf16(L.wdown, s.w_down, bf, d * F, st));
+    if (llama) {
+      HIPCHK(rl_pack_gate_up(L.wup, s.w_gate, s.w_up, bf, (int)F, (int)d, st));
+    } else {
+      HIPCHK(rl_to_bf16(L.wup, s.w_up, bf, F * d, st));
+      HIPCHK(rl_to_f32(L.n1b, s.norm1_b, bf, d, st));
+      HIPCHK(rl_to_f32(L.n2b, s.norm2_b, bf, d, st));
+      HIPCHK(rl_to_f32(L.bqkv, s.bq, bf, qd, st));
+      HIPCHK(rl_to_f32(L.bqkv + qd, s.bk, bf, kvd, st));
+      HIPCHK(rl_to_f32(L.bqkv + qd + kvd, s.bv, bf, kvd, st));
+      HIPCHK(rl_to_f32(L.bo, s.bo, bf, d, st));
+      HIPCHK(rl_to_f32(L.bup, s.b_up, bf, F, st));
+      HIPCHK(rl_to_f32(L.bdown, s.b_down, bf, d, st));
+    }
+  }
+  return RLGEN_OK;
+}
+
+// Expands per-sequence metadata into the per-row arrays the kernels index.  One block per sequence.
+__global__ void expand_kernel(const SeqMeta* meta, int first, const int* tokens, int* tok_index, int* pos, int* dst_seq,
+                              AttnJob* jobs, int* lm_row, int* target, int* out_index, int scoring) {
+  const SeqMeta m = meta[first + blockIdx.x];
+  for (int p = threadIdx.x; p < m.len; p += blockDim.x) {
+    tok_index[m.row0 + p] = m.src_off + p;
+    pos[m.row0 + p] = p;
+    dst_seq[m.row0 + p] = m.cache_seq;
+  }
+  const int nj = (m.len + 15) >> 4;
+  for (int j = threadIdx.x; j < nj; j += blockDim.x) jobs[m.job0 + j] = AttnJob{m.cache_seq, m.row0, m.len, j};
+  if (scoring) {
+    for (int t = m.score_from + threadIdx.x; t < m.len; t += blockDim.x) {
+      const int i = m.lm0 + (t - m.score_from);
+      lm_row[i] = m.row0 + t - 1;
+      target[i] = tokens[m.src_off + t];
+      out_index[i] = m.out_off + t;
+    }
+  }
+}
+__global__ void fill_f32_kernel(float* p, size_t n, float v) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) p[i] = v;
+}
+__global__ void clamp_targets_kernel(int* target, int n, int vocab, unsigned* status) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const int t = target[i];
+  if (t < 0 || t >= vocab) {
+    atomicOr(status, RLGEN_FAULT_TOKEN);
+    target[i] = min(max(t, 0), vocab - 1);
+  }
+}
+
+struct Chunk { int first, count, rows, jobs, lm_rows; };
+
+// One pass of all decoder blocks over `rows` packed rows held in c->x.
+//  decode: rows are sequences 0..rows-1 at step t (the token drawn at step t-1 enters at position
+//          ctx_base + t - 1); otherwise rows follow d_pos / d_dst_seq / d_jobs of the current chunk.
+int run_layers(rlgen_ctx* c, int rows, bool decode, int t, int ncopy, bool use_cache_layers, int njobs, hipStream_t st) {
+  const rlgen_model_cfg& m = c->cfg;
+  const bool llama = m.arch == RLGEN_ARCH_LLAMA;
+  const int d = m.d_model, F = m.d_ffn, h = m.head_dim;
+  const int qd = m.n_q_heads * h, nqkv = qd + 2 * m.n_kv_heads * h;
+  for (int l = 0; l < m.n_layers; ++l) {
+    const LayerW& L = c->layers[l];
+    uint16_t* kvl = c->kv + (use_cache_layers ? (size_t)c->lay.layer_stride * l : 0);
+    if (llama) HIPCHK(rl_norm(c->x, nullptr, rows, d, m.norm_eps, L.n1g, nullptr, c->n1, nullptr, nullptr, nullptr, st));
+    else HIPCHK(rl_norm(c->x, nullptr, rows, d, m.norm_eps, L.n1g, L.n1b, c->n1, L.n2g, L.n2b, c->n2, st));
+    GemmArgs g{};
+    g.A = c->n1; g.lda = d; g.W = L.wqkv; g.ldw = d; g.M = rows; g.N = nqkv; g.K = d;
+    g.bias = llama ? nullptr : L.bqkv; g.out = c->qkv; g.ldo = nqkv;
+    HIPCHK(rl_gemm(g, EPI_F32, st));
+    RopeArgs r{};
+    r.qkv = c->qkv; r.rows = rows; r.Hq = m.n_q_heads; r.Hkv = m.n_kv_heads; r.h = h; r.r = m.rotary_dim;
+    r.table = c->rope; r.q = c->q; r.kv = kvl; r.lay = c->lay; r.kv_off = c->d_kv_off; r.kv_cap = c->d_kv_cap;
+    if (decode) { r.pos = c->d_ctx_base; r.pos_add = t - 1; r.dst_seq = c->d_iota; r.ncopy = 1; }
+    else { r.pos = c->d_pos; r.pos_add = 0; r.dst_seq = c->d_dst_seq; r.ncopy = ncopy; }
+    HIPCHK(rl_rope_kv(r, st));
+    AttnArgs a{};
+    a.q = c->q; a.q_ld = qd; a.out = c->attn; a.out_ld = qd; a.kv = kvl; a.lay = c->lay;
+    a.kv_off = c->d_kv_off; a.kv_cap = c->d_kv_cap; a.Hq = m.n_q_heads; a.scale = 1.0f / sqrtf((float)h);
+    if (decode) {
+      a.ctx_base = c->d_ctx_base; a.ctx_add = t; a.S = rows;
+      hipEvent_t e0 = nullptr, e1 = nullptr;
+      if (c->profiling) {
+        while (c->prof_events.size() < c->prof_used + 2) {
+          hipEvent_t e;
+          HIPCHK(hipEventCreate(&e));
+          c->prof_events.push_back(e);
+        }
+        e0 = c->prof_events[c->prof_used++];
+        e1 = c->prof_events[c->prof_used++];
+        HIPCHK(hipEventRecord(e0, st));
+      }
+      HIPCHK(rl_attention_decode(a, st));
+      if (e1) HIPCHK(hipEventRecord(e1, st));
+    } else {
+      a.jobs = c->d_jobs; a.njobs = njobs;
+      HIPCHK(rl_attention_prefill(a, st));
+    }
+    g = GemmArgs{};
+    g.A = c->attn; g.lda = qd; g.W = L.wo; g.ldw = qd; g.M = rows; g.N = d; g.K = qd;
+    g.bias = llama ? nullptr : L.bo; g.out = c->x; g.ldo = d;
+    HIPCHK(rl_gemm(g, EPI_RESID, st));
+    if (llama) HIPCHK(rl_norm(c->x, nullptr, rows, d, m.norm_eps, L.n2g, nullptr, c->n2, nullptr, nullptr, nullptr, st));
+    g = GemmArgs{};
+    g.A = c->n2; g.lda = d; g.W = L.wup; g.ldw = d; g.M = rows; g.N = llama ? 2 * F : F; g.K = d;
+    g.bias = llama ? nullptr : L.bup; g.out = c->act; g.ldo = F;
+    HIPCHK(rl_gemm(g, llama ? EPI_SWIGLU_BF16 : EPI_GELU_BF16, st));
+    g = GemmArgs{};
+    g.A = c->act; g.lda = F; g.W = L.wdown; g.ldw = F; g.M = rows; g.N = d; g.K = F;
+    g.bias = llama ? nullptr : L.bdown; g.out = c->x; g.ldo = d;
+    HIPCHK(rl_gemm(g, EPI_RESID, st));
+  }
+  return RLGEN_OK;
+}
+
+// Final norm of selected rows of c->x into c->hfin.
+int final_norm(rlgen_ctx* c, const int* row_index, int rows, uint16_t* out, hipStream_t st) {
+  const rlgen_model_cfg& m = c->cfg;
+  HIPCHK(rl_norm(c->x, row_index, rows, m.d_model, m.norm_eps, c->fng, m.arch == RLGEN_ARCH_LLAMA ? nullptr : c->fnb, out,
+                 nullptr, nullptr, nullptr, st));
+  return RLGEN_OK;
+}
+
+int lm_head_stats(rlgen_ctx* c, const uint16_t* hfin, int rows, float temperature, const int* target, hipStream_t st) {
+  GemmArgs g{};
+  g.A = hfin; g.lda = c->cfg.d_model; g.W = c->lm_head; g.ldw = c->cfg.d_model;
+  g.M = rows; g.N = c->cfg.vocab; g.K = c->cfg.d_model;
+  g.temperature = temperature; g.partial = c->partial; g.target = target; g.target_logit = c->target_logit;
+  HIPCHK(rl_gemm(g, EPI_LMHEAD, st));
+  return RLGEN_OK;
+}
+
+int sample_rows(rlgen_ctx* c, int rows, float temperature, const float* uniforms, const int* forced, int io_stride,
+                int io_add, int* tokens, float* logprobs, int* next_token, hipStream_t st) {
+  int rc = lm_head_stats(c, c->hfin, rows, temperature, nullptr, st);
+  if (rc) return rc;
+  SampleArgs s{};
+  s.partial = c->partial; s.ngroups = c->ngroups; s.hfin = c->hfin; s.d = c->cfg.d_model;
+  s.lm_head = c->lm_head; s.vocab = c->cfg.vocab; s.temperature = temperature;
+  s.uniforms = uniforms; s.forced = forced; s.io_index = nullptr; s.io_stride = io_stride; s.io_add = io_add;
+  s.tokens = tokens; s.logprobs = logprobs; s.next_token = next_token; s.R = rows; s.status = c->status;
+  HIPCHK(rl_sample(s, st));
+  return RLGEN_OK;
+}
+
+// Waits until the previous call's metadata upload has left the staging buffer.
+int stage_begin(rlgen_ctx* c) {
+  if (c->meta_pending) {
+    HIPCHK(hipEventSynchronize(c->ev_meta));
+    c->meta_pending = false;
+  }
+  return RLGEN_OK;
+}
+
+struct Staged {
+  SeqMeta* meta; int *kv_off, *kv_cap, *ctx_base, *iota, *lastrow;
+};
+Staged stage_views(rlgen_ctx* c) {
+  const size_t S = c->cfg.max_seqs;
+  char* p = c->h_stage;
+  Staged s;
+  s.meta = (SeqMeta*)p; p += align_up(S * sizeof(SeqMeta));
+  s.kv_off = (int*)p; p += align_up(S * 4);
+  s.kv_cap = (int*)p; p += align_up(S * 4);
+  s.ctx_base = (int*)p; p += align_up(S * 4);
+  s.iota = (int*)p; p += align_up(S * 4);
+  s.lastrow = (int*)p;
+  return s;
+}
+int stage_upload(rlgen_ctx* c, const Staged& s, int nmeta, int nseq, hipStream_t st) {
+  HIPCHK(hipMemcpyAsync(c->d_meta, s.meta, (size_t)nmeta * sizeof(SeqMeta), hipMemcpyHostToDevice, st));
+  HIPCHK(hipMemcpyAsync(c->d_kv_off, s.kv_off, (size_t)nseq * 4, hipMemcpyHostToDevice, st));
+  HIPCHK(hipMemcpyAsync(c->d_kv_cap, s.kv_cap, (size_t)nseq * 4, hipMemcpyHostToDevice, st));
+  HIPCHK(hipMemcpyAsync(c->d_ctx_base, s.ctx_base, (size_t)nseq * 4, hipMemcpyHostToDevice, st));
+  HIPCHK(hipMemcpyAsync(c->d_iota, s.iota, (size_t)nseq * 4, hipMemcpyHostToDevice, st));
+  HIPCHK(hipMemcpyAsync(c->d_lastrow, s.lastrow, (size_t)nseq * 4, hipMemcpyHostToDevice, st));
+  HIPCHK(hipEventRecord(c->ev_meta, st));
+  c->meta_pending = true;
+  return RLGEN_OK;
+}
+
+int expand(rlgen_ctx* c, const Chunk& ch, const int* tokens, bool scoring, hipStream_t st) {
+  hipLaunchKernelGGL(expand_kernel, dim3(ch.count), dim3(256), 0, st, c->d_meta, ch.first, tokens, c->d_tok_index, c->d_pos,
+                     c->d_dst_seq, c->d_jobs, c->d_lm_row, c->d_target, c->d_out_index, scoring ? 1 : 0);
+  HIPCHK(hipGetLastError());
+  return RLGEN_OK;
+}
+
+// Teacher-forced pass shared by rlgen_score (logits == nullptr) and rlgen_debug_logits.
+int score_impl(rlgen_ctx* c, const int32_t* seqs, const int32_t* seq_lens, const int32_t* score_from, int N, int stride,
+               float temperature, float* out, float* logits, hipStream_t st) {
+  if (!c || !seqs || !seq_lens || (!out && !logits)) return RLGEN_ERR_NULL;
+  const rlgen_model_cfg& m = c->cfg;
+  if (N < 1 || stride < 1) return RLGEN_ERR_BAD_ARG;
+  if (!(temperature > 0.f) || !std::isfinite(temperature)) return RLGEN_ERR_BAD_ARG;
+  if (N > m.max_seqs) return RLGEN_ERR_CAPACITY;
+  for (int n = 0; n < N; ++n) {
+    if (seq_lens[n] < 1 || seq_lens[n] > stride) return RLGEN_ERR_BAD_ARG;
+    if (seq_lens[n] > m.max_seq_len) return RLGEN_ERR_CAPACITY;
+  }
+  int rc = stage_begin(c);
+  if (rc) return rc;
+  Staged s = stage_views(c);
+  std::vector<Chunk> chunks;
+  Chunk cur{0, 0, 0, 0, 0};
+  long long kvtok = 0;
+  for (int n = 0; n < N; ++n) {
+    const int len = seq_lens[n];
+    const int from = logits ? len : std::max(1, score_from ? score_from[n] : 1);
+    const int nlm = logits ? 1 : std::max(0, len - from);
+    if (cur.count && (cur.rows + len > c->R || kvtok + round32(len) > m.max_kv_tokens)) {
+      chunks.push_back(cur);
+      cur = Chunk{n, 0, 0, 0, 0};
+      kvtok = 0;
+    }
+    SeqMeta& e = s.meta[n];
+    e.row0 = cur.rows; e.len = len; e.src_off = n * stride; e.cache_seq = n; e.job0 = cur.jobs;
+    e.lm0 = cur.lm_rows; e.score_from = from; e.out_off = n * stride;
+    s.kv_off[n] = (int)kvtok; s.kv_cap[n] = round32(len);
+    s.ctx_base[n] = len; s.iota[n] = n; s.lastrow[n] = cur.rows + len - 1;
+    kvtok += round32(len);
+    cur.count++; cur.rows += len; cur.jobs += (len + 15) / 16; cur.lm_rows += nlm;
+  }
+  chunks.push_back(cur);
+  rc = stage_upload(c, s, N, N, st);
+  if (rc) return rc;
+  if (c->timed) HIPCHK(hipEventRecord(c->ev_start, st));
+  if (!logits) {
+    hipLaunchKernelGGL(fill_f32_kernel, dim3(std::min<size_t>(((size_t)N * stride + 255) / 256, 65536)), dim3(256), 0, st, out,
+                       (size_t)N * stride, 0.f);
+    HIPCHK(hipGetLastError());
+  }
+  for (const Chunk& ch : chunks) {
+    rc = expand(c, ch, seqs, !logits, st);
+    if (rc) return rc;
+    HIPCHK(rl_embed(c->x, c->embed, seqs, c->d_tok_index, ch.rows, m.d_model, m.vocab, c->status, st));
+    rc = run_layers(c, ch.rows, false, 0, 1, false, ch.jobs, st);
+    if (rc) return rc;
+    if (logits) {
+      rc = final_norm(c, c->d_lastrow + ch.first, ch.count, c->hfin, st);
+      if (rc) return rc;
+      GemmArgs g{};
+      g.A = c->hfin; g.lda = m.d_model; g.W = c->lm_head; g.ldw = m.d_model; g.M = ch.count; g.N = m.vocab; g.K = m.d_model;
+      g.out = logits + (size_t)ch.first * m.vocab; g.ldo = m.vocab;
+      HIPCHK(rl_gemm(g, EPI_F32, st));
+    } else {
+      if (ch.lm_rows > 0) {
+        hipLaunchKernelGGL(clamp_targets_kernel, dim3((ch.lm_rows + 255) / 256), dim3(256), 0, st, c->d_target, ch.lm_rows,
+                           m.vocab, c->status);
+        HIPCHK(hipGetLastError());
+      }
+      for (int r0 = 0; r0 < ch.lm_rows; r0 += c->LM) {
+        const int nr = std::min(c->LM, ch.lm_rows - r0);
+        rc = final_norm(c, c->d_lm_row + r0, nr, c->hfin, st);
+        if (rc) return rc;
+        rc = lm_head_stats(c, c->hfin, nr, temperature, c->d_target + r0, st);
+        if (rc) return rc;
+        HIPCHK(rl_score_finalize(c->partial, c->ngroups, c->target_logit, c->d_out_index + r0, out, nr, st));
+      }
+    }
+  }
+  if (c->timed) {
+    HIPCHK(hipEventRecord(c->ev_mid, st));
+    HIPCHK(hipEventRecord(c->ev_end, st));
+  }
+  return RLGEN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t rlgen_workspace_bytes(const rlgen_model_cfg* cfg) {
+  if (check_cfg(cfg) != RLGEN_OK) return 0;
+  rlgen_ctx tmp{};
+  tmp.cfg = *cfg;
+  return carve(&tmp, nullptr);
+}
+
+int rlgen_create(const rlgen_model_cfg* cfg, const rlgen_weights* weights, void* workspace, size_t workspace_bytes,
+                 void* hip_stream, rlgen_ctx** out) {
+  if (!cfg || !weights || !workspace || !out) return RLGEN_ERR_NULL;
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  rlgen_ctx* c = new (std::nothrow) rlgen_ctx{};
+  if (!c) return RLGEN_ERR_DEVICE;
+  c->cfg = *cfg;
+  c->need = carve(c, nullptr);
+  if (workspace_bytes < c->need || ((uintptr_t)workspace) % ALIGN != 0) {
+    delete c;
+    return RLGEN_ERR_WORKSPACE;
+  }
+  c->ws = (char*)workspace;
+  carve(c, c->ws);
+  hipStream_t st = (hipStream_t)hip_stream;
+  const size_t S = cfg->max_seqs;
+  c->stage_bytes = align_up(S * sizeof(SeqMeta)) + 5 * align_up(S * 4);
+  auto fail = [&](int code) {
+    rlgen_destroy(c);
+    return code;
+  };
+  if (hipHostMalloc((void**)&c->h_stage, c->stage_bytes, hipHostMallocDefault) != hipSuccess) return fail(RLGEN_ERR_DEVICE);
+  if (hipEventCreateWithFlags(&c->ev_meta, hipEventDisableTiming) != hipSuccess) return fail(RLGEN_ERR_DEVICE);
+  if (hipEventCreate(&c->ev_start) != hipSuccess || hipEventCreate(&c->ev_mid) != hipSuccess ||
+      hipEventCreate(&c->ev_end) != hipSuccess)
+    return fail(RLGEN_ERR_DEVICE);
+  c->timed = true;
+  rc = pack_weights(c, weights, st);
+  if (rc) return fail(rc);
+  if (rl_fill_zero(c->status, 256, st) != hipSuccess) return fail(RLGEN_ERR_DEVICE);
+  if (rl_rope_table(c->rope, cfg->max_seq_len, cfg->rotary_dim, cfg->rope_theta, st) != hipSuccess) return fail(RLGEN_ERR_DEVICE);
+  // The cache must hold finite values everywhere: a partly filled super-block is read whole and the
+  // unused keys are masked to probability zero, which only cancels finite values.
+  if (rl_fill_zero(c->kv, (size_t)c->lay.layer_stride * cfg->n_layers * 2, st) != hipSuccess) return fail(RLGEN_ERR_DEVICE);
+  *out = c;
+  return RLGEN_OK;
+}
+
+int rlgen_update_weights(rlgen_ctx* ctx, const rlgen_weights* weights, void* hip_stream) {
+  if (!ctx || !weights) return RLGEN_ERR_NULL;
+  return pack_weights(ctx, weights, (hipStream_t)hip_stream);
+}
+
+int rlgen_generate(rlgen_ctx* c, const int32_t* prompts, const int32_t* prompt_lens, int32_t B, int32_t prompt_stride,
+                   int32_t k, int32_t max_new, float temperature, const float* uniforms, const int32_t* forced,
+                   int32_t* tokens, float* token_logprobs, void* hip_stream) {
+  if (!c || !prompts || !prompt_lens || !uniforms || !tokens || !token_logprobs) return RLGEN_ERR_NULL;
+  const rlgen_model_cfg& m = c->cfg;
+  if (B < 1 || k < 1 || max_new < 1 || prompt_stride < 1) return RLGEN_ERR_BAD_ARG;
+  if (!(temperature > 0.f) || !std::isfinite(temperature)) return RLGEN_ERR_BAD_ARG;
+  if ((long long)B * k > m.max_seqs) return RLGEN_ERR_CAPACITY;
+  long long kvtok = 0;
+  for (int b = 0; b < B; ++b) {
+    if (prompt_lens[b] < 1 || prompt_lens[b] > prompt_stride) return RLGEN_ERR_BAD_ARG;
+    if ((long long)prompt_lens[b] + max_new > m.max_seq_len) return RLGEN_ERR_CAPACITY;
+    kvtok += (long long)k * round32(prompt_lens[b] + max_new);
+  }
+  if (kvtok > m.max_kv_tokens) return RLGEN_ERR_CAPACITY;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int S = B * k;
+  int rc = stage_begin(c);
+  if (rc) return rc;
+  Staged s = stage_views(c);
+  std::vector<Chunk> chunks;
+  Chunk cur{0, 0, 0, 0, 0};
+  long long off = 0;
+  for (int b = 0; b < B; ++b) {
+    const int len = prompt_lens[b];
+    if (cur.count && cur.rows + len > c->R) {
+      chunks.push_back(cur);
+      cur = Chunk{b, 0, 0, 0, 0};
+    }
+    SeqMeta& e = s.meta[b];
+    e.row0 = cur.rows; e.len = len; e.src_off = b * prompt_stride; e.cache_seq = b * k; e.job0 = cur.jobs;
+    e.lm0 = 0; e.score_from = len; e.out_off = 0;
+    for (int j = 0; j < k; ++j) {
+      const int q = b * k + j;
+      s.kv_off[q] = (int)off; s.kv_cap[q] = round32(len + max_new);
+      s.ctx_base[q] = len; s.iota[q] = q; s.lastrow[q] = cur.rows + len - 1;
+      off += round32(len + max_new);
+    }
+    cur.count++; cur.rows += len; cur.jobs += (len + 15) / 16;
+  }
+  chunks.push_back(cur);
+  rc = stage_upload(c, s, B, S, st);
+  if (rc) return rc;
+  c->prof_used = 0;
+  if (c->timed) HIPCHK(hipEventRecord(c->ev_start, st));
+  // prompt pass: once per prompt; keys and values go to all k sequences of the prompt
+  for (const Chunk& ch : chunks) {
+    rc = expand(c, ch, prompts, false, st);
+    if (rc) return rc;
+    HIPCHK(rl_embed(c->x, c->embed, prompts, c->d_tok_index, ch.rows, m.d_model, m.vocab, c->status, st));
+    rc = run_layers(c, ch.rows, false, 0, k, true, ch.jobs, st);
+    if (rc) return rc;
+    rc = final_norm(c, c->d_lastrow + ch.first * k, ch.count * k, c->hfin + (size_t)ch.first * k * m.d_model, st);
+    if (rc) return rc;
+  }
+  if (c->timed) HIPCHK(hipEventRecord(c->ev_mid, st));
+  rc = sample_rows(c, S, temperature, uniforms, forced, max_new, 0, tokens, token_logprobs, c->d_next_token, st);
+  if (rc) return rc;
+  for (int t = 1; t < max_new; ++t) {
+    HIPCHK(rl_embed(c->x, c->embed, c->d_next_token, nullptr, S, m.d_model, m.vocab, c->status, st));
+    rc = run_layers(c, S, true, t, 1, true, 0, st);
+    if (rc) return rc;
+    rc = final_norm(c, nullptr, S, c->hfin, st);
+    if (rc) return rc;
+    rc = sample_rows(c, S, temperature, uniforms, forced, max_new, t, tokens, token_logprobs, c->d_next_token, st);
+    if (rc) return rc;
+  }
+  if (c->timed) HIPCHK(hipEventRecord(c->ev_end, st));
+  return RLGEN_OK;
+}
+
+int rlgen_score(rlgen_ctx* ctx, const int32_t* seqs, const int32_t* seq_lens, const int32_t* score_from, int32_t N,
+                int32_t stride, float temperature, float* token_logprobs, void* hip_stream) {
+  if (!ctx || !token_logprobs) return RLGEN_ERR_NULL;
+  return score_impl(ctx, seqs, seq_lens, score_from, N, stride, temperature, token_logprobs, nullptr, (hipStream_t)hip_stream);
+}
+
+int rlgen_debug_logits(rlgen_ctx* ctx, const int32_t* seqs, const int32_t* seq_lens, int32_t N, int32_t stride, float* logits,
+                       void* hip_stream) {
+  if (!ctx || !logits) return RLGEN_ERR_NULL;
+  return score_impl(ctx, seqs, seq_lens, nullptr, N, stride, 1.0f, nullptr, logits, (hipStream_t)hip_stream);
+}
+
+int rlgen_debug_sample(rlgen_ctx* c, const float* hidden, int32_t R, float temperature, const float* uniforms,
+                       const int32_t* forced, int32_t* tokens, float* token_logprobs, void* hip_stream) {
+  if (!c || !hidden || !uniforms || !tokens || !token_logprobs) return RLGEN_ERR_NULL;
+  if (R < 1) return RLGEN_ERR_BAD_ARG;
+  if (!(temperature > 0.f) || !std::isfinite(temperature)) return RLGEN_ERR_BAD_ARG;
+  if (R > c->LM) return RLGEN_ERR_CAPACITY;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const rlgen_model_cfg& m = c->cfg;
+  HIPCHK(rl_norm(hidden, nullptr, R, m.d_model, m.norm_eps, c->fng, m.arch == RLGEN_ARCH_LLAMA ? nullptr : c->fnb, c->hfin,
+                 nullptr, nullptr, nullptr, st));
+  return sample_rows(c, R, temperature, uniforms, forced, 1, 0, tokens, token_logprobs, nullptr, st);
+}
+
+int rlgen_sequence_logprob(const float* token_logprobs, const int32_t* from, const int32_t* lens, int32_t N, int32_t stride,
+                           float* seq_logprob, void* hip_stream) {
+  if (!token_logprobs || !from || !lens || !seq_logprob) return RLGEN_ERR_NULL;
+  if (N < 1 || stride < 1) return RLGEN_ERR_BAD_ARG;
+  HIPCHK(rl_sequence_logprob(token_logprobs, from, lens, N, stride, seq_logprob, (hipStream_t)hip_stream));
+  return RLGEN_OK;
+}
+
+int rlgen_dpo_loss(const float* pol_pos, const float* ref_pos, const float* pol_neg, const float* ref_neg, int32_t P, float beta,
+                   float* loss, void* hip_stream) {
+  if (!pol_pos || !ref_pos || !pol_neg || !ref_neg || !loss) return RLGEN_ERR_NULL;
+  if (P < 1 || !std::isfinite(beta)) return RLGEN_ERR_BAD_ARG;
+  HIPCHK(rl_dpo_loss(pol_pos, ref_pos, pol_neg, ref_neg, P, beta, loss, (hipStream_t)hip_stream));
+  return RLGEN_OK;
+}
+
+int rlgen_get_timings(rlgen_ctx* c, float* prefill_ms, float* decode_ms, float* decode_attn_ms, int32_t* decode_attn_launches) {
+  if (!c) return RLGEN_ERR_NULL;
+  HIPCHK(hipEventSynchronize(c->ev_end));
+  float a = 0.f, b = 0.f;
+  HIPCHK(hipEventElapsedTime(&a, c->ev_start, c->ev_mid));
+  HIPCHK(hipEventElapsedTime(&b, c->ev_mid, c->ev_end));
+  if (prefill_ms) *prefill_ms = a;
+  if (decode_ms) *decode_ms = b;
+  float tot = 0.f;
+  for (size_t i = 0; i + 1 < c->prof_used; i += 2) {
+    float t = 0.f;
+    HIPCHK(hipEventElapsedTime(&t, c->prof_events[i], c->prof_events[i + 1]));
+    tot += t;
+  }
+  if (decode_attn_ms) *decode_attn_ms = tot;
+  if (decode_attn_launches) *decode_attn_launches = (int32_t)(c->prof_used / 2);
+  return RLGEN_OK;
+}
+
+int rlgen_set_profiling(rlgen_ctx* c, int32_t on) {
+  if (!c) return RLGEN_ERR_NULL;
+  c->profiling = on != 0;
+  if (!on) c->prof_used = 0;
+  return RLGEN_OK;
+}
+
+int rlgen_status(rlgen_ctx* c, void* hip_stream) {
+  if (!c) return RLGEN_ERR_NULL;
+  unsigned v = 0;
+  HIPCHK(hipMemcpyAsync(&v, c->status, sizeof(v), hipMemcpyDeviceToHost, (hipStream_t)hip_stream));
+  HIPCHK(hipStreamSynchronize((hipStream_t)hip_stream));
+  return v ? RLGEN_ERR_DEVICE : RLGEN_OK;
+}
+
+const char* rlgen_strerror(int code) {
+  switch (code) {
+    case RLGEN_OK: return "ok";
+    case RLGEN_ERR_NULL: return "a required pointer is null";
+    case RLGEN_ERR_BAD_CFG: return "inconsistent or unsupported model configuration";
+    case RLGEN_ERR_BAD_ARG: return "argument out of its domain";
+    case RLGEN_ERR_CAPACITY: return "call exceeds the capacity the context was created with";
+    case RLGEN_ERR_WORKSPACE: return "workspace too small or misaligned";
+    case RLGEN_ERR_UNIMPLEMENTED: return "not implemented";
+    case RLGEN_ERR_DEVICE: return "HIP call failed or a kernel flagged an out-of-range token id or uniform";
+  }
+  return "unknown error code";
+}
+
+void rlgen_destroy(rlgen_ctx* c) {
+  if (!c) return;
+  if (c->ev_meta) {
+    if (c->meta_pending) (void)hipEventSynchronize(c->ev_meta);
+    (void)hipEventDestroy(c->ev_meta);
+  }
+  if (c->ev_start) (void)hipEventDestroy(c->ev_start);
+  if (c->ev_mid) (void)hipEventDestroy(c->ev_mid);
+  if (c->ev_end) (void)hipEventDestroy(c->ev_end);
+  for (hipEvent_t e : c->prof_events) (void)hipEventDestroy(e);
+  if (c->h_stage) (void)hipHostFree(c->h_stage);
+  delete c;
+}
+
+}  // extern "C"

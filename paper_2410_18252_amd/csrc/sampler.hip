@@ -1,0 +1,147 @@
+// Second phase of the fused LM-head sampler and scorer.  The LM-head GEMM (EPI_LMHEAD) leaves, per
+// row and per group of 64 vocabulary columns, the max and the sum of exp of the tempered logits --
+// never the logits or the probabilities.  Here one wave per row combines them into log Z, walks
+// the group sums in ascending vocabulary order (fp64) to find the group in which the CDF crosses
+// u, recomputes that group's 64 logits (one column per lane) and finishes the scan inside it.
+#include "kernels.h"
+
+namespace {
+
+__device__ __forceinline__ double wave_incl_scan(double v, int lane) {
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const double t = __shfl_up(v, o, WAVE);
+    if (lane >= o) v += t;
+  }
+  return v;
+}
+
+// log Z of one row from its partials; also returns the reference max M.  All lanes get the result.
+__device__ __forceinline__ void row_logz(const float2* p, int ngroups, int lane, float& M, double& Z) {
+  float mx = -INFINITY;
+  for (int g = lane; g < ngroups; g += 64) mx = fmaxf(mx, p[g].x);
+  M = wave_max(mx);
+  double z = 0.0;
+  const int per = (ngroups + 63) / 64;
+  const int g0 = lane * per, g1 = min(g0 + per, ngroups);
+  for (int g = g0; g < g1; ++g) z += (double)(p[g].y * __expf(p[g].x - M));
+  Z = wave_incl_scan(z, lane);   // inclusive prefix; lane 63 holds the total
+}
+
+__global__ __launch_bounds__(256) void sample_kernel(SampleArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= a.R) return;
+  const size_t idx = (size_t)(a.io_index ? a.io_index[row] : row) * a.io_stride + a.io_add;
+  float u = a.uniforms[idx];
+  if (!(u >= 0.f && u < 1.f)) {
+    if (lane == 0) atomicOr(a.status, RLGEN_FAULT_UNIFORM);
+    u = (u >= 1.f) ? 0.99999994f : 0.f;
+  }
+  int forced = a.forced ? a.forced[idx] : -1;
+  if (forced >= a.vocab) {
+    if (lane == 0) atomicOr(a.status, RLGEN_FAULT_TOKEN);
+    forced = a.vocab - 1;
+  }
+  const float2* p = a.partial + (size_t)row * a.ngroups;
+  float M;
+  double incl;
+  row_logz(p, a.ngroups, lane, M, incl);
+  const double Z = __shfl(incl, 63, WAVE);
+  const double logZ = (double)M + log(Z);
+  const double target = (double)u * Z;
+
+  // locate the group: lanes own contiguous runs of groups, in ascending order
+  const int per = (a.ngroups + 63) / 64;
+  const int g0 = lane * per, g1 = min(g0 + per, a.ngroups);
+  double run = incl;
+  {
+    double own = 0.0;
+    for (int g = g0; g < g1; ++g) own += (double)(p[g].y * __expf(p[g].x - M));
+    run = incl - own;   // exclusive prefix of this lane
+  }
+  int gsel = 0x7fffffff;
+  double base = 0.0;
+  {
+    double r = run;
+    for (int g = g0; g < g1; ++g) {
+      const double w = (double)(p[g].y * __expf(p[g].x - M));
+      if (r + w > target && gsel == 0x7fffffff) {
+        gsel = g;
+        base = r;
+      }
+      r += w;
+    }
+  }
+  int gmin = gsel;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) gmin = min(gmin, __shfl_xor(gmin, o, WAVE));
+  if (gmin == 0x7fffffff) gmin = a.ngroups - 1;                 // cannot happen for u < 1; stay in bounds
+  const int owner = min(gmin / per, 63);
+  base = __shfl(gsel == gmin ? base : run, owner, WAVE);
+  if (forced >= 0) gmin = forced >> 6;
+
+  // recompute the 64 tempered logits of group gmin: lane j <-> column 64 gmin + j
+  const int col = gmin * 64 + lane;
+  float logit = -INFINITY;
+  if (col < a.vocab) {
+    const uint16_t* w = a.lm_head + (size_t)col * a.d;
+    const uint16_t* hrow = a.hfin + (size_t)row * a.d;
+    float acc = 0.f;
+    for (int k = 0; k < a.d; k += 8) {
+      const u32x4 wv = *(const u32x4*)(w + k);
+      const u32x4 hv = *(const u32x4*)(hrow + k);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        acc += __uint_as_float(wv[e] << 16) * __uint_as_float(hv[e] << 16);
+        acc += __uint_as_float(wv[e] & 0xffff0000u) * __uint_as_float(hv[e] & 0xffff0000u);
+      }
+    }
+    logit = acc / a.temperature;
+  }
+  int tok;
+  if (forced >= 0) {
+    tok = forced;
+  } else {
+    const double e = (logit == -INFINITY) ? 0.0 : (double)__expf(logit - M);
+    const double cum = base + wave_incl_scan(e, lane);
+    const unsigned long long hit = __ballot(cum > target && e > 0.0);
+    const unsigned long long pos = __ballot(e > 0.0);
+    int j;
+    if (hit) j = __ffsll((long long)hit) - 1;
+    else if (pos) j = 63 - __clzll((long long)pos);   // rounding left the crossing outside: last positive column
+    else j = 0;
+    tok = min(gmin * 64 + j, a.vocab - 1);
+  }
+  const float ltok = __shfl(logit, tok & 63, WAVE);
+  if (lane == 0) {
+    a.tokens[idx] = tok;
+    a.logprobs[idx] = (float)((double)ltok - logZ);
+    if (a.next_token) a.next_token[row] = tok;
+  }
+}
+
+__global__ __launch_bounds__(256) void score_finalize_kernel(const float2* partial, int ngroups, const float* target_logit,
+                                                            const int* out_index, float* out, int R) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= R) return;
+  float M;
+  double incl;
+  row_logz(partial + (size_t)row * ngroups, ngroups, lane, M, incl);
+  if (lane == 63) out[out_index[row]] = (float)((double)target_logit[row] - ((double)M + log(incl)));
+}
+
+}  // namespace
+
+hipError_t rl_sample(const SampleArgs& a, hipStream_t s) {
+  if (a.R <= 0) return hipSuccess;
+  hipLaunchKernelGGL(sample_kernel, dim3((a.R + 3) / 4), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+hipError_t rl_score_finalize(const float2* partial, int ngroups, const float* target_logit, const int* out_index,
+                             float* out, int R, hipStream_t s) {
+  if (R <= 0) return hipSuccess;
+  hipLaunchKernelGGL(score_finalize_kernel, dim3((R + 3) / 4), dim3(256), 0, s, partial, ngroups, target_logit, out_index, out, R);
+  return hipGetLastError();
+}

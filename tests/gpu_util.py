@@ -1,0 +1,78 @@
+"""Glue for the GPU parity tests: builds a library context from seeded workload weights and runs
+the oracle on the same inputs."""
+import numpy as np
+import torch
+
+from oracle import decoder as O
+from workloads import ModelShape, Weights, make_weights
+from workloads.configs import ARCH_LLAMA, ARCH_NEOX
+
+TOL_LOGITS = 2e-2     # max-abs on raw logits (bf16 weights and GEMM inputs, fp32 accumulation)
+TOL_LOGPROB = 1e-2    # max-abs on token log-probs
+MARGIN = 1e-3         # tokens must agree wherever the oracle's CDF margin exceeds this
+
+
+def R():
+    import paper_2410_18252_amd.rlgen as R_
+    return R_
+
+
+GPU_SHAPES = {
+    "neox-h16-raggedV": ModelShape(ARCH_NEOX, 2, 64, 4, 4, 16, 128, 200, rotary_dim=4),
+    "neox-h80": ModelShape(ARCH_NEOX, 2, 160, 2, 2, 80, 320, 321, rotary_dim=20),
+    "neox-h256": ModelShape(ARCH_NEOX, 1, 256, 1, 1, 256, 256, 130, rotary_dim=64),
+    "llama-gqa4-h16": ModelShape(ARCH_LLAMA, 2, 128, 8, 2, 16, 96, 500, rotary_dim=16, rope_theta=500000.0),
+    "llama-gqa2-h128": ModelShape(ARCH_LLAMA, 2, 256, 2, 1, 128, 64, 64, rotary_dim=128, rope_theta=500000.0),
+}
+
+
+def scaled_bf16_weights(shape, seed=21, scale=5.0, lm_head_scale=1.0) -> Weights:
+    """Small models get weights scaled up (so that logits are O(1)) and rounded to bf16, so that the
+    oracle and the GPU see identical values."""
+    W = make_weights(shape, seed, bf16=False, lm_head_scale=lm_head_scale)
+    for k in W.tensors:
+        if not k.endswith("_g"):
+            W.tensors[k] = W.tensors[k] * np.float32(scale)
+    return W.rounded_to_bf16()
+
+
+def make_policy(W: Weights, *, max_seqs, max_seq_len, max_kv_tokens=None, max_batch_tokens=0):
+    r = R()
+    if max_kv_tokens is None:
+        max_kv_tokens = max_seqs * ((max_seq_len + 31) // 32 * 32)
+    dev = r.upload_weights(W.tensors)
+    cfg = r.make_cfg(W.model, weight_dtype=r.DTYPE_BF16 if W.is_bf16 else r.DTYPE_F32, max_seqs=max_seqs,
+                     max_seq_len=max_seq_len, max_kv_tokens=max_kv_tokens, max_batch_tokens=max_batch_tokens)
+    return r.Policy(cfg, dev)
+
+
+def dev_i32(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
+
+
+def dev_f32(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+
+
+def padded(seqs, pad=-1):
+    lens = np.array([len(s) for s in seqs], np.int32)
+    arr = np.full((len(seqs), int(lens.max())), pad, np.int32)
+    for i, s in enumerate(seqs):
+        arr[i, :len(s)] = s
+    return arr, lens
+
+
+def oracle_generate_batch(dec, prompts, lens, k, max_new, T, uniforms, forced=None, with_buckets=False):
+    B = len(lens)
+    toks = np.zeros((B, k, max_new), np.int32)
+    lps = np.zeros((B, k, max_new), np.float32)
+    margins = np.zeros((B, k, max_new))
+    buckets = np.zeros((B, k, max_new, 2)) if with_buckets else None
+    zfin = []
+    for b in range(B):
+        t, l, m, z = O.generate(dec, prompts[b, :lens[b]], k, max_new, T, uniforms[b],
+                                None if forced is None else forced[b], return_final_logits=True,
+                                buckets=None if buckets is None else buckets[b])
+        toks[b], lps[b], margins[b] = t, l, m
+        zfin.append(z)
+    return toks, lps, margins, np.stack(zfin), buckets

@@ -1,0 +1,279 @@
+"""GPU parity: every entry point of librlgen.so against the CPU oracle, element by element, on the
+same seeded inputs.  Tolerances: raw logits 2e-2 max-abs, token log-probs 1e-2 max-abs, tokens
+identical wherever the oracle's CDF margin exceeds 1e-3 (the oracle's token forced elsewhere)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import decoder as O
+from workloads import get_config, make_prompts, make_uniforms, make_weights, Weights
+from gpu_util import (GPU_SHAPES, MARGIN, TOL_LOGITS, TOL_LOGPROB, R, dev_f32, dev_i32, make_policy,
+                      oracle_generate_batch, padded, scaled_bf16_weights)
+
+pytestmark = pytest.mark.gpu
+
+
+def rand_seqs(rng, vocab, lens):
+    return [rng.integers(0, vocab, size=n) for n in lens]
+
+
+@pytest.fixture(scope="module", params=list(GPU_SHAPES))
+def small(request):
+    m = GPU_SHAPES[request.param]
+    W = scaled_bf16_weights(m)
+    # max_batch_tokens == max_seq_len forces several chunks in prefill and scoring
+    pol = make_policy(W, max_seqs=12, max_seq_len=80, max_batch_tokens=80)
+    yield m, W, O.Decoder(W, m), pol
+    pol.close()
+
+
+def test_logits_match_oracle(small):
+    m, W, dec, pol = small
+    rng = np.random.default_rng(31)
+    seqs = rand_seqs(rng, m.vocab, [1, 2, 16, 17, 31, 32, 33, 64, 65, 80, 47, 5])
+    arr, lens = padded(seqs, pad=10 ** 6)          # pad cells hold an out-of-range id: never read
+    got = R().rlgen_debug_logits(pol, dev_i32(arr), lens).cpu().numpy()
+    ref = np.stack([O.last_logits(dec, s) for s in seqs])
+    assert np.abs(ref).max() > 0.3
+    assert np.abs(got - ref).max() < TOL_LOGITS
+    assert R().rlgen_status(pol) == 0
+
+
+def test_score_matches_oracle(small):
+    m, W, dec, pol = small
+    rng = np.random.default_rng(32)
+    seqs = rand_seqs(rng, m.vocab, [80, 3, 33, 64, 1, 2, 70])
+    arr, lens = padded(seqs, pad=-5)
+    score_from = np.array([40, 1, 0, 60, 1, 1, 69], np.int32)
+    for sf in (None, score_from):
+        got = R().rlgen_score(pol, dev_i32(arr), lens, 0.7, sf).cpu().numpy()
+        for i, s in enumerate(seqs):
+            ref = O.score(dec, s, 0.7, 1 if sf is None else sf[i])
+            assert np.abs(got[i, :len(s)] - ref).max() < TOL_LOGPROB, (i, sf is None)
+            assert (got[i, len(s):] == 0).all()
+            lo = max(1, 1 if sf is None else sf[i])
+            assert (got[i, :lo] == 0).all()
+    assert R().rlgen_status(pol) == 0
+
+
+def test_generate_matches_oracle(small):
+    m, W, dec, pol = small
+    rng = np.random.default_rng(33)
+    B, k, T, temp = 5, 2, 9, 0.7
+    prompts = rand_seqs(rng, m.vocab, [30, 1, 33, 64, 71])
+    arr, lens = padded(prompts, pad=-1)
+    u = rng.random((B, k, T), dtype=np.float32)
+    u[0, 1] = u[0, 0]                                   # equal uniforms -> equal samples
+    r = R()
+    # (1) the literal rule: oracle first, force its token where the margin is small, compare the rest
+    t_o, l_o, margins, z_o, _ = oracle_generate_batch(dec, arr, lens, k, T, temp, u)
+    forced = np.where(margins > MARGIN, -1, t_o).astype(np.int32)
+    t_g, l_g = r.rlgen_generate(pol, dev_i32(arr), lens, k, T, temp, dev_f32(u), dev_i32(forced))
+    t_g, l_g = t_g.cpu().numpy(), l_g.cpu().numpy()
+    np.testing.assert_array_equal(t_g, t_o)
+    assert np.abs(l_g - l_o).max() < TOL_LOGPROB
+    assert (forced < 0).mean() > 0.2                    # the comparison of free tokens is not vacuous
+    # (2) unforced run: the GPU's token must be a valid draw under the oracle's CDF along the GPU's own path
+    t_f, l_f = r.rlgen_generate(pol, dev_i32(arr), lens, k, T, temp, dev_f32(u))
+    t_f, l_f = t_f.cpu().numpy(), l_f.cpu().numpy()
+    _, l_t, _, z_t, buckets = oracle_generate_batch(dec, arr, lens, k, T, temp, u, forced=t_f, with_buckets=True)
+    assert (buckets[..., 0] - MARGIN <= u).all() and (u <= buckets[..., 1] + MARGIN).all()
+    assert np.abs(l_f - l_t).max() < TOL_LOGPROB
+    np.testing.assert_array_equal(t_f[0, 0], t_f[0, 1])
+    # (3) logits after the last generated token, through the prompt-pass kernels
+    full = [np.concatenate([prompts[b], t_f[b, j]]) for b in range(B) for j in range(k)]
+    farr, flens = padded(full)
+    z_g = r.rlgen_debug_logits(pol, dev_i32(farr), flens).cpu().numpy()
+    assert np.abs(z_g - z_t.reshape(B * k, -1)).max() < TOL_LOGITS
+    # (4) scoring the generated sequences reproduces generate's log-probs (prefill kernels vs decode kernels)
+    sc = r.rlgen_score(pol, dev_i32(farr), flens, temp, np.repeat(lens, k)).cpu().numpy()
+    for i in range(B * k):
+        P = flens[i] - T
+        assert np.abs(sc[i, P:flens[i]] - l_f.reshape(B * k, T)[i]).max() < TOL_LOGPROB
+    # (5) bit-for-bit determinism
+    t_2, l_2 = r.rlgen_generate(pol, dev_i32(arr), lens, k, T, temp, dev_f32(u))
+    assert torch.equal(t_2.cpu(), torch.from_numpy(t_f)) and torch.equal(l_2.cpu(), torch.from_numpy(l_f))
+    assert r.rlgen_status(pol) == 0
+
+
+def test_batch_composition_does_not_change_a_sequence(small):
+    m, W, dec, pol = small
+    rng = np.random.default_rng(34)
+    prompts = rand_seqs(rng, m.vocab, [20, 45, 7, 64])
+    u = rng.random((4, 2, 6), dtype=np.float32)
+    r = R()
+    arr, lens = padded(prompts, pad=-1)
+    ta, la = r.rlgen_generate(pol, dev_i32(arr), lens, 2, 6, 0.7, dev_f32(u))
+    order = [2, 0, 3, 1]
+    arr2, lens2 = padded([prompts[i] for i in order], pad=10 ** 7)
+    tb, lb = r.rlgen_generate(pol, dev_i32(arr2), lens2, 2, 6, 0.7, dev_f32(u[order]))
+    assert torch.equal(ta[order], tb) and torch.equal(la[order], lb)
+    arr3, lens3 = padded([prompts[1]])
+    tc, lc = r.rlgen_generate(pol, dev_i32(arr3), lens3, 2, 6, 0.7, dev_f32(u[1:2]))
+    assert torch.equal(ta[1:2], tc) and torch.equal(la[1:2], lc)
+
+
+def test_sampler_exact_on_all_zero_model():
+    """Every logit is exactly 0 on both sides: token = floor(u V) and log-prob = -ln V test the group
+    search, the in-group scan and the ragged last group without any rounding slack."""
+    for name in ("neox-h16-raggedV", "llama-gqa4-h16"):
+        m = GPU_SHAPES[name]
+        W = make_weights(m, 1, bf16=False)
+        W = Weights(m, {k: np.zeros_like(v) for k, v in W.tensors.items()}, False)
+        pol = make_policy(W, max_seqs=64, max_seq_len=40)
+        rng = np.random.default_rng(35)
+        u = rng.random((32, 2, 4), dtype=np.float32)
+        u[0, 0, :] = [0.0, 0.99999994, 0.5, 63.5 / m.vocab]
+        keep = np.abs(u.astype(np.float64) * m.vocab - np.round(u.astype(np.float64) * m.vocab)) > 1e-3
+        prompts = np.zeros((32, 3), np.int32)
+        t, l = R().rlgen_generate(pol, dev_i32(prompts), np.full(32, 3), 2, 4, 0.7, dev_f32(u))
+        t, l = t.cpu().numpy(), l.cpu().numpy()
+        want = np.floor(u.astype(np.float64) * m.vocab).astype(np.int32)
+        np.testing.assert_array_equal(t[keep], want[keep])
+        assert np.abs(l + math.log(m.vocab)).max() < 1e-5
+        pol.close()
+
+
+@pytest.mark.parametrize("peak", [1.0, 8.0])
+def test_sampler_in_isolation_on_exact_logits(peak):
+    """With final-norm gain 0 and a one-hot final-norm bias the LM-head input is exactly e_j, so the
+    logits are exactly column j of the bf16 LM head on both sides: any token mismatch outside a 1e-6
+    margin is the sampler's fault.  peak > 1 scales the LM head so that few tokens carry the mass."""
+    m = GPU_SHAPES["neox-h80"]
+    W = scaled_bf16_weights(m, seed=36, scale=5.0 * 6, lm_head_scale=peak)
+    t = dict(W.tensors)
+    from workloads import f32_to_bf16_bits
+    g = np.zeros(m.d_model, np.float32)
+    b = np.zeros(m.d_model, np.float32)
+    b[7] = 1.0
+    t["final_norm_g"], t["final_norm_b"] = f32_to_bf16_bits(g), f32_to_bf16_bits(b)
+    W = Weights(m, t, True)
+    dec = O.Decoder(W, m)
+    pol = make_policy(W, max_seqs=512, max_seq_len=40, max_batch_tokens=512)
+    rng = np.random.default_rng(37)
+    Rr = 400
+    hidden = rng.normal(size=(Rr, m.d_model)).astype(np.float32)
+    u = rng.random(Rr, dtype=np.float32)
+    tok, lp = R().rlgen_debug_sample(pol, dev_f32(hidden), 0.7, dev_f32(u))
+    tok, lp = tok.cpu().numpy(), lp.cpu().numpy()
+    z = dec.logits(hidden)
+    np.testing.assert_array_equal(z[0], W.f32("lm_head")[:, 7])
+    logp = O.tempered_log_softmax(z, 0.7)
+    checked = 0
+    for i in range(Rr):
+        want, margin = O.sample_inverse_cdf(logp[i], u[i])
+        if margin > 1e-6:
+            assert tok[i] == want, i
+            checked += 1
+        assert abs(lp[i] - logp[i][tok[i]]) < 1e-5
+    assert checked > 0.95 * Rr
+    # forced tokens: the reported log-prob is that token's
+    forced = rng.integers(0, m.vocab, size=Rr).astype(np.int32)
+    forced[::3] = -1
+    tok2, lp2 = R().rlgen_debug_sample(pol, dev_f32(hidden), 0.7, dev_f32(u), dev_i32(forced))
+    tok2, lp2 = tok2.cpu().numpy(), lp2.cpu().numpy()
+    np.testing.assert_array_equal(tok2[forced >= 0], forced[forced >= 0])
+    np.testing.assert_array_equal(tok2[forced < 0], tok[forced < 0])
+    assert np.abs(lp2 - logp[np.arange(Rr), tok2]).max() < 1e-5
+    pol.close()
+
+
+def test_config1_end_to_end():
+    """Config 1 as specified: fp32 weights (the library rounds them to bf16), 4 prompts x 32 tokens,
+    K = 2, 16 new tokens, temperature 0.7."""
+    w = get_config(1)
+    W = make_weights(w.model, w.seed_weights, w.bf16_weights)
+    arr, lens = make_prompts(w)
+    u = make_uniforms(w)
+    dec = O.Decoder(W, w.model)
+    pol = make_policy(W, max_seqs=w.n_prompts * w.k, max_seq_len=w.prompt_len_hi + w.max_new)
+    r = R()
+    t_o, l_o, margins, z_o, _ = oracle_generate_batch(dec, arr, lens, w.k, w.max_new, w.temperature, u)
+    forced = np.where(margins > MARGIN, -1, t_o).astype(np.int32)
+    t_g, l_g = r.rlgen_generate(pol, dev_i32(arr), lens, w.k, w.max_new, w.temperature, dev_f32(u), dev_i32(forced))
+    np.testing.assert_array_equal(t_g.cpu().numpy(), t_o)
+    assert np.abs(l_g.cpu().numpy() - l_o).max() < TOL_LOGPROB
+    t_f, l_f = r.rlgen_generate(pol, dev_i32(arr), lens, w.k, w.max_new, w.temperature, dev_f32(u))
+    t_f = t_f.cpu().numpy()
+    _, l_t, _, z_t, buckets = oracle_generate_batch(dec, arr, lens, w.k, w.max_new, w.temperature, u, forced=t_f,
+                                                    with_buckets=True)
+    assert (buckets[..., 0] - MARGIN <= u).all() and (u <= buckets[..., 1] + MARGIN).all()
+    assert np.abs(l_f.cpu().numpy() - l_t).max() < TOL_LOGPROB
+    full = [np.concatenate([arr[b, :lens[b]], t_f[b, j]]) for b in range(w.n_prompts) for j in range(w.k)]
+    farr, flens = padded(full)
+    z_g = r.rlgen_debug_logits(pol, dev_i32(farr), flens).cpu().numpy()
+    assert np.abs(z_g - z_t.reshape(len(full), -1)).max() < TOL_LOGITS
+    # the same model with weights pre-rounded to bf16 on the host: separates weight rounding from the rest
+    decb = O.Decoder(W.rounded_to_bf16(), w.model)
+    zb = np.stack([O.last_logits(decb, s) for s in full])
+    assert np.abs(z_g - zb).max() <= np.abs(z_g - z_t.reshape(len(full), -1)).max() + 1e-3
+    pol.close()
+
+
+def test_argument_and_capacity_errors(small):
+    m, W, dec, pol = small
+    r = R()
+    arr, lens = padded([[1, 2, 3], [4, 5]])
+    u = dev_f32(np.zeros((2, 2, 4), np.float32))
+    d = dev_i32(arr)
+
+    def code(fn):
+        with pytest.raises(r.RlgenError) as e:
+            fn()
+        return e.value.code
+
+    assert code(lambda: r.rlgen_generate(pol, d, [3, 0], 2, 4, 0.7, u)) == r.ERR_BAD_ARG
+    assert code(lambda: r.rlgen_generate(pol, d, [3, 4], 2, 4, 0.7, u)) == r.ERR_BAD_ARG          # longer than stride
+    assert code(lambda: r.rlgen_generate(pol, d, lens, 2, 4, 0.0, u)) == r.ERR_BAD_ARG
+    assert code(lambda: r.rlgen_generate(pol, d, lens, 2, 4, float("nan"), u)) == r.ERR_BAD_ARG
+    assert code(lambda: r.rlgen_generate(pol, d, lens, 2, 4, -1.0, u)) == r.ERR_BAD_ARG
+    big_u = dev_f32(np.zeros((2, 2, 78), np.float32))
+    assert code(lambda: r.rlgen_generate(pol, d, lens, 2, 78, 0.7, big_u)) == r.ERR_CAPACITY      # 3 + 78 > 80
+    many_u = dev_f32(np.zeros((2, 7, 4), np.float32))
+    assert code(lambda: r.rlgen_generate(pol, d, lens, 7, 4, 0.7, many_u)) == r.ERR_CAPACITY      # 14 sequences > 12
+    assert code(lambda: r.rlgen_score(pol, d, [3, 0], 0.7)) == r.ERR_BAD_ARG
+    assert code(lambda: r.rlgen_score(pol, d, lens, 0.0)) == r.ERR_BAD_ARG
+    long = dev_i32(np.zeros((1, 81), np.int32))
+    assert code(lambda: r.rlgen_score(pol, long, [81], 0.7)) == r.ERR_CAPACITY
+    assert r.rlgen_status(pol) == 0
+
+
+def test_device_detected_faults_are_sticky_and_in_bounds():
+    m = GPU_SHAPES["neox-h16-raggedV"]
+    W = scaled_bf16_weights(m)
+    pol = make_policy(W, max_seqs=4, max_seq_len=40)
+    r = R()
+    arr, lens = padded([[1, 2, m.vocab + 5], [4, -3, 0]])
+    u = np.full((2, 1, 3), 0.5, np.float32)
+    t, l = r.rlgen_generate(pol, dev_i32(arr), lens, 1, 3, 0.7, dev_f32(u))
+    assert r.rlgen_status(pol) == r.ERR_DEVICE
+    t = t.cpu().numpy()
+    assert ((0 <= t) & (t < m.vocab)).all() and np.isfinite(l.cpu().numpy()).all()
+    pol.close()
+    pol = make_policy(W, max_seqs=4, max_seq_len=40)
+    assert r.rlgen_status(pol) == 0
+    u[0, 0, 1] = 1.0
+    t, l = r.rlgen_generate(pol, dev_i32(np.array([[1, 2]], np.int32)), [2], 1, 3, 0.7, dev_f32(u[:1]))
+    assert r.rlgen_status(pol) == r.ERR_DEVICE
+    assert ((0 <= t.cpu().numpy()) & (t.cpu().numpy() < m.vocab)).all()
+    pol.close()
+
+
+def test_dpo_loss_and_sequence_logprob_match_oracle():
+    rng = np.random.default_rng(38)
+    r = R()
+    N, stride = 37, 50
+    tlp = -rng.random((N, stride)).astype(np.float32) * 5
+    lens = rng.integers(1, stride + 1, size=N).astype(np.int32)
+    start = np.minimum(rng.integers(0, stride, size=N), lens).astype(np.int32)
+    got = r.rlgen_sequence_logprob(dev_f32(tlp), dev_i32(start), dev_i32(lens)).cpu().numpy()
+    ref = np.array([O.sequence_logprob(tlp[i], start[i], lens[i]) for i in range(N)])
+    assert np.abs(got - ref).max() < 1e-4
+    P = 101
+    a, b, c, d = (-(rng.random(P) * 200).astype(np.float32) for _ in range(4))
+    for beta in (0.1, 0.05, 0.03):
+        got = r.rlgen_dpo_loss(dev_f32(a), dev_f32(b), dev_f32(c), dev_f32(d), beta).cpu().numpy()
+        ref = O.dpo_pair_loss(a.astype(np.float64), b.astype(np.float64), c.astype(np.float64), d.astype(np.float64), beta)
+        assert np.abs(got - ref).max() < 1e-5 * max(1.0, np.abs(ref).max())
