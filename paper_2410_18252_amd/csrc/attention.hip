@@ -6,6 +6,8 @@
 // memory: no LDS, no cross-lane reduction over head_dim.
 //   S^T[key, col] = sum_d K[key, d] q[col, d]       2 x ceil(h/32) MFMA 16x16x32 per super-block
 //   O^T[d, col]  += sum_key V^T[d, key] P^T[key, col]   h/16 MFMA 16x16x32 per super-block
+// K and V are stored as bf16 and widened to fp16 in registers (exact for every value in fp16's
+// normal range); queries, probabilities and the MFMAs are fp16 with fp32 accumulation.
 // The cache layout (see KvLayout) makes every operand fragment one 16-byte load per lane and every
 // load instruction one contiguous kilobyte per wave.  The K rows of a super-block are assigned to
 // MFMA rows so that the score registers of lane group g (keys 8g..8g+7) are exactly the B-operand
@@ -57,16 +59,16 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a) {
   const uint16_t* __restrict__ vst = a.kv + a.lay.v_stream(off, cap, kvh);
 
   // query fragments (B operand): lane (c, g) holds q[col c][32 i + 8 g .. + 7]
-  bf16x8 qf[KSTEPS];
+  f16x8 qf[KSTEPS];
   {
     const uint16_t* qp = a.q + (size_t)qrow * a.q_ld + qhead * HD;
 #pragma unroll
     for (int i = 0; i < KSTEPS; ++i) {
       const int d0 = 32 * i + 8 * g;
-      if (d0 < HD) qf[i] = *(const bf16x8*)(qp + d0);
+      if (d0 < HD) qf[i] = *(const f16x8*)(qp + d0);
       else
 #pragma unroll
-        for (int e = 0; e < 8; ++e) qf[i][e] = (bf16_t)0.f;
+        for (int e = 0; e < 8; ++e) qf[i][e] = (f16_t)0.f;
     }
   }
 
@@ -79,26 +81,24 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a) {
   for (int sb = 0; sb < nsb; ++sb) {
     const uint16_t* kb = kst + (size_t)sb * 32 * HD;
     const uint16_t* vb = vst + (size_t)sb * 32 * HD;
-    bf16x8 kf[2][KSTEPS], vf[VT];
+    u32x4 kraw[2][KSTEPS], vraw[VT];
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int i = 0; i < KSTEPS; ++i) {
         const int chunk = 4 * i + g;
-        if (chunk < NCH) kf[t][i] = *(const bf16x8*)(kb + (((t * NCH + chunk) * 16 + c) << 3));
-        else
-#pragma unroll
-          for (int e = 0; e < 8; ++e) kf[t][i][e] = (bf16_t)0.f;
+        kraw[t][i] = chunk < NCH ? *(const u32x4*)(kb + (((t * NCH + chunk) * 16 + c) << 3)) : u32x4{0, 0, 0, 0};
       }
 #pragma unroll
-    for (int t = 0; t < VT; ++t) vf[t] = *(const bf16x8*)(vb + ((((t * 4 + g) * 16) + c) << 3));
+    for (int t = 0; t < VT; ++t) vraw[t] = *(const u32x4*)(vb + ((((t * 4 + g) * 16) + c) << 3));
 
     f32x4 sc[2];
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       sc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int i = 0; i < KSTEPS; ++i) sc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[t][i], qf[i], sc[t], 0, 0, 0);
+      for (int i = 0; i < KSTEPS; ++i)
+        sc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(bf16x8_to_f16x8(kraw[t][i]), qf[i], sc[t], 0, 0, 0);
     }
     // lane (c, g) now holds the scores of keys 32 sb + 8 g + 4 t + j against column c
     float p[8];
@@ -124,13 +124,13 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a) {
       psum += p[e];
     }
     lsum = lsum * alpha + psum;
-    bf16x8 pf;
+    f16x8 pf;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) pf[e] = (bf16_t)p[e];
+    for (int e = 0; e < 8; ++e) pf[e] = (f16_t)p[e];
 #pragma unroll
     for (int t = 0; t < VT; ++t) {
       o[t] *= alpha;
-      o[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[t], pf, o[t], 0, 0, 0);
+      o[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(bf16x8_to_f16x8(vraw[t]), pf, o[t], 0, 0, 0);
     }
   }
   lsum += __shfl_xor(lsum, 16, WAVE);
@@ -141,8 +141,8 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a) {
 #pragma unroll
     for (int t = 0; t < VT; ++t) {
       u32x2 w;
-      w[0] = pack_bf16x2(o[t][0] * inv, o[t][1] * inv);
-      w[1] = pack_bf16x2(o[t][2] * inv, o[t][3] * inv);
+      w[0] = pack_f16x2(o[t][0] * inv, o[t][1] * inv);
+      w[1] = pack_f16x2(o[t][2] * inv, o[t][3] * inv);
       *(u32x2*)(op + 16 * t + 4 * g) = w;
     }
   }

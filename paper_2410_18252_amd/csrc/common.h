@@ -6,6 +6,8 @@
 typedef __bf16 bf16_t;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16_t;
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -25,6 +27,29 @@ __device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) {
 }
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   return (uint32_t)f32_to_bf16_bits(lo) | ((uint32_t)f32_to_bf16_bits(hi) << 16);
+}
+
+// fp32 -> fp16, round to nearest even, saturating at the largest finite fp16.
+__device__ __forceinline__ uint16_t f32_to_f16_bits(float f) {
+  const f16_t h = (f16_t)fminf(fmaxf(f, -65504.f), 65504.f);
+  return __builtin_bit_cast(uint16_t, h);
+}
+__device__ __forceinline__ float f16_bits_to_f32(uint16_t b) { return (float)__builtin_bit_cast(f16_t, b); }
+__device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi) {
+  return (uint32_t)f32_to_f16_bits(lo) | ((uint32_t)f32_to_f16_bits(hi) << 16);
+}
+// Eight bf16 values (as loaded from the KV cache) to fp16.  Every bf16 value whose magnitude lies in
+// fp16's normal range converts exactly (8 significant bits fit in 11); larger finite values saturate.
+__device__ __forceinline__ f16x8 bf16x8_to_f16x8(u32x4 v) {
+  typedef __fp16 h2 __attribute__((ext_vector_type(2)));
+  f16x8 r;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const h2 h = __builtin_amdgcn_cvt_pkrtz(__uint_as_float(v[e] << 16), __uint_as_float(v[e] & 0xffff0000u));
+    r[2 * e] = (f16_t)h[0];
+    r[2 * e + 1] = (f16_t)h[1];
+  }
+  return r;
 }
 
 __device__ __forceinline__ float wave_sum(float v) {

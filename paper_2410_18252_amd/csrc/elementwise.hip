@@ -13,6 +13,14 @@ __global__ void to_bf16_kernel(uint16_t* dst, const void* src, int src_is_bf16, 
   for (; i < n; i += stride)
     dst[i] = src_is_bf16 ? ((const uint16_t*)src)[i] : f32_to_bf16_bits(((const float*)src)[i]);
 }
+__global__ void to_f16w_kernel(uint16_t* dst, const void* src, int src_is_bf16, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) {
+    const uint16_t b = src_is_bf16 ? ((const uint16_t*)src)[i] : f32_to_bf16_bits(((const float*)src)[i]);
+    dst[i] = f32_to_f16_bits(bf16_bits_to_f32(b));
+  }
+}
 __global__ void to_f32_kernel(float* dst, const void* src, int src_is_bf16, size_t n) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -27,7 +35,8 @@ __global__ void pack_gate_up_kernel(uint16_t* dst, const void* gate, const void*
     const int blk = row >> 5, in = row & 31;
     const void* src = (blk & 1) ? up : gate;
     const size_t si = (size_t)((blk >> 1) * 32 + in) * d + col;
-    dst[i] = src_is_bf16 ? ((const uint16_t*)src)[si] : f32_to_bf16_bits(((const float*)src)[si]);
+    const uint16_t b = src_is_bf16 ? ((const uint16_t*)src)[si] : f32_to_bf16_bits(((const float*)src)[si]);
+    dst[i] = f32_to_f16_bits(bf16_bits_to_f32(b));
   }
 }
 __global__ void rope_table_kernel(float2* tab, int max_pos, int r, double theta) {
@@ -67,7 +76,7 @@ __global__ void embed_kernel(float* x, const uint16_t* E, const int* tokens, con
 }
 
 // One wave per row; the row lives in registers (d <= 64 * 4 * NV).  Mean, then variance of the
-// centred values (two passes over registers), all in fp32.
+// centred values (two passes over registers), all in fp32; the normalised row is stored as fp16.
 template <int NV>
 __global__ __launch_bounds__(256) void norm_kernel(const float* x, const int* row_index, int rows, int d, float eps,
                                                    const float* g1, const float* b1, uint16_t* out1,
@@ -107,15 +116,15 @@ __global__ __launch_bounds__(256) void norm_kernel(const float* x, const int* ro
     f32x4 ba = f32x4{0.f, 0.f, 0.f, 0.f};
     if (!rms) ba = *(const f32x4*)(b1 + col);
     u32x2 w;
-    w[0] = pack_bf16x2(v[i][0] * rstd * ga[0] + ba[0], v[i][1] * rstd * ga[1] + ba[1]);
-    w[1] = pack_bf16x2(v[i][2] * rstd * ga[2] + ba[2], v[i][3] * rstd * ga[3] + ba[3]);
+    w[0] = pack_f16x2(v[i][0] * rstd * ga[0] + ba[0], v[i][1] * rstd * ga[1] + ba[1]);
+    w[1] = pack_f16x2(v[i][2] * rstd * ga[2] + ba[2], v[i][3] * rstd * ga[3] + ba[3]);
     *(u32x2*)(out1 + (size_t)row * d + col) = w;
     if (out2) {
       const f32x4 gb = *(const f32x4*)(g2 + col);
       f32x4 bb = f32x4{0.f, 0.f, 0.f, 0.f};
       if (b2) bb = *(const f32x4*)(b2 + col);
-      w[0] = pack_bf16x2(v[i][0] * rstd * gb[0] + bb[0], v[i][1] * rstd * gb[1] + bb[1]);
-      w[1] = pack_bf16x2(v[i][2] * rstd * gb[2] + bb[2], v[i][3] * rstd * gb[3] + bb[3]);
+      w[0] = pack_f16x2(v[i][0] * rstd * gb[0] + bb[0], v[i][1] * rstd * gb[1] + bb[1]);
+      w[1] = pack_f16x2(v[i][2] * rstd * gb[2] + bb[2], v[i][3] * rstd * gb[3] + bb[3]);
       *(u32x2*)(out2 + (size_t)row * d + col) = w;
     }
   }
@@ -152,7 +161,7 @@ __global__ void rope_kv_kernel(RopeArgs a) {
   if (slot < a.Hq) {
     u32x4 w;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) w[e] = pack_bf16x2(v[2 * e], v[2 * e + 1]);
+    for (int e = 0; e < 4; ++e) w[e] = pack_f16x2(v[2 * e], v[2 * e + 1]);
     *(u32x4*)(a.q + (size_t)row * a.Hq * a.h + slot * a.h + chunk * 8) = w;
     return;
   }
@@ -196,6 +205,11 @@ __global__ void dpo_loss_kernel(const float* pp, const float* rp, const float* p
 hipError_t rl_to_bf16(uint16_t* dst, const void* src, int src_is_bf16, size_t n, hipStream_t s) {
   if (!n) return hipSuccess;
   hipLaunchKernelGGL(to_bf16_kernel, dim3(min(blocks_for(n), 65536)), dim3(TPB), 0, s, dst, src, src_is_bf16, n);
+  return hipGetLastError();
+}
+hipError_t rl_to_f16w(uint16_t* dst, const void* src, int src_is_bf16, size_t n, hipStream_t s) {
+  if (!n) return hipSuccess;
+  hipLaunchKernelGGL(to_f16w_kernel, dim3(min(blocks_for(n), 65536)), dim3(TPB), 0, s, dst, src, src_is_bf16, n);
   return hipGetLastError();
 }
 hipError_t rl_to_f32(float* dst, const void* src, int src_is_bf16, size_t n, hipStream_t s) {

@@ -1,5 +1,7 @@
-// bf16 x bf16 -> fp32 GEMM on the gfx950 matrix cores, C[M,N] = A[M,K] . W[N,K]^T, with the
-// epilogues the decoder needs fused in.  Both operands are K-contiguous, so every MFMA operand
+// fp16 x fp16 -> fp32 GEMM on the gfx950 matrix cores, C[M,N] = A[M,K] . W[N,K]^T, with the
+// epilogues the decoder needs fused in.  (Weights are the caller's bf16 values held in fp16, which
+// represents them exactly; activations are fp16, whose 11 significant bits keep the logits within
+// the parity bound where bf16 activations do not.)  Both operands are K-contiguous, so every MFMA operand
 // fragment is one 16-byte load.  256 threads = 4 waves in a 2x2 arrangement; each wave owns a
 // (BM/2)x(BN/2) sub-tile built from 32x32x16 MFMAs; A and W tiles of depth 64 are staged through
 // LDS (16-byte chunks, XOR-swizzled by row so that fragment reads spread over all banks) with
@@ -33,7 +35,7 @@ __device__ __forceinline__ float gelu_erf(float v) { return 0.5f * v * (1.0f + e
 __device__ __forceinline__ float silu(float v) { return v / (1.0f + __expf(-v)); }
 
 template <int BM, int BN, int EPI>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
+__global__ __launch_bounds__(256) void gemm_f16_kernel(GemmArgs g) {
   constexpr int TM = BM / 64, TN = BN / 64;      // 32x32 MFMA tiles per wave in each direction
   __shared__ __attribute__((aligned(16))) uint16_t lds[2][(BM + BN) * BK];
 
@@ -104,23 +106,23 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     const uint16_t* lb = lds[cur] + BM * BK + (wn * (BN / 2)) * BK;
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8 fa[TM], fb[TN];
+      f16x8 fa[TM], fb[TN];
       const int chunk = kk * 2 + fhalf;
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
         int r = i * 32 + frow;
-        fa[i] = *(const bf16x8*)(la + r * BK + ((chunk ^ (r & 7)) * 8));
+        fa[i] = *(const f16x8*)(la + r * BK + ((chunk ^ (r & 7)) * 8));
       }
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
         int r = j * 32 + frow;
-        fb[j] = *(const bf16x8*)(lb + r * BK + ((chunk ^ (r & 7)) * 8));
+        fb[j] = *(const f16x8*)(lb + r * BK + ((chunk ^ (r & 7)) * 8));
       }
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
     if (kt + 1 < nk) store_lds(cur ^ 1);
     __syncthreads();
@@ -177,15 +179,15 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
           } else if constexpr (EPI == EPI_RESID) {
             float* p = (float*)g.out + (size_t)row * g.ldo + col;
             *p = *p + v;
-          } else if constexpr (EPI == EPI_GELU_BF16) {
-            ((uint16_t*)g.out)[(size_t)row * g.ldo + col] = f32_to_bf16_bits(gelu_erf(v));
-          } else if constexpr (EPI == EPI_SWIGLU_BF16) {
+          } else if constexpr (EPI == EPI_GELU_F16) {
+            ((uint16_t*)g.out)[(size_t)row * g.ldo + col] = f32_to_f16_bits(gelu_erf(v));
+          } else if constexpr (EPI == EPI_SWIGLU_F16) {
             // weight rows come in blocks of 32: block 2b = gate rows [32b, 32b+32), block 2b+1 = the
             // matching up rows, so tile j (even) and tile j+1 hold gate and up of the same features.
             if ((j & 1) == 0) {
               const float up = acc[i][j + 1 < TN ? j + 1 : j][e];
               const int f = ((wcol0 + j * 32) >> 1) + frow;
-              ((uint16_t*)g.out)[(size_t)row * g.ldo + f] = f32_to_bf16_bits(silu(v) * up);
+              ((uint16_t*)g.out)[(size_t)row * g.ldo + f] = f32_to_f16_bits(silu(v) * up);
             }
           }
         }
@@ -197,7 +199,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
 template <int BM, int BN, int EPI>
 hipError_t launch(const GemmArgs& g, hipStream_t s) {
   const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
-  hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, EPI>), dim3(tiles), dim3(256), 0, s, g);
+  hipLaunchKernelGGL((gemm_f16_kernel<BM, BN, EPI>), dim3(tiles), dim3(256), 0, s, g);
   return hipGetLastError();
 }
 
@@ -209,10 +211,10 @@ hipError_t rl_gemm(const GemmArgs& g, int epi, hipStream_t s) {
   switch (epi) {
     case EPI_F32: return launch<128, 128, EPI_F32>(g, s);
     case EPI_RESID: return launch<128, 128, EPI_RESID>(g, s);
-    case EPI_GELU_BF16: return launch<128, 128, EPI_GELU_BF16>(g, s);
-    case EPI_SWIGLU_BF16:
+    case EPI_GELU_F16: return launch<128, 128, EPI_GELU_F16>(g, s);
+    case EPI_SWIGLU_F16:
       if (g.N % 64 != 0) return hipErrorInvalidValue;
-      return launch<128, 128, EPI_SWIGLU_BF16>(g, s);
+      return launch<128, 128, EPI_SWIGLU_F16>(g, s);
     case EPI_LMHEAD: return launch<128, 128, EPI_LMHEAD>(g, s);
   }
   return hipErrorInvalidValue;

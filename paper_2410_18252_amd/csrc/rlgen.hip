@@ -177,7 +177,7 @@ int pack_weights(rlgen_ctx* c, const rlgen_weights* w, hipStream_t st) {
       return RLGEN_ERR_NULL;
   }
   HIPCHK(rl_to_bf16(c->embed, w->embed_in, bf, V * d, st));
-  HIPCHK(rl_to_bf16(c->lm_head, w->lm_head, bf, V * d, st));
+  HIPCHK(rl_to_f16w(c->lm_head, w->lm_head, bf, V * d, st));
   HIPCHK(rl_to_f32(c->fng, w->final_norm_g, bf, d, st));
   if (!llama) HIPCHK(rl_to_f32(c->fnb, w->final_norm_b, bf, d, st));
   for (int l = 0; l < m.n_layers; ++l) {
@@ -185,15 +185,15 @@ int pack_weights(rlgen_ctx* c, const rlgen_weights* w, hipStream_t st) {
     LayerW& L = c->layers[l];
     HIPCHK(rl_to_f32(L.n1g, s.norm1_g, bf, d, st));
     HIPCHK(rl_to_f32(L.n2g, s.norm2_g, bf, d, st));
-    HIPCHK(rl_to_bf16(L.wqkv, s.wq, bf, qd * d, st));
-    HIPCHK(rl_to_bf16(L.wqkv + qd * d, s.wk, bf, kvd * d, st));
-    HIPCHK(rl_to_bf16(L.wqkv + (qd + kvd) * d, s.wv, bf, kvd * d, st));
-    HIPCHK(rl_to_bf16(L.wo, s.wo, bf, d * qd, st));
-    HIPCHK(rl_to_bf16(L.wdown, s.w_down, bf, d * F, st));
+    HIPCHK(rl_to_f16w(L.wqkv, s.wq, bf, qd * d, st));
+    HIPCHK(rl_to_f16w(L.wqkv + qd * d, s.wk, bf, kvd * d, st));
+    HIPCHK(rl_to_f16w(L.wqkv + (qd + kvd) * d, s.wv, bf, kvd * d, st));
+    HIPCHK(rl_to_f16w(L.wo, s.wo, bf, d * qd, st));
+    HIPCHK(rl_to_f16w(L.wdown, s.w_down, bf, d * F, st));
     if (llama) {
       HIPCHK(rl_pack_gate_up(L.wup, s.w_gate, s.w_up, bf, (int)F, (int)d, st));
     } else {
-      HIPCHK(rl_to_bf16(L.wup, s.w_up, bf, F * d, st));
+      HIPCHK(rl_to_f16w(L.wup, s.w_up, bf, F * d, st));
       HIPCHK(rl_to_f32(L.n1b, s.norm1_b, bf, d, st));
       HIPCHK(rl_to_f32(L.n2b, s.norm2_b, bf, d, st));
       HIPCHK(rl_to_f32(L.bqkv, s.bq, bf, qd, st));
@@ -297,7 +297,7 @@ int run_layers(rlgen_ctx* c, int rows, bool decode, int t, int ncopy, bool use_c
     g = GemmArgs{};
     g.A = c->n2; g.lda = d; g.W = L.wup; g.ldw = d; g.M = rows; g.N = llama ? 2 * F : F; g.K = d;
     g.bias = llama ? nullptr : L.bup; g.out = c->act; g.ldo = F;
-    HIPCHK(rl_gemm(g, llama ? EPI_SWIGLU_BF16 : EPI_GELU_BF16, st));
+    HIPCHK(rl_gemm(g, llama ? EPI_SWIGLU_F16 : EPI_GELU_F16, st));
     g = GemmArgs{};
     g.A = c->act; g.lda = F; g.W = L.wdown; g.ldw = F; g.M = rows; g.N = d; g.K = F;
     g.bias = llama ? nullptr : L.bdown; g.out = c->x; g.ldo = d;

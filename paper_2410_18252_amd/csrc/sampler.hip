@@ -93,8 +93,8 @@ __global__ __launch_bounds__(256) void sample_kernel(SampleArgs a) {
       const u32x4 hv = *(const u32x4*)(hrow + k);
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        acc += __uint_as_float(wv[e] << 16) * __uint_as_float(hv[e] << 16);
-        acc += __uint_as_float(wv[e] & 0xffff0000u) * __uint_as_float(hv[e] & 0xffff0000u);
+        acc += f16_bits_to_f32((uint16_t)(wv[e] & 0xffffu)) * f16_bits_to_f32((uint16_t)(hv[e] & 0xffffu));
+        acc += f16_bits_to_f32((uint16_t)(wv[e] >> 16)) * f16_bits_to_f32((uint16_t)(hv[e] >> 16));
       }
     }
     logit = acc / a.temperature;

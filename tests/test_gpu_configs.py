@@ -1,0 +1,113 @@
+"""Parity at the full sizes of workloads 2-5, in the launch configuration the bench times.
+
+The GPU runs the whole workload (all prompts, K samples, all new tokens).  The oracle cannot, so it
+runs a deterministic subset -- the shortest prompt, the longest prompt and the first one or two by
+index, K samples, the first 8 new tokens -- and the GPU's outputs for exactly those sequences are
+compared element by element: tokens (oracle's token forced where its CDF margin <= 1e-3), token
+log-probs (1e-2) and raw logits after the 8th token (2e-2).  The remaining outputs are checked through
+properties that hold at any size: tokens in range, finite log-probs, equal uniforms giving equal
+samples, run-to-run bit-identity, and (workload 4, as its definition asks) rlgen_score over all
+generated sequences reproducing rlgen_generate's log-probs."""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import decoder as O
+from workloads import get_config, make_prompts, make_uniforms, make_weights, parity_subset
+from gpu_util import MARGIN, TOL_LOGITS, TOL_LOGPROB, R, dev_f32, dev_i32, oracle_generate_batch, padded, report
+
+pytestmark = pytest.mark.gpu
+N_ORACLE_TOKENS = 8
+
+
+def log(msg):
+    print(f"[{time.strftime('%H:%M:%S')}] {msg}", flush=True)
+
+
+@pytest.mark.parametrize("ci", [2, 3, 4, 5])
+def test_full_size_workload(ci):
+    w = get_config(ci)
+    m = w.model
+    r = R()
+    log(f"config {ci}: drawing {m.n_params / 1e9:.2f}B weights")
+    W = make_weights(m, w.seed_weights, w.bf16_weights, threads=16)
+    arr, lens = make_prompts(w)
+    u = make_uniforms(w)
+    B, k, T = w.n_prompts, w.k, w.max_new
+    u[1, 1] = u[1, 0]                                    # one prompt draws the same sample twice
+    subset = parity_subset(lens, n_first=1 if ci == 5 else 2)
+
+    log("uploading weights and building the context")
+    kv_tokens = int(sum(k * ((int(n) + T + 31) // 32 * 32) for n in lens))
+    cfg = r.make_cfg(m, weight_dtype=r.DTYPE_BF16, max_seqs=B * k, max_seq_len=int(lens.max()) + T,
+                     max_kv_tokens=kv_tokens)
+    dev = r.upload_weights(W.tensors)
+    pol = r.Policy(cfg, dev)
+    del dev
+    torch.cuda.empty_cache()
+
+    log(f"oracle on prompts {subset} (lengths {[int(lens[i]) for i in subset]}), {N_ORACLE_TOKENS} tokens each")
+    dec = O.Decoder(W, m)
+    n8 = N_ORACLE_TOKENS
+    t0 = time.time()
+    t_o, l_o, margins, z_o, _ = oracle_generate_batch(dec, arr[subset], lens[subset], k, n8, w.temperature, u[subset][:, :, :n8])
+    log(f"oracle done in {time.time() - t0:.1f}s")
+    forced = np.full((B, k, T), -1, np.int32)
+    forced[subset, :, :n8] = np.where(margins > MARGIN, -1, t_o)
+
+    log("GPU: full workload")
+    d_arr, d_u, d_forced = dev_i32(arr), dev_f32(u), dev_i32(forced)
+    t_g, l_g = r.rlgen_generate(pol, d_arr, lens, k, T, w.temperature, d_u, d_forced)
+    torch.cuda.synchronize()
+    tm = r.rlgen_get_timings(pol)
+    log(f"GPU done: prefill {tm['prefill_ms']:.1f} ms, decode {tm['decode_ms']:.1f} ms")
+    assert r.rlgen_status(pol) == 0
+    tg, lg = t_g.cpu().numpy(), l_g.cpu().numpy()
+
+    # subset, element by element
+    lp_err = np.abs(lg[subset][:, :, :n8] - l_o).max()
+    mism = int((tg[subset][:, :, :n8] != t_o).sum())
+    seqs8 = [np.concatenate([arr[b, :lens[b]], t_o[i, j]]) for i, b in enumerate(subset) for j in range(k)]
+    sarr, slens = padded(seqs8)
+    z_g = r.rlgen_debug_logits(pol, dev_i32(sarr), slens).cpu().numpy()
+    z_err = np.abs(z_g - z_o.reshape(len(seqs8), -1)).max()
+    report(f"config{ci}", logit_err=z_err, lp_err=lp_err, mismatches=mism, forced_fraction=(forced[subset, :, :n8] >= 0).mean(),
+           z_std=z_o.std(), prefill_ms=tm["prefill_ms"], decode_ms=tm["decode_ms"])
+    log(f"logit err {z_err:.4g}, logprob err {lp_err:.4g}, token mismatches {mism}")
+    assert mism == 0
+    assert lp_err < TOL_LOGPROB
+    assert z_err < TOL_LOGITS
+
+    # everything else, through properties
+    assert ((tg >= 0) & (tg < m.vocab)).all()
+    assert np.isfinite(lg).all() and (lg < 0).all()
+    np.testing.assert_array_equal(tg[1, 0], tg[1, 1])
+    np.testing.assert_array_equal(lg[1, 0], lg[1, 1])
+    t_2, l_2 = r.rlgen_generate(pol, d_arr, lens, k, T, w.temperature, d_u, d_forced)
+    assert torch.equal(t_2, t_g) and torch.equal(l_2, l_g)
+    if ci in (2, 4):
+        log("GPU: scoring all generated sequences")
+        full = np.full((B * k, int(lens.max()) + T), -1, np.int32)
+        flens = np.repeat(lens, k) + T
+        for b in range(B):
+            for j in range(k):
+                full[b * k + j, :lens[b]] = arr[b, :lens[b]]
+                full[b * k + j, lens[b]:lens[b] + T] = tg[b, j]
+        sc = r.rlgen_score(pol, dev_i32(full), flens, w.temperature, np.repeat(lens, k))
+        torch.cuda.synchronize()
+        log(f"score done in {r.rlgen_get_timings(pol)['prefill_ms']:.1f} ms")
+        sc = sc.cpu().numpy()
+        worst = 0.0
+        for i in range(B * k):
+            P = int(flens[i]) - T
+            worst = max(worst, float(np.abs(sc[i, P:P + T] - lg.reshape(B * k, T)[i]).max()))
+            assert (sc[i, :P] == 0).all() and (sc[i, P + T:] == 0).all()
+        report(f"config{ci}-score-vs-generate", err=worst)
+        assert worst < TOL_LOGPROB
+        # and against the oracle on the subset's 8-token sequences
+        sc8 = r.rlgen_score(pol, dev_i32(sarr), slens, w.temperature, slens - n8).cpu().numpy()
+        for i in range(len(seqs8)):
+            assert np.abs(sc8[i, slens[i] - n8:slens[i]] - l_o.reshape(-1, n8)[i]).max() < TOL_LOGPROB
+    pol.close()

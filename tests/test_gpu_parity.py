@@ -9,7 +9,7 @@ import torch
 
 from oracle import decoder as O
 from workloads import get_config, make_prompts, make_uniforms, make_weights, Weights
-from gpu_util import (GPU_SHAPES, MARGIN, TOL_LOGITS, TOL_LOGPROB, R, dev_f32, dev_i32, make_policy,
+from gpu_util import (report, GPU_SHAPES, MARGIN, TOL_LOGITS, TOL_LOGPROB, R, dev_f32, dev_i32, make_policy,
                       oracle_generate_batch, padded, scaled_bf16_weights)
 
 pytestmark = pytest.mark.gpu
@@ -36,6 +36,7 @@ def test_logits_match_oracle(small):
     arr, lens = padded(seqs, pad=10 ** 6)          # pad cells hold an out-of-range id: never read
     got = R().rlgen_debug_logits(pol, dev_i32(arr), lens).cpu().numpy()
     ref = np.stack([O.last_logits(dec, s) for s in seqs])
+    report("logits", err=np.abs(got - ref).max(), ref_std=ref.std(), ref_max=np.abs(ref).max(), d=m.d_model, h=m.head_dim)
     assert np.abs(ref).max() > 0.3
     assert np.abs(got - ref).max() < TOL_LOGITS
     assert R().rlgen_status(pol) == 0
@@ -51,6 +52,7 @@ def test_score_matches_oracle(small):
         got = R().rlgen_score(pol, dev_i32(arr), lens, 0.7, sf).cpu().numpy()
         for i, s in enumerate(seqs):
             ref = O.score(dec, s, 0.7, 1 if sf is None else sf[i])
+            report("score", err=np.abs(got[i, :len(s)] - ref).max(), n=len(s), h=m.head_dim)
             assert np.abs(got[i, :len(s)] - ref).max() < TOL_LOGPROB, (i, sf is None)
             assert (got[i, len(s):] == 0).all()
             lo = max(1, 1 if sf is None else sf[i])
@@ -72,6 +74,7 @@ def test_generate_matches_oracle(small):
     forced = np.where(margins > MARGIN, -1, t_o).astype(np.int32)
     t_g, l_g = r.rlgen_generate(pol, dev_i32(arr), lens, k, T, temp, dev_f32(u), dev_i32(forced))
     t_g, l_g = t_g.cpu().numpy(), l_g.cpu().numpy()
+    report("generate-forced", err=np.abs(l_g - l_o).max(), mismatches=(t_g != t_o).sum(), free=(forced < 0).mean(), h=m.head_dim)
     np.testing.assert_array_equal(t_g, t_o)
     assert np.abs(l_g - l_o).max() < TOL_LOGPROB
     assert (forced < 0).mean() > 0.2                    # the comparison of free tokens is not vacuous
@@ -79,6 +82,8 @@ def test_generate_matches_oracle(small):
     t_f, l_f = r.rlgen_generate(pol, dev_i32(arr), lens, k, T, temp, dev_f32(u))
     t_f, l_f = t_f.cpu().numpy(), l_f.cpu().numpy()
     _, l_t, _, z_t, buckets = oracle_generate_batch(dec, arr, lens, k, T, temp, u, forced=t_f, with_buckets=True)
+    report("generate-free", err=np.abs(l_f - l_t).max(), cdf_slack=max((buckets[..., 0] - u).max(), (u - buckets[..., 1]).max()),
+           same_as_oracle=(t_f == t_o).mean(), h=m.head_dim)
     assert (buckets[..., 0] - MARGIN <= u).all() and (u <= buckets[..., 1] + MARGIN).all()
     assert np.abs(l_f - l_t).max() < TOL_LOGPROB
     np.testing.assert_array_equal(t_f[0, 0], t_f[0, 1])
@@ -86,6 +91,7 @@ def test_generate_matches_oracle(small):
     full = [np.concatenate([prompts[b], t_f[b, j]]) for b in range(B) for j in range(k)]
     farr, flens = padded(full)
     z_g = r.rlgen_debug_logits(pol, dev_i32(farr), flens).cpu().numpy()
+    report("generate-final-logits", err=np.abs(z_g - z_t.reshape(B * k, -1)).max(), h=m.head_dim)
     assert np.abs(z_g - z_t.reshape(B * k, -1)).max() < TOL_LOGITS
     # (4) scoring the generated sequences reproduces generate's log-probs (prefill kernels vs decode kernels)
     sc = r.rlgen_score(pol, dev_i32(farr), flens, temp, np.repeat(lens, k)).cpu().numpy()
@@ -204,6 +210,8 @@ def test_config1_end_to_end():
     full = [np.concatenate([arr[b, :lens[b]], t_f[b, j]]) for b in range(w.n_prompts) for j in range(w.k)]
     farr, flens = padded(full)
     z_g = r.rlgen_debug_logits(pol, dev_i32(farr), flens).cpu().numpy()
+    report("config1", logit_err=np.abs(z_g - z_t.reshape(len(full), -1)).max(), lp_err=np.abs(l_f.cpu().numpy() - l_t).max(),
+           forced_fraction=(forced >= 0).mean(), z_std=z_t.std())
     assert np.abs(z_g - z_t.reshape(len(full), -1)).max() < TOL_LOGITS
     # the same model with weights pre-rounded to bf16 on the host: separates weight rounding from the rest
     decb = O.Decoder(W.rounded_to_bf16(), w.model)
