@@ -1,0 +1,139 @@
+#!/usr/bin/env python3
+"""Throughput of the generation hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--no-cpu-baseline]
+
+One step = one rlgen_generate call over the whole synthetic batch of the chosen workload (default:
+workload 4, the Pythia-2.8B-shaped one the headline target is quoted on): prompt pass, K-way fan-out
+and all decode steps, inputs already resident in HBM.  Prints ONE JSON line with generated tokens/s,
+the roofline of the dominant kernel (decode attention, HBM-bound; its launch time is measured with HIP
+events on the launch stream inside the timed region) and the CPU oracle timed on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", type=int, default=4)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1")
+
+    import torch
+    import paper_2410_18252_amd.rlgen as R
+    from workloads import get_config, make_prompts, make_uniforms, make_weights, parity_subset
+
+    w = get_config(args.config)
+    m = w.model
+    t0 = time.time()
+    W = make_weights(m, w.seed_weights, w.bf16_weights, threads=16)
+    arr, lens = make_prompts(w)
+    u = make_uniforms(w)
+    B, k, T = w.n_prompts, w.k, w.max_new
+    S = B * k
+    kv_tokens = int(sum(k * ((int(n) + T + 31) // 32 * 32) for n in lens))
+    cfg = R.make_cfg(m, weight_dtype=R.DTYPE_BF16 if W.is_bf16 else R.DTYPE_F32, max_seqs=S,
+                     max_seq_len=int(lens.max()) + T, max_kv_tokens=kv_tokens)
+    dev = R.upload_weights(W.tensors)
+    pol = R.Policy(cfg, dev)
+    del dev
+    torch.cuda.empty_cache()
+    setup_s = time.time() - t0
+
+    d_arr = torch.from_numpy(arr).cuda()
+    d_u = torch.from_numpy(u).cuda()
+    out = (torch.empty((B, k, T), dtype=torch.int32, device="cuda"),
+           torch.empty((B, k, T), dtype=torch.float32, device="cuda"))
+
+    def step():
+        R.rlgen_generate(pol, d_arr, lens, k, T, w.temperature, d_u, None, out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    R.rlgen_set_profiling(pol, True)
+    prefill_ms, decode_ms, attn_ms, attn_launches = [], [], 0.0, 0
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+        tm = R.rlgen_get_timings(pol)        # waits for this step's events only
+        prefill_ms.append(tm["prefill_ms"]); decode_ms.append(tm["decode_ms"])
+        attn_ms += tm["decode_attn_ms"]; attn_launches += tm["decode_attn_launches"]
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    R.rlgen_set_profiling(pol, False)
+    assert R.rlgen_status(pol) == 0
+    toks = out[0].cpu().numpy()
+    assert ((toks >= 0) & (toks < m.vocab)).all()
+
+    ms_per_step = 1e3 * elapsed / args.steps
+    tokens_per_s = S * T / (elapsed / args.steps)
+
+    # ---- roofline of the dominant kernel: decode attention.  Algorithmic bytes of one launch (one layer, one
+    # decode step t): every sequence reads its K and V streams of ctx = prompt_len + t keys (bf16), plus q in
+    # and the attention output out (fp16).
+    seq_len = np.repeat(lens.astype(np.int64), k)
+    per_key = 2 * 2 * m.n_kv_heads * m.head_dim                    # K and V, 2 bytes each
+    qo = 2 * 2 * S * m.n_q_heads * m.head_dim
+    bytes_per_launch = np.mean([per_key * int((seq_len + t).sum()) + qo for t in range(1, T)]) if T > 1 else 0.0
+    attn_us = 1e3 * attn_ms / max(attn_launches, 1)
+    achieved = bytes_per_launch / (attn_us * 1e-6) / 1e9 if attn_launches else 0.0
+    roofline = {"bound": "hbm", "kernel": "attention_kernel<HD,decode>", "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": None, "algorithmic_bytes_per_launch": int(bytes_per_launch),
+                "avg_launch_us": round(attn_us, 2), "launches": attn_launches}
+
+    # whole decode phase: weights once per step + KV, over the measured decode time
+    wbytes = 2 * (m.n_params - m.vocab * m.d_model)                # all matrices but the embedding table
+    decode_bytes = sum(wbytes + m.n_layers * (per_key * int((seq_len + t).sum()) + per_key * S) for t in range(1, T))
+    decode_gbs = decode_bytes / (np.mean(decode_ms) * 1e-3) / 1e9 if T > 1 else 0.0
+
+    result = {
+        "metric": "generated tokens/s (K=2/prompt) at 1 GPU; decode HBM GB/s as % of peak",
+        "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 2), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": w.name, "prompts": B, "k": k, "max_new": T, "prompt_len": [w.prompt_len_lo, w.prompt_len_hi],
+                   "temperature": w.temperature, "generated_tokens_per_step": S * T,
+                   "storage": "bf16 weights (held as fp16, exact) and bf16 KV cache; fp16 MFMA inputs, fp32 accumulation"},
+        "prefill_ms": round(float(np.mean(prefill_ms)), 2), "decode_ms": round(float(np.mean(decode_ms)), 2),
+        "decode_algorithmic_GBps": round(decode_gbs, 1), "decode_frac_of_hbm_peak": round(decode_gbs / HBM_PEAK_GBS, 4),
+        "setup_s": round(setup_s, 1),
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import decoder as O
+        subset = parity_subset(lens, n_first=2) if args.config != 5 else parity_subset(lens, n_first=0)[:1]
+        n_new = min(8, T)
+        dec = O.Decoder(W, m)
+        t0 = time.perf_counter()
+        for b in subset:
+            O.generate(dec, arr[b, :lens[b]], k, n_new, w.temperature, u[b][:, :n_new])
+        cpu_s = time.perf_counter() - t0
+        result["cpu_baseline"] = {
+            "value": round(len(subset) * k * n_new / cpu_s, 3), "unit": "tokens/s", "cores": len(os.sched_getaffinity(0)),
+            "kind": "oracle", "seconds": round(cpu_s, 1),
+            "sample": f"prompts {subset} of the same workload (lengths {[int(lens[b]) for b in subset]}), "
+                      f"K={k}, first {n_new} new tokens each, full-size weights; numpy fp32 (BLAS threads = cores)"}
+    pol.close()
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
