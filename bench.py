@@ -21,6 +21,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per decode-attention launch over its algorithmic bytes on workload 4, measured with rocprofv3
+# FETCH_SIZE + WRITE_SIZE, each scaled by its reading for a plain 1 GiB copy (profiles/attention_decode_c4_hbm_traffic.txt).
+TRAFFIC_OVER_ALGORITHMIC = 1.039
 
 
 def main():
@@ -30,6 +33,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy (calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--max-new", type=int, default=0, help="override the workload's number of new tokens (profiling runs)")
+    ap.add_argument("--no-kernel-events", action="store_true",
+                    help="do not bracket the decode-attention launches with HIP events (for rocprofv3 --pmc runs)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1")
@@ -39,6 +47,9 @@ def main():
     from workloads import get_config, make_prompts, make_uniforms, make_weights, parity_subset
 
     w = get_config(args.config)
+    if args.max_new:
+        import dataclasses
+        w = dataclasses.replace(w, max_new=args.max_new, name=f"{w.name}-maxnew{args.max_new}")
     m = w.model
     t0 = time.time()
     W = make_weights(m, w.seed_weights, w.bf16_weights, threads=16)
@@ -63,10 +74,16 @@ def main():
     def step():
         R.rlgen_generate(pol, d_arr, lens, k, T, w.temperature, d_u, None, out)
 
+    if args.copy_probe:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    R.rlgen_set_profiling(pol, True)
+    R.rlgen_set_profiling(pol, not args.no_kernel_events)
     prefill_ms, decode_ms, attn_ms, attn_launches = [], [], 0.0, 0
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -95,7 +112,8 @@ def main():
     achieved = bytes_per_launch / (attn_us * 1e-6) / 1e9 if attn_launches else 0.0
     roofline = {"bound": "hbm", "kernel": "attention_kernel<HD,decode>", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": None, "algorithmic_bytes_per_launch": int(bytes_per_launch),
+                "traffic": int(round(TRAFFIC_OVER_ALGORITHMIC * bytes_per_launch)) if args.config == 4 else None,
+                "algorithmic_bytes_per_launch": int(bytes_per_launch),
                 "avg_launch_us": round(attn_us, 2), "launches": attn_launches}
 
     # whole decode phase: weights once per step + KV, over the measured decode time

@@ -19,7 +19,8 @@
  *    validation launches nothing and writes nothing.  Conditions only the device can see (a token
  *    id outside [0, vocab), a uniform outside [0, 1)) clamp the value, never read out of bounds,
  *    and set a sticky flag reported by rlgen_status.
- *  - Arithmetic: weights, GEMM inputs and the KV cache are bf16; accumulation, the residual
+ *  - Arithmetic: weights are bf16 values (held in fp16, which represents them exactly in its normal
+ *    range); GEMM and attention inputs are fp16; the KV cache is bf16; accumulation, the residual
  *    stream, normalisation statistics, softmax and log-sum-exp are fp32 (fp64 for the CDF scan).
  */
 #ifndef RLGEN_H
@@ -95,7 +96,8 @@ typedef struct {
  * weights, the KV cache, activations and sampler partials), or 0 if cfg is null or invalid. */
 size_t rlgen_workspace_bytes(const rlgen_model_cfg *cfg);
 
-/* Builds a context for one policy (Algorithm 1: "update generation model theta <- theta_i").
+/* Builds a context for one policy (Algorithm 1: procedure Generate starts by loading the current
+ * parameters theta_i into the generation model).
  * cfg, weights: HOST structs holding DEVICE tensor pointers.  workspace: DEVICE, 256-byte aligned,
  * at least rlgen_workspace_bytes(cfg); it must stay alive, and must not be written by the caller,
  * until rlgen_destroy.  The weight tensors are converted/copied on `hip_stream` (a hipStream_t, or
@@ -105,7 +107,7 @@ int rlgen_create(const rlgen_model_cfg *cfg, const rlgen_weights *weights, void 
                  size_t workspace_bytes, void *hip_stream, rlgen_ctx **out);
 
 /* Replaces the policy's weights in place with a new theta_i of the same shape (Algorithm 1,
- * procedure Generate, first line; Section 5.2 notes that this hand-off is on the critical path). */
+ * procedure Generate, first step; Appendix A.2 notes that this hand-off blocks the learner). */
 int rlgen_update_weights(rlgen_ctx *ctx, const rlgen_weights *weights, void *hip_stream);
 
 /* y ~ pi_theta(. | x): k completions of exactly max_new tokens per prompt by inverse-CDF sampling
