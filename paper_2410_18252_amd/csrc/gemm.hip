@@ -10,7 +10,14 @@
 
 namespace {
 
-constexpr int BK = 64;            // bf16 elements of K per LDS stage (128 bytes per row)
+constexpr int BK = 64;            // fp16 elements of K per LDS stage (128 bytes per row)
+#ifndef SWZ_SHIFT
+#define SWZ_SHIFT 1
+#endif
+// LDS rows are 8 chunks of 16 bytes; chunk c of row r is stored at chunk position c ^ swz(r).  The LDS of
+// gfx950 has 64 banks of 4 bytes: 16 lanes of a 128-bit read are served per cycle, and rows r, r + 1 sit in
+// opposite halves of the banks, so the swizzle steps every second row (measured: SQ_LDS_BANK_CONFLICT = 0).
+__device__ __forceinline__ int swz(int r) { return (r >> SWZ_SHIFT) & 7; }
 
 // Blocks are handed to the 8 XCDs round-robin by the hardware.  Renumber them so that each XCD
 // (one L2) works on a contiguous range of logical tile ids, then walk tiles M-fastest inside groups
@@ -34,54 +41,66 @@ __device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int& tm,
 __device__ __forceinline__ float gelu_erf(float v) { return 0.5f * v * (1.0f + erff(v * 0.70710678118654752f)); }
 __device__ __forceinline__ float silu(float v) { return v / (1.0f + __expf(-v)); }
 
-template <int BM, int BN, int EPI>
-__global__ __launch_bounds__(256) void gemm_f16_kernel(GemmArgs g) {
-  constexpr int TM = BM / 64, TN = BN / 64;      // 32x32 MFMA tiles per wave in each direction
-  __shared__ __attribute__((aligned(16))) uint16_t lds[2][(BM + BN) * BK];
+template <int BM, int BN, int WM, int WN, int EPI, bool KTAIL>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_f16_kernel(GemmArgs g) {
+  constexpr int NT = WM * WN * 64;               // threads
+  constexpr int TM = BM / WM / 32, TN = BN / WN / 32;   // 32x32 MFMA tiles per wave in each direction
+  constexpr int RPP = NT / 8;                    // rows covered by one pass of 16-byte loads
+  constexpr int PA = BM / RPP, PB = BN / RPP;
+  static_assert(PA >= 1 && PB >= 1 && TM >= 1 && TN >= 1, "tile too small for the thread count");
+  extern __shared__ __attribute__((aligned(16))) uint16_t lds[];   // 2 x (BM + BN) x BK
+  constexpr int STAGE = (BM + BN) * BK;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WN, wn = wave % WN;
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
   int tile_m, tile_n;
   tile_of_block(tiles_m, tiles_n, tile_m, tile_n);
   const int row0 = tile_m * BM, col0 = tile_n * BN;
 
-  // ---- global -> register staging: thread t covers chunk (t % 8) of rows (t / 8) + 32 i
+  // ---- global -> register staging: thread t covers chunk (t % 8) of rows (t / 8) + RPP i
   const int ld_chunk = tid & 7, ld_row = tid >> 3;
   const uint16_t* __restrict__ A = (const uint16_t*)g.A;
   const uint16_t* __restrict__ W = (const uint16_t*)g.W;
-  u32x4 ra[BM / 32], rb[BN / 32];
-  const uint16_t* pa[BM / 32];
-  const uint16_t* pb[BN / 32];
+  u32x4 ra[PA], rb[PB];
+  const uint16_t* pa[PA];
+  const uint16_t* pb[PB];
 #pragma unroll
-  for (int i = 0; i < BM / 32; ++i) {
-    int r = min(row0 + ld_row + 32 * i, g.M - 1);
+  for (int i = 0; i < PA; ++i) {
+    int r = min(row0 + ld_row + RPP * i, g.M - 1);
     pa[i] = A + (size_t)r * g.lda + ld_chunk * 8;
   }
 #pragma unroll
-  for (int i = 0; i < BN / 32; ++i) {
-    int r = min(col0 + ld_row + 32 * i, g.N - 1);
+  for (int i = 0; i < PB; ++i) {
+    int r = min(col0 + ld_row + RPP * i, g.N - 1);
     pb[i] = W + (size_t)r * g.ldw + ld_chunk * 8;
   }
   auto load_global = [&](int k0) {
-    const bool ok = k0 + ld_chunk * 8 < g.K;
+    if constexpr (KTAIL) {     // K is not a multiple of BK: chunks beyond K read as zero
+      const bool ok = k0 + ld_chunk * 8 < g.K;
 #pragma unroll
-    for (int i = 0; i < BM / 32; ++i) ra[i] = ok ? *(const u32x4*)(pa[i] + k0) : u32x4{0, 0, 0, 0};
+      for (int i = 0; i < PA; ++i) ra[i] = ok ? *(const u32x4*)(pa[i] + k0) : u32x4{0, 0, 0, 0};
 #pragma unroll
-    for (int i = 0; i < BN / 32; ++i) rb[i] = ok ? *(const u32x4*)(pb[i] + k0) : u32x4{0, 0, 0, 0};
+      for (int i = 0; i < PB; ++i) rb[i] = ok ? *(const u32x4*)(pb[i] + k0) : u32x4{0, 0, 0, 0};
+    } else {
+#pragma unroll
+      for (int i = 0; i < PA; ++i) ra[i] = *(const u32x4*)(pa[i] + k0);
+#pragma unroll
+      for (int i = 0; i < PB; ++i) rb[i] = *(const u32x4*)(pb[i] + k0);
+    }
   };
   auto store_lds = [&](int buf) {
-    uint16_t* la = lds[buf];
-    uint16_t* lb = lds[buf] + BM * BK;
+    uint16_t* la = lds + buf * STAGE;
+    uint16_t* lb = la + BM * BK;
 #pragma unroll
-    for (int i = 0; i < BM / 32; ++i) {
-      int r = ld_row + 32 * i;
-      *(u32x4*)(la + r * BK + ((ld_chunk ^ (r & 7)) * 8)) = ra[i];
+    for (int i = 0; i < PA; ++i) {
+      int r = ld_row + RPP * i;
+      *(u32x4*)(la + r * BK + ((ld_chunk ^ swz(r)) * 8)) = ra[i];
     }
 #pragma unroll
-    for (int i = 0; i < BN / 32; ++i) {
-      int r = ld_row + 32 * i;
-      *(u32x4*)(lb + r * BK + ((ld_chunk ^ (r & 7)) * 8)) = rb[i];
+    for (int i = 0; i < PB; ++i) {
+      int r = ld_row + RPP * i;
+      *(u32x4*)(lb + r * BK + ((ld_chunk ^ swz(r)) * 8)) = rb[i];
     }
   };
 
@@ -102,63 +121,72 @@ __global__ __launch_bounds__(256) void gemm_f16_kernel(GemmArgs g) {
   for (int kt = 0; kt < nk; ++kt) {
     const int cur = kt & 1;
     if (kt + 1 < nk) load_global((kt + 1) * BK);
-    const uint16_t* la = lds[cur] + (wm * (BM / 2)) * BK;
-    const uint16_t* lb = lds[cur] + BM * BK + (wn * (BN / 2)) * BK;
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      f16x8 fa[TM], fb[TN];
+    const uint16_t* la = lds + cur * STAGE + (wm * (BM / WM)) * BK;
+    const uint16_t* lb = lds + cur * STAGE + BM * BK + (wn * (BN / WN)) * BK;
+    // fragments of step kk + 1 are fetched from LDS while the MFMAs of step kk run; the next tile moves
+    // from registers to the other LDS buffer under the last MFMAs of this one
+    f16x8 fa[2][TM], fb[2][TN];
+    auto load_frags = [&](int kk, int slot) {
       const int chunk = kk * 2 + fhalf;
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
         int r = i * 32 + frow;
-        fa[i] = *(const f16x8*)(la + r * BK + ((chunk ^ (r & 7)) * 8));
+        fa[slot][i] = *(const f16x8*)(la + r * BK + ((chunk ^ swz(r)) * 8));
       }
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
         int r = j * 32 + frow;
-        fb[j] = *(const f16x8*)(lb + r * BK + ((chunk ^ (r & 7)) * 8));
+        fb[slot][j] = *(const f16x8*)(lb + r * BK + ((chunk ^ swz(r)) * 8));
       }
+    };
+    load_frags(0, 0);
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      if (kk + 1 < BK / 16) load_frags(kk + 1, (kk + 1) & 1);
+      if (kk == BK / 16 - 2 && kt + 1 < nk) store_lds(cur ^ 1);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[kk & 1][i], fb[kk & 1][j], acc[i][j], 0, 0, 0);
     }
-    if (kt + 1 < nk) store_lds(cur ^ 1);
     __syncthreads();
   }
 
   // ---- epilogue.  acc[i][j][e]: row = 8 (e / 4) + 4 (lane / 32) + e % 4, col = lane % 32 of the 32x32 tile
-  const int wrow0 = row0 + wm * (BM / 2), wcol0 = col0 + wn * (BN / 2);
+  const int wrow0 = row0 + wm * (BM / WM), wcol0 = col0 + wn * (BN / WN);
   if constexpr (EPI == EPI_LMHEAD) {
     // per row and per 64-column group: max and sum of exp of the tempered logits; optional capture
     // of the target column's tempered logit.  Nothing of size [M, N] is written.
-    static_assert(BN == 128, "one wave must own one 64-column group");
-    const int group = wcol0 >> 6;
+    static_assert(TN % 2 == 0, "a wave must own whole 64-column groups");
     const int ngroups = (g.N + 63) >> 6;
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
+    for (int gi = 0; gi < TN / 2; ++gi) {
+      const int group = (wcol0 >> 6) + gi;
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int row = wrow0 + i * 32 + 8 * (e >> 2) + 4 * fhalf + (e & 3);
-        float l[TN];
-        float mx = -INFINITY;
+      for (int i = 0; i < TM; ++i) {
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          const int col = wcol0 + j * 32 + frow;
-          l[j] = col < g.N ? acc[i][j][e] / g.temperature : -INFINITY;
-          mx = fmaxf(mx, l[j]);
-          if (g.target != nullptr && row < g.M && col < g.N && g.target[row] == col) g.target_logit[row] = l[j];
+        for (int e = 0; e < 16; ++e) {
+          const int row = wrow0 + i * 32 + 8 * (e >> 2) + 4 * fhalf + (e & 3);
+          float l[2];
+          float mx = -INFINITY;
+#pragma unroll
+          for (int jj = 0; jj < 2; ++jj) {
+            const int col = wcol0 + (2 * gi + jj) * 32 + frow;
+            l[jj] = col < g.N ? acc[i][2 * gi + jj][e] / g.temperature : -INFINITY;
+            mx = fmaxf(mx, l[jj]);
+            if (g.target != nullptr && row < g.M && col < g.N && g.target[row] == col) g.target_logit[row] = l[jj];
+          }
+#pragma unroll
+          for (int o = 16; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, WAVE));
+          float s = 0.f;
+#pragma unroll
+          for (int jj = 0; jj < 2; ++jj) s += (l[jj] == -INFINITY) ? 0.f : __expf(l[jj] - mx);
+#pragma unroll
+          for (int o = 16; o > 0; o >>= 1) s += __shfl_xor(s, o, WAVE);
+          if (frow == 0 && row < g.M && group < ngroups)
+            g.partial[(size_t)row * ngroups + group] = make_float2(mx, s);
         }
-#pragma unroll
-        for (int o = 16; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, WAVE));
-        float s = 0.f;
-#pragma unroll
-        for (int j = 0; j < TN; ++j) s += (l[j] == -INFINITY) ? 0.f : __expf(l[j] - mx);
-#pragma unroll
-        for (int o = 16; o > 0; o >>= 1) s += __shfl_xor(s, o, WAVE);
-        if (frow == 0 && row < g.M && group < ngroups)
-          g.partial[(size_t)row * ngroups + group] = make_float2(mx, s);
       }
     }
   } else {
@@ -184,6 +212,7 @@ __global__ __launch_bounds__(256) void gemm_f16_kernel(GemmArgs g) {
           } else if constexpr (EPI == EPI_SWIGLU_F16) {
             // weight rows come in blocks of 32: block 2b = gate rows [32b, 32b+32), block 2b+1 = the
             // matching up rows, so tile j (even) and tile j+1 hold gate and up of the same features.
+            static_assert(TN % 2 == 0, "a wave must own gate and up of the same features");
             if ((j & 1) == 0) {
               const float up = acc[i][j + 1 < TN ? j + 1 : j][e];
               const int f = ((wcol0 + j * 32) >> 1) + frow;
@@ -196,26 +225,72 @@ __global__ __launch_bounds__(256) void gemm_f16_kernel(GemmArgs g) {
   }
 }
 
-template <int BM, int BN, int EPI>
-hipError_t launch(const GemmArgs& g, hipStream_t s) {
+template <int BM, int BN, int WM, int WN, int EPI, bool KTAIL>
+hipError_t launch_k(const GemmArgs& g, hipStream_t s) {
+  constexpr size_t lds_bytes = 2 * (size_t)(BM + BN) * BK * sizeof(uint16_t);
+  static bool configured = false;
+  if (!configured) {
+    if (lds_bytes > 65536) {
+      hipError_t e = hipFuncSetAttribute((const void*)gemm_f16_kernel<BM, BN, WM, WN, EPI, KTAIL>,
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+      if (e != hipSuccess) return e;
+    }
+    configured = true;
+  }
   const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
-  hipLaunchKernelGGL((gemm_f16_kernel<BM, BN, EPI>), dim3(tiles), dim3(256), 0, s, g);
+  hipLaunchKernelGGL((gemm_f16_kernel<BM, BN, WM, WN, EPI, KTAIL>), dim3(tiles), dim3(WM * WN * 64), lds_bytes, s, g);
   return hipGetLastError();
+}
+
+template <int BM, int BN, int WM, int WN, int EPI>
+hipError_t launch(const GemmArgs& g, hipStream_t s) {
+  return g.K % BK == 0 ? launch_k<BM, BN, WM, WN, EPI, false>(g, s) : launch_k<BM, BN, WM, WN, EPI, true>(g, s);
+}
+
+template <int EPI>
+hipError_t launch_variant(const GemmArgs& g, int variant, hipStream_t s) {
+  switch (variant) {
+    case 0: return launch<128, 128, 2, 2, EPI>(g, s);
+    case 1: return launch<256, 128, 2, 2, EPI>(g, s);
+    case 2: return launch<256, 256, 2, 2, EPI>(g, s);
+    case 3: return launch<256, 256, 4, 2, EPI>(g, s);
+    case 4: return launch<128, 256, 2, 2, EPI>(g, s);
+    case 5: return launch<256, 128, 4, 2, EPI>(g, s);
+    case 6:
+      if constexpr (EPI == EPI_F32 || EPI == EPI_RESID || EPI == EPI_GELU_F16) return launch<128, 64, 2, 2, EPI>(g, s);
+      else return hipErrorInvalidValue;
+    case 7:
+      if constexpr (EPI == EPI_F32 || EPI == EPI_RESID || EPI == EPI_GELU_F16) return launch<64, 128, 1, 4, EPI>(g, s);
+      else return hipErrorInvalidValue;
+  }
+  return hipErrorInvalidValue;
 }
 
 }  // namespace
 
-hipError_t rl_gemm(const GemmArgs& g, int epi, hipStream_t s) {
+hipError_t rl_gemm_variant(const GemmArgs& g, int epi, int variant, hipStream_t s) {
   if (g.M <= 0 || g.N <= 0) return hipSuccess;
   if (g.K % 8 != 0 || g.lda % 8 != 0 || g.ldw % 8 != 0) return hipErrorInvalidValue;
   switch (epi) {
-    case EPI_F32: return launch<128, 128, EPI_F32>(g, s);
-    case EPI_RESID: return launch<128, 128, EPI_RESID>(g, s);
-    case EPI_GELU_F16: return launch<128, 128, EPI_GELU_F16>(g, s);
+    case EPI_F32: return launch_variant<EPI_F32>(g, variant, s);
+    case EPI_RESID: return launch_variant<EPI_RESID>(g, variant, s);
+    case EPI_GELU_F16: return launch_variant<EPI_GELU_F16>(g, variant, s);
     case EPI_SWIGLU_F16:
       if (g.N % 64 != 0) return hipErrorInvalidValue;
-      return launch<128, 128, EPI_SWIGLU_F16>(g, s);
-    case EPI_LMHEAD: return launch<128, 128, EPI_LMHEAD>(g, s);
+      return launch_variant<EPI_SWIGLU_F16>(g, variant, s);
+    case EPI_LMHEAD: return launch_variant<EPI_LMHEAD>(g, variant, s);
   }
   return hipErrorInvalidValue;
+}
+
+// Tile shape by problem size (measured on MI355X): the largest tile that still gives every CU work.
+hipError_t rl_gemm(const GemmArgs& g, int epi, hipStream_t s) {
+  auto tiles = [&](int bm, int bn) { return (long long)((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn); };
+  const bool wide_only = (epi == EPI_SWIGLU_F16 || epi == EPI_LMHEAD);   // a wave must own 64 columns
+  int variant;
+  if (tiles(256, 256) >= 160) variant = 3;
+  else if (tiles(256, 128) >= 200) variant = 5;
+  else if (tiles(128, 128) >= 400 || wide_only) variant = 0;
+  else variant = 7;
+  return rl_gemm_variant(g, epi, variant, s);
 }

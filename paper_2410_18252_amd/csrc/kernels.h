@@ -50,6 +50,8 @@ struct GemmArgs {
   float* target_logit;          // [M]
 };
 hipError_t rl_gemm(const GemmArgs& g, int epi, hipStream_t s);
+// the same with an explicit tile shape (tuning and tests): 0 = 128x128, 1 = 256x128, 2 = 256x256, ...
+hipError_t rl_gemm_variant(const GemmArgs& g, int epi, int variant, hipStream_t s);
 
 // ------------------------------------------------------------------ attention
 struct AttnJob { int cache_seq, row0, len, qblock; };   // prefill: 16 queries [16 qblock, 16 qblock + 16) of one sequence
