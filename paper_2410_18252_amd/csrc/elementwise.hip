@@ -135,12 +135,13 @@ __global__ __launch_bounds__(256) void norm_kernel(const float* x, const int* ro
 __global__ void rope_kv_kernel(RopeArgs a) {
   const int nch = a.h >> 3;
   const int slots = a.Hq + 2 * a.Hkv;
+  const int done = a.v_by_blocks ? a.Hq + a.Hkv : slots;     // head slots this kernel handles
   const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const size_t total = (size_t)a.rows * slots * nch;
+  const size_t total = (size_t)a.rows * done * nch;
   if (idx >= total) return;
   const int chunk = (int)(idx % nch);
-  const int slot = (int)((idx / nch) % slots);
-  const int row = (int)(idx / ((size_t)nch * slots));
+  const int slot = (int)((idx / nch) % done);
+  const int row = (int)(idx / ((size_t)nch * done));
   const float* src = a.qkv + (size_t)row * slots * a.h + (size_t)slot * a.h;
   const int pos = a.pos[row] + a.pos_add;
   const int half = a.r >> 1;
@@ -180,6 +181,35 @@ __global__ void rope_kv_kernel(RopeArgs a) {
       uint16_t* st = a.kv + a.lay.v_stream(off, cap, slot - a.Hq - a.Hkv);
 #pragma unroll
       for (int e = 0; e < 8; ++e) st[a.lay.v_elem(pos, chunk * 8 + e)] = f32_to_bf16_bits(v[e]);
+    }
+  }
+}
+
+// Prompt pass: values of 8 consecutive tokens of one sequence and one head dim form one 16-byte unit of
+// the cache layout, so one thread gathers them (coalesced across head dims) and writes the unit whole, to
+// every copy.  One block per 16-token job; slots past the prompt's end are written as zero (the decode
+// steps fill them later).
+__global__ __launch_bounds__(256) void rope_v_prefill_kernel(RopeArgs a) {
+  const AttnJob jb = a.jobs[blockIdx.x];
+  const int slots = a.Hq + 2 * a.Hkv;
+  const int per_group = a.Hkv * a.h;
+  const size_t ld = (size_t)slots * a.h;
+  for (int item = threadIdx.x; item < 2 * per_group; item += blockDim.x) {
+    const int grp = item / per_group, rem = item - grp * per_group;
+    const int head = rem / a.h, dim = rem - head * a.h;
+    const int pos0 = jb.qblock * 16 + grp * 8;
+    if (pos0 >= jb.len) continue;
+    const float* src = a.qkv + (size_t)(jb.row0 + pos0) * ld + (size_t)(a.Hq + a.Hkv + head) * a.h + dim;
+    float v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = pos0 + i < jb.len ? src[(size_t)i * ld] : 0.f;
+    u32x4 w;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) w[e] = pack_bf16x2(v[2 * e], v[2 * e + 1]);
+    for (int cpy = 0; cpy < a.ncopy; ++cpy) {
+      const int s = jb.cache_seq + cpy;
+      uint16_t* st = a.kv + a.lay.v_stream(a.kv_off[s], a.kv_cap[s], head);
+      *(u32x4*)(st + a.lay.v_elem(pos0, dim)) = w;
     }
   }
 }
@@ -257,9 +287,10 @@ hipError_t rl_norm(const float* x, const int* row_index, int rows, int d, float 
   return hipGetLastError();
 }
 hipError_t rl_rope_kv(const RopeArgs& a, hipStream_t s) {
-  const size_t total = (size_t)a.rows * (a.Hq + 2 * a.Hkv) * (a.h >> 3);
+  const size_t total = (size_t)a.rows * (a.v_by_blocks ? a.Hq + a.Hkv : a.Hq + 2 * a.Hkv) * (a.h >> 3);
   if (!total) return hipSuccess;
   hipLaunchKernelGGL(rope_kv_kernel, dim3(blocks_for(total)), dim3(TPB), 0, s, a);
+  if (a.v_by_blocks && a.njobs > 0) hipLaunchKernelGGL(rope_v_prefill_kernel, dim3(a.njobs), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 hipError_t rl_sequence_logprob(const float* tlp, const int* from, const int* lens, int N, int stride, float* out, hipStream_t s) {

@@ -106,6 +106,8 @@ struct RopeArgs {
   int pos_add;                   // added to pos[] (decode step)
   uint16_t* q;                   // out
   uint16_t* kv; KvLayout lay; const int* kv_off; const int* kv_cap;
+  // prompt pass: V is written by a second kernel, one block per 16-token job (dst_seq[row] == jobs[].cache_seq)
+  int v_by_blocks; const AttnJob* jobs; int njobs;
 };
 hipError_t rl_rope_kv(const RopeArgs& a, hipStream_t s);
 

@@ -265,7 +265,7 @@ int run_layers(rlgen_ctx* c, int rows, bool decode, int t, int ncopy, bool use_c
     r.qkv = c->qkv; r.rows = rows; r.Hq = m.n_q_heads; r.Hkv = m.n_kv_heads; r.h = h; r.r = m.rotary_dim;
     r.table = c->rope; r.q = c->q; r.kv = kvl; r.lay = c->lay; r.kv_off = c->d_kv_off; r.kv_cap = c->d_kv_cap;
     if (decode) { r.pos = c->d_ctx_base; r.pos_add = t - 1; r.dst_seq = c->d_iota; r.ncopy = 1; }
-    else { r.pos = c->d_pos; r.pos_add = 0; r.dst_seq = c->d_dst_seq; r.ncopy = ncopy; }
+    else { r.pos = c->d_pos; r.pos_add = 0; r.dst_seq = c->d_dst_seq; r.ncopy = ncopy; r.v_by_blocks = 1; r.jobs = c->d_jobs; r.njobs = njobs; }
     HIPCHK(rl_rope_kv(r, st));
     AttnArgs a{};
     a.q = c->q; a.q_ld = qd; a.out = c->attn; a.out_ld = qd; a.kv = kvl; a.lay = c->lay;
