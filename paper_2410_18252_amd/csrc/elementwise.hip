@@ -172,13 +172,13 @@ __global__ void rope_kv_kernel(RopeArgs a) {
     const long long off = a.kv_off[s];
     const int cap = a.kv_cap[s];
     if (!is_v) {
-      uint16_t* st = a.kv + a.lay.k_stream(off, cap, slot - a.Hq);
+      uint16_t* st = a.kv + a.lay.stream(off, cap, slot - a.Hq);
       u32x4 w;
 #pragma unroll
       for (int e = 0; e < 4; ++e) w[e] = pack_bf16x2(v[2 * e], v[2 * e + 1]);
       *(u32x4*)(st + a.lay.k_elem(pos, chunk * 8)) = w;
     } else {
-      uint16_t* st = a.kv + a.lay.v_stream(off, cap, slot - a.Hq - a.Hkv);
+      uint16_t* st = a.kv + a.lay.stream(off, cap, slot - a.Hq - a.Hkv);
 #pragma unroll
       for (int e = 0; e < 8; ++e) st[a.lay.v_elem(pos, chunk * 8 + e)] = f32_to_bf16_bits(v[e]);
     }
@@ -208,7 +208,7 @@ __global__ __launch_bounds__(256) void rope_v_prefill_kernel(RopeArgs a) {
     for (int e = 0; e < 4; ++e) w[e] = pack_bf16x2(v[2 * e], v[2 * e + 1]);
     for (int cpy = 0; cpy < a.ncopy; ++cpy) {
       const int s = jb.cache_seq + cpy;
-      uint16_t* st = a.kv + a.lay.v_stream(a.kv_off[s], a.kv_cap[s], head);
+      uint16_t* st = a.kv + a.lay.stream(a.kv_off[s], a.kv_cap[s], head);
       *(u32x4*)(st + a.lay.v_elem(pos0, dim)) = w;
     }
   }

@@ -3,35 +3,33 @@
 #include "common.h"
 
 // ------------------------------------------------------------------ KV cache layout
-// One stream per (layer, sequence, kv head): `cap` keys (a multiple of 32) of head_dim bf16 each,
-// K stream then V stream, cut into super-blocks of 32 keys.  Inside a super-block the elements are
-// ordered so that every MFMA operand fragment the attention kernel needs is one 16-byte unit and
-// every wave-wide load instruction reads one contiguous kilobyte:
+// One contiguous stream per (layer, sequence, kv head): `cap` keys (a multiple of 32), cut into
+// super-blocks of 32 keys; each super-block holds its 32 keys (32 h bf16) followed by its 32 values, so a
+// decode step reads the stream front to back.  Inside a super-block the elements are ordered so
+// that every MFMA operand fragment the attention kernel needs is one 16-byte unit and every
+// wave-wide load instruction reads one contiguous kilobyte:
 //   K super-block: [t = 0..1][chunk = 0..h/8-1][r = 0..15][8 head dims]
 //                  holding key 8 (r / 4) + 4 t + r % 4, head dims 8 chunk .. 8 chunk + 7
 //   V super-block: [tile = 0..h/16-1][g = 0..3][r = 0..15][8 keys]
 //                  holding head dim 16 tile + r, keys 8 g .. 8 g + 7
-// Streams of a sequence: K of head 0..Hkv-1, then V of head 0..Hkv-1; sequences follow each other
-// at token offsets kv_off[s]; layers are max_kv_tokens * Hkv * h * 2 elements apart.
+// Streams of a sequence: head 0..Hkv-1; sequences follow each other at token offsets kv_off[s];
+// layers are max_kv_tokens * Hkv * h * 2 elements apart.
 struct KvLayout {
   int Hkv, h;
   long long layer_stride;  // elements between layers
   __host__ __device__ long long seq_base(long long kv_off) const { return 2LL * kv_off * Hkv * h; }
-  __host__ __device__ long long k_stream(long long kv_off, int cap, int head) const {
-    return seq_base(kv_off) + (long long)head * cap * h;
+  __host__ __device__ long long stream(long long kv_off, int cap, int head) const {
+    return seq_base(kv_off) + (long long)head * 2 * cap * h;
   }
-  __host__ __device__ long long v_stream(long long kv_off, int cap, int head) const {
-    return seq_base(kv_off) + (long long)(Hkv + head) * cap * h;
-  }
-  // element offset of (key, dim) inside a K stream / V stream
+  // element offset of key / value (key, dim) inside a stream
   __host__ __device__ long long k_elem(int key, int dim) const {
     const int sb = key >> 5, kk = key & 31;
     const int r = 4 * (kk >> 3) + (kk & 3), t = (kk >> 2) & 1;
-    return (long long)sb * 32 * h + (((t * (h >> 3) + (dim >> 3)) * 16 + r) << 3) + (dim & 7);
+    return (long long)sb * 64 * h + (((t * (h >> 3) + (dim >> 3)) * 16 + r) << 3) + (dim & 7);
   }
   __host__ __device__ long long v_elem(int key, int dim) const {
     const int sb = key >> 5, kk = key & 31;
-    return (long long)sb * 32 * h + (((((dim >> 4) * 4 + (kk >> 3)) * 16) + (dim & 15)) << 3) + (kk & 7);
+    return (long long)sb * 64 * h + 32 * h + (((((dim >> 4) * 4 + (kk >> 3)) * 16) + (dim & 15)) << 3) + (kk & 7);
   }
 };
 
@@ -65,6 +63,7 @@ struct AttnArgs {
   float scale;
   // decode: one query row per sequence, keys 0 .. ctx_base[s] + ctx_add - 1
   const int* ctx_base; int ctx_add; int S;
+  const int* order;                   // nullable [S]: sequence handled by slot i
   // prefill
   const AttnJob* jobs; int njobs;
 };

@@ -5,6 +5,7 @@
 #include "../../include/rlgen.h"
 #include "kernels.h"
 
+#include <algorithm>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -61,7 +62,8 @@ struct rlgen_ctx {
   unsigned* status;
   // per-call metadata (device)
   SeqMeta* d_meta;
-  int *d_kv_off, *d_kv_cap, *d_ctx_base, *d_iota, *d_lastrow;
+  int *d_kv_off, *d_kv_cap, *d_ctx_base, *d_iota, *d_lastrow, *d_order;
+  bool use_order;
   int *d_tok_index, *d_pos, *d_dst_seq, *d_lm_row, *d_target, *d_out_index, *d_next_token;
   AttnJob* d_jobs;
   // activations
@@ -144,6 +146,7 @@ size_t carve(rlgen_ctx* c, char* base) {
   c->d_kv_off = k.take<int>(base, S); c->d_kv_cap = k.take<int>(base, S);
   c->d_ctx_base = k.take<int>(base, S); c->d_iota = k.take<int>(base, S);
   c->d_lastrow = k.take<int>(base, S); c->d_next_token = k.take<int>(base, S);
+  c->d_order = k.take<int>(base, S);
   c->d_tok_index = k.take<int>(base, R); c->d_pos = k.take<int>(base, R); c->d_dst_seq = k.take<int>(base, R);
   c->d_lm_row = k.take<int>(base, R); c->d_target = k.take<int>(base, R); c->d_out_index = k.take<int>(base, R);
   c->d_jobs = k.take<AttnJob>(base, R / 16 + S + 1);
@@ -271,7 +274,7 @@ int run_layers(rlgen_ctx* c, int rows, bool decode, int t, int ncopy, bool use_c
     a.q = c->q; a.q_ld = qd; a.out = c->attn; a.out_ld = qd; a.kv = kvl; a.lay = c->lay;
     a.kv_off = c->d_kv_off; a.kv_cap = c->d_kv_cap; a.Hq = m.n_q_heads; a.scale = 1.0f / sqrtf((float)h);
     if (decode) {
-      a.ctx_base = c->d_ctx_base; a.ctx_add = t; a.S = rows;
+      a.ctx_base = c->d_ctx_base; a.ctx_add = t; a.S = rows; a.order = c->use_order ? c->d_order : nullptr;
       hipEvent_t e0 = nullptr, e1 = nullptr;
       if (c->profiling) {
         while (c->prof_events.size() < c->prof_used + 2) {
@@ -346,7 +349,7 @@ int stage_begin(rlgen_ctx* c) {
 }
 
 struct Staged {
-  SeqMeta* meta; int *kv_off, *kv_cap, *ctx_base, *iota, *lastrow;
+  SeqMeta* meta; int *kv_off, *kv_cap, *ctx_base, *iota, *lastrow, *order;
 };
 Staged stage_views(rlgen_ctx* c) {
   const size_t S = c->cfg.max_seqs;
@@ -357,7 +360,8 @@ Staged stage_views(rlgen_ctx* c) {
   s.kv_cap = (int*)p; p += align_up(S * 4);
   s.ctx_base = (int*)p; p += align_up(S * 4);
   s.iota = (int*)p; p += align_up(S * 4);
-  s.lastrow = (int*)p;
+  s.lastrow = (int*)p; p += align_up(S * 4);
+  s.order = (int*)p;
   return s;
 }
 int stage_upload(rlgen_ctx* c, const Staged& s, int nmeta, int nseq, hipStream_t st) {
@@ -367,6 +371,7 @@ int stage_upload(rlgen_ctx* c, const Staged& s, int nmeta, int nseq, hipStream_t
   HIPCHK(hipMemcpyAsync(c->d_ctx_base, s.ctx_base, (size_t)nseq * 4, hipMemcpyHostToDevice, st));
   HIPCHK(hipMemcpyAsync(c->d_iota, s.iota, (size_t)nseq * 4, hipMemcpyHostToDevice, st));
   HIPCHK(hipMemcpyAsync(c->d_lastrow, s.lastrow, (size_t)nseq * 4, hipMemcpyHostToDevice, st));
+  HIPCHK(hipMemcpyAsync(c->d_order, s.order, (size_t)nseq * 4, hipMemcpyHostToDevice, st));
   HIPCHK(hipEventRecord(c->ev_meta, st));
   c->meta_pending = true;
   return RLGEN_OK;
@@ -410,7 +415,7 @@ int score_impl(rlgen_ctx* c, const int32_t* seqs, const int32_t* seq_lens, const
     e.row0 = cur.rows; e.len = len; e.src_off = n * stride; e.cache_seq = n; e.job0 = cur.jobs;
     e.lm0 = cur.lm_rows; e.score_from = from; e.out_off = n * stride;
     s.kv_off[n] = (int)kvtok; s.kv_cap[n] = round32(len);
-    s.ctx_base[n] = len; s.iota[n] = n; s.lastrow[n] = cur.rows + len - 1;
+    s.ctx_base[n] = len; s.iota[n] = n; s.lastrow[n] = cur.rows + len - 1; s.order[n] = n;
     kvtok += round32(len);
     cur.count++; cur.rows += len; cur.jobs += (len + 15) / 16; cur.lm_rows += nlm;
   }
@@ -487,7 +492,7 @@ int rlgen_create(const rlgen_model_cfg* cfg, const rlgen_weights* weights, void*
   carve(c, c->ws);
   hipStream_t st = (hipStream_t)hip_stream;
   const size_t S = cfg->max_seqs;
-  c->stage_bytes = align_up(S * sizeof(SeqMeta)) + 5 * align_up(S * 4);
+  c->stage_bytes = align_up(S * sizeof(SeqMeta)) + 6 * align_up(S * 4);
   auto fail = [&](int code) {
     rlgen_destroy(c);
     return code;
@@ -555,6 +560,11 @@ int rlgen_generate(rlgen_ctx* c, const int32_t* prompts, const int32_t* prompt_l
     cur.count++; cur.rows += len; cur.jobs += (len + 15) / 16;
   }
   chunks.push_back(cur);
+  // decode attention takes the sequences longest context first when there are few jobs per CU, so that the
+  // launch does not end on a handful of long ones
+  for (int q = 0; q < S; ++q) s.order[q] = q;
+  std::stable_sort(s.order, s.order + S, [&](int x, int y) { return s.ctx_base[x] > s.ctx_base[y]; });
+  c->use_order = (long long)S * m.n_kv_heads <= 8192;
   rc = stage_upload(c, s, B, S, st);
   if (rc) return rc;
   c->prof_used = 0;
