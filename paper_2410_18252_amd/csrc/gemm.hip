@@ -7,6 +7,7 @@
 // LDS (16-byte chunks, XOR-swizzled by row so that fragment reads spread over all banks) with
 // register prefetch of the next tile and one barrier per K step.
 #include "kernels.h"
+#include <algorithm>
 
 namespace {
 
@@ -22,12 +23,15 @@ __device__ __forceinline__ int swz(int r) { return (r >> SWZ_SHIFT) & 7; }
 // Blocks are handed to the 8 XCDs round-robin by the hardware.  Renumber them so that each XCD
 // (one L2) works on a contiguous range of logical tile ids, then walk tiles M-fastest inside groups
 // of 8 M-tiles: the blocks that share a weight tile run on the same L2 at the same time.
-__device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int& tm, int& tn) {
+// With split-K the `splits` blocks of one tile are neighbours in that order.
+__device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int splits, int& tm, int& tn, int& split) {
   const int nb = gridDim.x, bid = blockIdx.x;
   const int per = (nb + 7) >> 3;
   const int full = (nb & 7) == 0 ? 8 : (nb & 7);
   const int xcd = bid & 7, slot = bid >> 3;
-  const int logical = xcd < full ? xcd * per + slot : full * per + (xcd - full) * (per - 1) + slot;
+  int logical = xcd < full ? xcd * per + slot : full * per + (xcd - full) * (per - 1) + slot;
+  split = logical % splits;
+  logical /= splits;
   constexpr int GROUP_M = 8;
   const int per_group = GROUP_M * tiles_n;
   const int group = logical / per_group;
@@ -54,8 +58,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f16_kernel(GemmArgs g) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
-  int tile_m, tile_n;
-  tile_of_block(tiles_m, tiles_n, tile_m, tile_n);
+  int tile_m, tile_n, split;
+  const int splits = EPI == EPI_PARTIAL ? g.splits : 1;
+  tile_of_block(tiles_m, tiles_n, splits, tile_m, tile_n, split);
   const int row0 = tile_m * BM, col0 = tile_n * BN;
 
   // ---- global -> register staging: thread t covers chunk (t % 8) of rows (t / 8) + RPP i
@@ -112,13 +117,15 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f16_kernel(GemmArgs g) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  const int nk = (g.K + BK - 1) / BK;
-  load_global(0);
-  store_lds(0);
+  const int nk_all = (g.K + BK - 1) / BK;
+  const int kt0 = (int)((long long)split * nk_all / splits);          // this block's share of the K tiles
+  const int nk = (int)((long long)(split + 1) * nk_all / splits);
+  load_global(kt0 * BK);
+  store_lds(kt0 & 1);
   __syncthreads();
 
   const int frow = lane & 31, fhalf = lane >> 5;
-  for (int kt = 0; kt < nk; ++kt) {
+  for (int kt = kt0; kt < nk; ++kt) {
     const int cur = kt & 1;
     if (kt + 1 < nk) load_global((kt + 1) * BK);
     const uint16_t* la = lds + cur * STAGE + (wm * (BM / WM)) * BK;
@@ -202,7 +209,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f16_kernel(GemmArgs g) {
           const int row = wrow0 + i * 32 + 8 * (e >> 2) + 4 * fhalf + (e & 3);
           if (row >= g.M) continue;
           float v = acc[i][j][e] + b;
-          if constexpr (EPI == EPI_F32) {
+          if constexpr (EPI == EPI_PARTIAL) {
+            g.ws[((size_t)split * g.M + row) * g.N + col] = acc[i][j][e];
+          } else if constexpr (EPI == EPI_F32) {
             ((float*)g.out)[(size_t)row * g.ldo + col] = v;
           } else if constexpr (EPI == EPI_RESID) {
             float* p = (float*)g.out + (size_t)row * g.ldo + col;
@@ -225,6 +234,27 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f16_kernel(GemmArgs g) {
   }
 }
 
+// Second half of a split-K product: sums the partial results in split order (so the result does not depend
+// on scheduling) and applies the epilogue.
+template <int EPI>
+__global__ void splitk_epilogue_kernel(GemmArgs g) {
+  const size_t n = (size_t)g.M * g.N;
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const int row = (int)(i / g.N), col = (int)(i % g.N);
+  float v = 0.f;
+  for (int sp = 0; sp < g.splits; ++sp) v += g.ws[(size_t)sp * n + i];
+  if (g.bias) v += g.bias[col];
+  if constexpr (EPI == EPI_F32) {
+    ((float*)g.out)[(size_t)row * g.ldo + col] = v;
+  } else if constexpr (EPI == EPI_RESID) {
+    float* p = (float*)g.out + (size_t)row * g.ldo + col;
+    *p = *p + v;
+  } else if constexpr (EPI == EPI_GELU_F16) {
+    ((uint16_t*)g.out)[(size_t)row * g.ldo + col] = f32_to_f16_bits(gelu_erf(v));
+  }
+}
+
 template <int BM, int BN, int WM, int WN, int EPI, bool KTAIL>
 hipError_t launch_k(const GemmArgs& g, hipStream_t s) {
   constexpr size_t lds_bytes = 2 * (size_t)(BM + BN) * BK * sizeof(uint16_t);
@@ -237,7 +267,7 @@ hipError_t launch_k(const GemmArgs& g, hipStream_t s) {
     }
     configured = true;
   }
-  const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
+  const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN) * (EPI == EPI_PARTIAL ? g.splits : 1);
   hipLaunchKernelGGL((gemm_f16_kernel<BM, BN, WM, WN, EPI, KTAIL>), dim3(tiles), dim3(WM * WN * 64), lds_bytes, s, g);
   return hipGetLastError();
 }
@@ -257,10 +287,10 @@ hipError_t launch_variant(const GemmArgs& g, int variant, hipStream_t s) {
     case 4: return launch<128, 256, 2, 2, EPI>(g, s);
     case 5: return launch<256, 128, 4, 2, EPI>(g, s);
     case 6:
-      if constexpr (EPI == EPI_F32 || EPI == EPI_RESID || EPI == EPI_GELU_F16) return launch<128, 64, 2, 2, EPI>(g, s);
+      if constexpr (EPI != EPI_SWIGLU_F16 && EPI != EPI_LMHEAD) return launch<128, 64, 2, 2, EPI>(g, s);
       else return hipErrorInvalidValue;
     case 7:
-      if constexpr (EPI == EPI_F32 || EPI == EPI_RESID || EPI == EPI_GELU_F16) return launch<64, 128, 1, 4, EPI>(g, s);
+      if constexpr (EPI != EPI_SWIGLU_F16 && EPI != EPI_LMHEAD) return launch<64, 128, 1, 4, EPI>(g, s);
       else return hipErrorInvalidValue;
   }
   return hipErrorInvalidValue;
@@ -279,8 +309,24 @@ hipError_t rl_gemm_variant(const GemmArgs& g, int epi, int variant, hipStream_t 
       if (g.N % 64 != 0) return hipErrorInvalidValue;
       return launch_variant<EPI_SWIGLU_F16>(g, variant, s);
     case EPI_LMHEAD: return launch_variant<EPI_LMHEAD>(g, variant, s);
+    case EPI_PARTIAL: return launch_variant<EPI_PARTIAL>(g, variant, s);
   }
   return hipErrorInvalidValue;
+}
+
+// Split-K: `splits` blocks per tile each take a share of K and write fp32 partial tiles to g.ws
+// ([splits, M, N]); a second kernel adds them in order and applies the epilogue.
+hipError_t rl_gemm_splitk(const GemmArgs& g, int epi, int variant, hipStream_t s) {
+  if (g.M <= 0 || g.N <= 0) return hipSuccess;
+  if (g.splits < 2 || !g.ws || (epi != EPI_F32 && epi != EPI_RESID && epi != EPI_GELU_F16)) return hipErrorInvalidValue;
+  hipError_t e = rl_gemm_variant(g, EPI_PARTIAL, variant, s);
+  if (e != hipSuccess) return e;
+  const size_t n = (size_t)g.M * g.N;
+  const dim3 grid((unsigned)((n + 255) / 256)), block(256);
+  if (epi == EPI_F32) hipLaunchKernelGGL(splitk_epilogue_kernel<EPI_F32>, grid, block, 0, s, g);
+  else if (epi == EPI_RESID) hipLaunchKernelGGL(splitk_epilogue_kernel<EPI_RESID>, grid, block, 0, s, g);
+  else hipLaunchKernelGGL(splitk_epilogue_kernel<EPI_GELU_F16>, grid, block, 0, s, g);
+  return hipGetLastError();
 }
 
 // Tile shape by problem size (measured on MI355X): the largest tile that still gives every CU work.
@@ -292,5 +338,20 @@ hipError_t rl_gemm(const GemmArgs& g, int epi, hipStream_t s) {
   else if (tiles(256, 128) >= 200) variant = 5;
   else if (tiles(128, 128) >= 400 || wide_only) variant = 0;
   else variant = 7;
+  if (variant == 7 && g.ws) {
+    // few 64x128 tiles (three fit on a CU): cut K so that about 800 blocks exist, each keeping >= 4 K tiles;
+    // with more than one tile per CU already, only a long K is worth the second pass over the partial sums
+    const long long t = tiles(64, 128);
+    const int nk = (g.K + BK - 1) / BK;
+    long long splits = (t <= 256 || (t <= 400 && nk >= 96)) ? (800 + t / 2) / t : 1;
+    splits = std::min<long long>(splits, 8);
+    splits = std::min<long long>(splits, nk / (t <= 256 ? 4 : 8));
+    splits = std::min<long long>(splits, (long long)(g.ws_elems / ((size_t)g.M * g.N)));
+    if (splits >= 2) {
+      GemmArgs h = g;
+      h.splits = (int)splits;
+      return rl_gemm_splitk(h, epi, 7, s);
+    }
+  }
   return rl_gemm_variant(g, epi, variant, s);
 }

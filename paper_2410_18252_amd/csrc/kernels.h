@@ -34,7 +34,7 @@ struct KvLayout {
 };
 
 // ------------------------------------------------------------------ GEMM
-enum { EPI_F32 = 0, EPI_RESID = 1, EPI_GELU_F16 = 2, EPI_SWIGLU_F16 = 3, EPI_LMHEAD = 4 };
+enum { EPI_F32 = 0, EPI_RESID = 1, EPI_GELU_F16 = 2, EPI_SWIGLU_F16 = 3, EPI_LMHEAD = 4, EPI_PARTIAL = 5 };
 struct GemmArgs {
   const void* A; int lda;       // [M, K] fp16
   const void* W; int ldw;       // [N, K] fp16
@@ -46,10 +46,13 @@ struct GemmArgs {
   float2* partial;              // [M, ceil(N/64)] (max, sum exp) of the tempered logits per 64 columns
   const int* target;            // nullable [M]: column whose tempered logit is captured
   float* target_logit;          // [M]
+  // split-K scratch (nullable: no split-K): fp32 [splits, M, N], ws_elems floats available
+  float* ws; size_t ws_elems; int splits;
 };
 hipError_t rl_gemm(const GemmArgs& g, int epi, hipStream_t s);
 // the same with an explicit tile shape (tuning and tests): 0 = 128x128, 1 = 256x128, 2 = 256x256, ...
 hipError_t rl_gemm_variant(const GemmArgs& g, int epi, int variant, hipStream_t s);
+hipError_t rl_gemm_splitk(const GemmArgs& g, int epi, int variant, hipStream_t s);   // needs g.ws, g.splits >= 2
 
 // ------------------------------------------------------------------ attention
 struct AttnJob { int cache_seq, row0, len, qblock; };   // prefill: 16 queries [16 qblock, 16 qblock + 16) of one sequence

@@ -67,7 +67,8 @@ struct rlgen_ctx {
   int *d_tok_index, *d_pos, *d_dst_seq, *d_lm_row, *d_target, *d_out_index, *d_next_token;
   AttnJob* d_jobs;
   // activations
-  float *x, *qkv, *target_logit;
+  float *x, *qkv, *target_logit, *splitk;
+  size_t splitk_elems;
   uint16_t *n1, *n2, *q, *attn, *act, *hfin;
   float2* partial;
   // host staging (pinned)
@@ -160,6 +161,8 @@ size_t carve(rlgen_ctx* c, char* base) {
   c->hfin = k.take<uint16_t>(base, LM * d);
   c->partial = k.take<float2>(base, LM * (size_t)c->ngroups);
   c->target_logit = k.take<float>(base, LM);
+  c->splitk_elems = (size_t)12 << 20;          // 48 MB of split-K partial sums
+  c->splitk = k.take<float>(base, c->splitk_elems);
   return k.off;
 }
 
@@ -262,7 +265,7 @@ int run_layers(rlgen_ctx* c, int rows, bool decode, int t, int ncopy, bool use_c
     else HIPCHK(rl_norm(c->x, nullptr, rows, d, m.norm_eps, L.n1g, L.n1b, c->n1, L.n2g, L.n2b, c->n2, st));
     GemmArgs g{};
     g.A = c->n1; g.lda = d; g.W = L.wqkv; g.ldw = d; g.M = rows; g.N = nqkv; g.K = d;
-    g.bias = llama ? nullptr : L.bqkv; g.out = c->qkv; g.ldo = nqkv;
+    g.bias = llama ? nullptr : L.bqkv; g.out = c->qkv; g.ldo = nqkv; g.ws = c->splitk; g.ws_elems = c->splitk_elems;
     HIPCHK(rl_gemm(g, EPI_F32, st));
     RopeArgs r{};
     r.qkv = c->qkv; r.rows = rows; r.Hq = m.n_q_heads; r.Hkv = m.n_kv_heads; r.h = h; r.r = m.rotary_dim;
@@ -294,16 +297,16 @@ int run_layers(rlgen_ctx* c, int rows, bool decode, int t, int ncopy, bool use_c
     }
     g = GemmArgs{};
     g.A = c->attn; g.lda = qd; g.W = L.wo; g.ldw = qd; g.M = rows; g.N = d; g.K = qd;
-    g.bias = llama ? nullptr : L.bo; g.out = c->x; g.ldo = d;
+    g.bias = llama ? nullptr : L.bo; g.out = c->x; g.ldo = d; g.ws = c->splitk; g.ws_elems = c->splitk_elems;
     HIPCHK(rl_gemm(g, EPI_RESID, st));
     if (llama) HIPCHK(rl_norm(c->x, nullptr, rows, d, m.norm_eps, L.n2g, nullptr, c->n2, nullptr, nullptr, nullptr, st));
     g = GemmArgs{};
     g.A = c->n2; g.lda = d; g.W = L.wup; g.ldw = d; g.M = rows; g.N = llama ? 2 * F : F; g.K = d;
-    g.bias = llama ? nullptr : L.bup; g.out = c->act; g.ldo = F;
+    g.bias = llama ? nullptr : L.bup; g.out = c->act; g.ldo = F; g.ws = c->splitk; g.ws_elems = c->splitk_elems;
     HIPCHK(rl_gemm(g, llama ? EPI_SWIGLU_F16 : EPI_GELU_F16, st));
     g = GemmArgs{};
     g.A = c->act; g.lda = F; g.W = L.wdown; g.ldw = F; g.M = rows; g.N = d; g.K = F;
-    g.bias = llama ? nullptr : L.bdown; g.out = c->x; g.ldo = d;
+    g.bias = llama ? nullptr : L.bdown; g.out = c->x; g.ldo = d; g.ws = c->splitk; g.ws_elems = c->splitk_elems;
     HIPCHK(rl_gemm(g, EPI_RESID, st));
   }
   return RLGEN_OK;
