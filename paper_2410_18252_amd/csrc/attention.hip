@@ -171,13 +171,12 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a) {
   lsum += __shfl_xor(lsum, 32, WAVE);
   const float inv = 1.0f / lsum;
   if (store_col) {
-    uint16_t* op = a.out + (size_t)qrow * a.out_ld + qhead * HD;
 #pragma unroll
     for (int t = 0; t < VT; ++t) {
       u32x2 w;
       w[0] = pack_f16x2(o[t][0] * inv, o[t][1] * inv);
       w[1] = pack_f16x2(o[t][2] * inv, o[t][3] * inv);
-      *(u32x2*)(op + 16 * t + 4 * g) = w;
+      *(u32x2*)(a.out + kblk_off(qrow, qhead * HD + 16 * t + 4 * g, a.out_rows)) = w;
     }
   }
 }

@@ -15,6 +15,16 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 #define WAVE 64
 
+// GEMM operands (weights and fp16 activations) are stored "K-block major": a matrix X[rows, K] is laid out
+// as [ceil(K / 64)][rows][64], so the 64 K-values of a row are 128 contiguous bytes and the tile a GEMM block
+// stages (BM rows x 64) is one contiguous run.  A wave-wide 16-byte-per-lane load then reads one contiguous
+// kilobyte, which the texture path of gfx950 serves about twice as fast as eight separate 128-byte row
+// pieces (measured: 34 vs 16 bytes/clk/CU from L2 at 4 waves per CU).
+__host__ __device__ __forceinline__ size_t kblk_off(int row, int col, int rows) {
+  return ((size_t)(col >> 6) * rows + row) * 64 + (col & 63);
+}
+__host__ __device__ __forceinline__ size_t kblk_elems(size_t rows, size_t K) { return ((K + 63) / 64) * rows * 64; }
+
 // fp32 -> bf16, round to nearest even (finite inputs; NaN stays NaN).
 __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
   uint32_t u = __float_as_uint(f);

@@ -13,12 +13,12 @@ __global__ void to_bf16_kernel(uint16_t* dst, const void* src, int src_is_bf16, 
   for (; i < n; i += stride)
     dst[i] = src_is_bf16 ? ((const uint16_t*)src)[i] : f32_to_bf16_bits(((const float*)src)[i]);
 }
-__global__ void to_f16w_kernel(uint16_t* dst, const void* src, int src_is_bf16, size_t n) {
+__global__ void to_f16w_kernel(uint16_t* dst, const void* src, int src_is_bf16, int rows, int K, int rows_total, int row0) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  const size_t n = (size_t)rows * K, stride = (size_t)gridDim.x * blockDim.x;
   for (; i < n; i += stride) {
     const uint16_t b = src_is_bf16 ? ((const uint16_t*)src)[i] : f32_to_bf16_bits(((const float*)src)[i]);
-    dst[i] = f32_to_f16_bits(bf16_bits_to_f32(b));
+    dst[kblk_off(row0 + (int)(i / K), (int)(i % K), rows_total)] = f32_to_f16_bits(bf16_bits_to_f32(b));
   }
 }
 __global__ void to_f32_kernel(float* dst, const void* src, int src_is_bf16, size_t n) {
@@ -36,7 +36,7 @@ __global__ void pack_gate_up_kernel(uint16_t* dst, const void* gate, const void*
     const void* src = (blk & 1) ? up : gate;
     const size_t si = (size_t)((blk >> 1) * 32 + in) * d + col;
     const uint16_t b = src_is_bf16 ? ((const uint16_t*)src)[si] : f32_to_bf16_bits(((const float*)src)[si]);
-    dst[i] = f32_to_f16_bits(bf16_bits_to_f32(b));
+    dst[kblk_off(row, col, 2 * F)] = f32_to_f16_bits(bf16_bits_to_f32(b));
   }
 }
 __global__ void rope_table_kernel(float2* tab, int max_pos, int r, double theta) {
@@ -80,7 +80,8 @@ __global__ void embed_kernel(float* x, const uint16_t* E, const int* tokens, con
 template <int NV>
 __global__ __launch_bounds__(256) void norm_kernel(const float* x, const int* row_index, int rows, int d, float eps,
                                                    const float* g1, const float* b1, uint16_t* out1,
-                                                   const float* g2, const float* b2, uint16_t* out2) {
+                                                   const float* g2, const float* b2, uint16_t* out2,
+                                                   int out_rows, int out_row0) {
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
@@ -118,14 +119,14 @@ __global__ __launch_bounds__(256) void norm_kernel(const float* x, const int* ro
     u32x2 w;
     w[0] = pack_f16x2(v[i][0] * rstd * ga[0] + ba[0], v[i][1] * rstd * ga[1] + ba[1]);
     w[1] = pack_f16x2(v[i][2] * rstd * ga[2] + ba[2], v[i][3] * rstd * ga[3] + ba[3]);
-    *(u32x2*)(out1 + (size_t)row * d + col) = w;
+    *(u32x2*)(out1 + kblk_off(out_row0 + row, col, out_rows)) = w;
     if (out2) {
       const f32x4 gb = *(const f32x4*)(g2 + col);
       f32x4 bb = f32x4{0.f, 0.f, 0.f, 0.f};
       if (b2) bb = *(const f32x4*)(b2 + col);
       w[0] = pack_f16x2(v[i][0] * rstd * gb[0] + bb[0], v[i][1] * rstd * gb[1] + bb[1]);
       w[1] = pack_f16x2(v[i][2] * rstd * gb[2] + bb[2], v[i][3] * rstd * gb[3] + bb[3]);
-      *(u32x2*)(out2 + (size_t)row * d + col) = w;
+      *(u32x2*)(out2 + kblk_off(out_row0 + row, col, out_rows)) = w;
     }
   }
 }
@@ -237,9 +238,10 @@ hipError_t rl_to_bf16(uint16_t* dst, const void* src, int src_is_bf16, size_t n,
   hipLaunchKernelGGL(to_bf16_kernel, dim3(min(blocks_for(n), 65536)), dim3(TPB), 0, s, dst, src, src_is_bf16, n);
   return hipGetLastError();
 }
-hipError_t rl_to_f16w(uint16_t* dst, const void* src, int src_is_bf16, size_t n, hipStream_t s) {
+hipError_t rl_to_f16w(uint16_t* dst, const void* src, int src_is_bf16, int rows, int K, int rows_total, int row0, hipStream_t s) {
+  const size_t n = (size_t)rows * K;
   if (!n) return hipSuccess;
-  hipLaunchKernelGGL(to_f16w_kernel, dim3(min(blocks_for(n), 65536)), dim3(TPB), 0, s, dst, src, src_is_bf16, n);
+  hipLaunchKernelGGL(to_f16w_kernel, dim3(min(blocks_for(n), 65536)), dim3(TPB), 0, s, dst, src, src_is_bf16, rows, K, rows_total, row0);
   return hipGetLastError();
 }
 hipError_t rl_to_f32(float* dst, const void* src, int src_is_bf16, size_t n, hipStream_t s) {
@@ -271,11 +273,12 @@ hipError_t rl_embed(float* x, const uint16_t* E, const int* tokens, const int* t
   return hipGetLastError();
 }
 hipError_t rl_norm(const float* x, const int* row_index, int rows, int d, float eps, const float* g1, const float* b1,
-                   uint16_t* out1, const float* g2, const float* b2, uint16_t* out2, hipStream_t s) {
+                   uint16_t* out1, const float* g2, const float* b2, uint16_t* out2, int out_rows, int out_row0,
+                   hipStream_t s) {
   if (rows <= 0) return hipSuccess;
   const dim3 grid((rows + 3) / 4), block(256);
   const int nv = (d + 255) / 256;
-#define NORM(NV) hipLaunchKernelGGL((norm_kernel<NV>), grid, block, 0, s, x, row_index, rows, d, eps, g1, b1, out1, g2, b2, out2)
+#define NORM(NV) hipLaunchKernelGGL((norm_kernel<NV>), grid, block, 0, s, x, row_index, rows, d, eps, g1, b1, out1, g2, b2, out2, out_rows, out_row0)
   if (nv <= 1) NORM(1);
   else if (nv <= 2) NORM(2);
   else if (nv <= 4) NORM(4);

@@ -1,8 +1,8 @@
 // fp16 x fp16 -> fp32 GEMM on the gfx950 matrix cores, C[M,N] = A[M,K] . W[N,K]^T, with the
 // epilogues the decoder needs fused in.  (Weights are the caller's bf16 values held in fp16, which
 // represents them exactly; activations are fp16, whose 11 significant bits keep the logits within
-// the parity bound where bf16 activations do not.)  Both operands are K-contiguous, so every MFMA operand
-// fragment is one 16-byte load.  256 threads = 4 waves in a 2x2 arrangement; each wave owns a
+// the parity bound where bf16 activations do not.)  Both operands are K-block major (see kblk_off), so a block's
+// tile is one contiguous run in memory and every MFMA operand fragment is one 16-byte LDS read.  256 threads = 4 waves in a 2x2 arrangement; each wave owns a
 // (BM/2)x(BN/2) sub-tile built from 32x32x16 MFMAs; A and W tiles of depth 64 are staged through
 // LDS (16-byte chunks, XOR-swizzled by row so that fragment reads spread over all banks) with
 // register prefetch of the next tile and one barrier per K step.
@@ -67,31 +67,34 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f16_kernel(GemmArgs g) {
   const int ld_chunk = tid & 7, ld_row = tid >> 3;
   const uint16_t* __restrict__ A = (const uint16_t*)g.A;
   const uint16_t* __restrict__ W = (const uint16_t*)g.W;
+  // operands are K-block major: K tile kt of rows r0.. is the contiguous run starting at (kt * rows + r0) * 64,
+  // and thread t reads bytes [16 t, 16 t + 16) of it (rows past the end repeat the last row)
   u32x4 ra[PA], rb[PB];
   const uint16_t* pa[PA];
   const uint16_t* pb[PB];
 #pragma unroll
   for (int i = 0; i < PA; ++i) {
     int r = min(row0 + ld_row + RPP * i, g.M - 1);
-    pa[i] = A + (size_t)r * g.lda + ld_chunk * 8;
+    pa[i] = A + (size_t)r * 64 + ld_chunk * 8;
   }
 #pragma unroll
   for (int i = 0; i < PB; ++i) {
     int r = min(col0 + ld_row + RPP * i, g.N - 1);
-    pb[i] = W + (size_t)r * g.ldw + ld_chunk * 8;
+    pb[i] = W + (size_t)r * 64 + ld_chunk * 8;
   }
-  auto load_global = [&](int k0) {
+  const size_t ka = (size_t)g.M * 64, kw = (size_t)g.N * 64;    // elements between K tiles
+  auto load_global = [&](int kt) {
     if constexpr (KTAIL) {     // K is not a multiple of BK: chunks beyond K read as zero
-      const bool ok = k0 + ld_chunk * 8 < g.K;
+      const bool ok = kt * BK + ld_chunk * 8 < g.K;
 #pragma unroll
-      for (int i = 0; i < PA; ++i) ra[i] = ok ? *(const u32x4*)(pa[i] + k0) : u32x4{0, 0, 0, 0};
+      for (int i = 0; i < PA; ++i) ra[i] = ok ? *(const u32x4*)(pa[i] + kt * ka) : u32x4{0, 0, 0, 0};
 #pragma unroll
-      for (int i = 0; i < PB; ++i) rb[i] = ok ? *(const u32x4*)(pb[i] + k0) : u32x4{0, 0, 0, 0};
+      for (int i = 0; i < PB; ++i) rb[i] = ok ? *(const u32x4*)(pb[i] + kt * kw) : u32x4{0, 0, 0, 0};
     } else {
 #pragma unroll
-      for (int i = 0; i < PA; ++i) ra[i] = *(const u32x4*)(pa[i] + k0);
+      for (int i = 0; i < PA; ++i) ra[i] = *(const u32x4*)(pa[i] + kt * ka);
 #pragma unroll
-      for (int i = 0; i < PB; ++i) rb[i] = *(const u32x4*)(pb[i] + k0);
+      for (int i = 0; i < PB; ++i) rb[i] = *(const u32x4*)(pb[i] + kt * kw);
     }
   };
   auto store_lds = [&](int buf) {
@@ -120,14 +123,14 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f16_kernel(GemmArgs g) {
   const int nk_all = (g.K + BK - 1) / BK;
   const int kt0 = (int)((long long)split * nk_all / splits);          // this block's share of the K tiles
   const int nk = (int)((long long)(split + 1) * nk_all / splits);
-  load_global(kt0 * BK);
+  load_global(kt0);
   store_lds(kt0 & 1);
   __syncthreads();
 
   const int frow = lane & 31, fhalf = lane >> 5;
   for (int kt = kt0; kt < nk; ++kt) {
     const int cur = kt & 1;
-    if (kt + 1 < nk) load_global((kt + 1) * BK);
+    if (kt + 1 < nk) load_global(kt + 1);
     const uint16_t* la = lds + cur * STAGE + (wm * (BM / WM)) * BK;
     const uint16_t* lb = lds + cur * STAGE + BM * BK + (wn * (BN / WN)) * BK;
     // fragments of step kk + 1 are fetched from LDS while the MFMAs of step kk run; the next tile moves
@@ -217,7 +220,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f16_kernel(GemmArgs g) {
             float* p = (float*)g.out + (size_t)row * g.ldo + col;
             *p = *p + v;
           } else if constexpr (EPI == EPI_GELU_F16) {
-            ((uint16_t*)g.out)[(size_t)row * g.ldo + col] = f32_to_f16_bits(gelu_erf(v));
+            ((uint16_t*)g.out)[kblk_off(row, col, g.M)] = f32_to_f16_bits(gelu_erf(v));
           } else if constexpr (EPI == EPI_SWIGLU_F16) {
             // weight rows come in blocks of 32: block 2b = gate rows [32b, 32b+32), block 2b+1 = the
             // matching up rows, so tile j (even) and tile j+1 hold gate and up of the same features.
@@ -225,7 +228,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f16_kernel(GemmArgs g) {
             if ((j & 1) == 0) {
               const float up = acc[i][j + 1 < TN ? j + 1 : j][e];
               const int f = ((wcol0 + j * 32) >> 1) + frow;
-              ((uint16_t*)g.out)[(size_t)row * g.ldo + f] = f32_to_f16_bits(silu(v) * up);
+              ((uint16_t*)g.out)[kblk_off(row, f, g.M)] = f32_to_f16_bits(silu(v) * up);
             }
           }
         }
@@ -251,7 +254,7 @@ __global__ void splitk_epilogue_kernel(GemmArgs g) {
     float* p = (float*)g.out + (size_t)row * g.ldo + col;
     *p = *p + v;
   } else if constexpr (EPI == EPI_GELU_F16) {
-    ((uint16_t*)g.out)[(size_t)row * g.ldo + col] = f32_to_f16_bits(gelu_erf(v));
+    ((uint16_t*)g.out)[kblk_off(row, col, g.M)] = f32_to_f16_bits(gelu_erf(v));
   }
 }
 
@@ -300,7 +303,7 @@ hipError_t launch_variant(const GemmArgs& g, int variant, hipStream_t s) {
 
 hipError_t rl_gemm_variant(const GemmArgs& g, int epi, int variant, hipStream_t s) {
   if (g.M <= 0 || g.N <= 0) return hipSuccess;
-  if (g.K % 8 != 0 || g.lda % 8 != 0 || g.ldw % 8 != 0) return hipErrorInvalidValue;
+  if (g.K % 8 != 0) return hipErrorInvalidValue;
   switch (epi) {
     case EPI_F32: return launch_variant<EPI_F32>(g, variant, s);
     case EPI_RESID: return launch_variant<EPI_RESID>(g, variant, s);

@@ -36,11 +36,12 @@ struct KvLayout {
 // ------------------------------------------------------------------ GEMM
 enum { EPI_F32 = 0, EPI_RESID = 1, EPI_GELU_F16 = 2, EPI_SWIGLU_F16 = 3, EPI_LMHEAD = 4, EPI_PARTIAL = 5 };
 struct GemmArgs {
-  const void* A; int lda;       // [M, K] fp16
-  const void* W; int ldw;       // [N, K] fp16
+  const void* A;                // [M, K] fp16, K-block major (kblk_off with rows = M)
+  const void* W;                // [N, K] fp16, K-block major (rows = N)
   int M, N, K;
   const float* bias;            // [N] or null
-  void* out; int ldo;           // EPI_F32 / EPI_RESID: fp32 [M, N]; *_F16: fp16
+  void* out; int ldo;           // EPI_F32 / EPI_RESID: fp32 [M, N] row-major, leading dim ldo;
+                                // *_F16: fp16 K-block major with rows = M (ldo unused)
   // EPI_LMHEAD only
   float temperature;
   float2* partial;              // [M, ceil(N/64)] (max, sum exp) of the tempered logits per 64 columns
@@ -58,7 +59,7 @@ hipError_t rl_gemm_splitk(const GemmArgs& g, int epi, int variant, hipStream_t s
 struct AttnJob { int cache_seq, row0, len, qblock; };   // prefill: 16 queries [16 qblock, 16 qblock + 16) of one sequence
 struct AttnArgs {
   const uint16_t* q; int q_ld;        // fp16 [rows, Hq * h], rotated
-  uint16_t* out; int out_ld;          // fp16 [rows, Hq * h]
+  uint16_t* out; int out_rows;        // fp16 [out_rows, Hq * h], K-block major (input of the O projection)
   const uint16_t* kv;                 // this layer's cache base
   KvLayout lay;
   const int* kv_off; const int* kv_cap;  // per cache sequence
@@ -76,11 +77,12 @@ hipError_t rl_attention_prefill(const AttnArgs& a, hipStream_t s);
 // ------------------------------------------------------------------ element-wise and small kernels
 // dst bf16 <- src (fp32 rounded to nearest even, or bf16 copied); n elements
 hipError_t rl_to_bf16(uint16_t* dst, const void* src, int src_is_bf16, size_t n, hipStream_t s);
-// dst fp16 <- the bf16 value of src (fp32 sources are first rounded to bf16, nearest even); n elements
-hipError_t rl_to_f16w(uint16_t* dst, const void* src, int src_is_bf16, size_t n, hipStream_t s);
+// dst fp16 K-block major [rows_total, K] <- the bf16 values of src [rows, K] row-major placed at rows
+// row0 .. row0 + rows - 1 (fp32 sources are first rounded to bf16, nearest even)
+hipError_t rl_to_f16w(uint16_t* dst, const void* src, int src_is_bf16, int rows, int K, int rows_total, int row0, hipStream_t s);
 // dst fp32 <- src (fp32 copied, or bf16 expanded); n elements
 hipError_t rl_to_f32(float* dst, const void* src, int src_is_bf16, size_t n, hipStream_t s);
-// gate/up rows interleaved in blocks of 32 rows: dst [2F, d] fp16 (bf16 values)
+// gate/up rows interleaved in blocks of 32 rows: dst [2F, d] fp16 (bf16 values), K-block major
 hipError_t rl_pack_gate_up(uint16_t* dst, const void* gate, const void* up, int src_is_bf16, int F, int d, hipStream_t s);
 // cos/sin table [max_pos, r/2] (float2), angles pos * theta^(-2i/r) evaluated in fp64
 hipError_t rl_rope_table(float2* tab, int max_pos, int rotary_dim, float theta, hipStream_t s);
@@ -91,9 +93,10 @@ hipError_t rl_embed(float* x, const uint16_t* E, const int* tokens, const int* t
                     int vocab, unsigned* status, hipStream_t s);
 // LayerNorm / RMSNorm of fp32 rows into fp16.  out2/g2/b2 nullable (second normalisation of the same
 // row with other gains, NeoX); b1 null selects RMSNorm.  row_index nullable: source row of output row i.
+// Outputs are K-block major matrices of out_rows rows; output row i goes to row out_row0 + i.
 hipError_t rl_norm(const float* x, const int* row_index, int rows, int d, float eps, const float* g1,
                    const float* b1, uint16_t* out1, const float* g2, const float* b2, uint16_t* out2,
-                   hipStream_t s);
+                   int out_rows, int out_row0, hipStream_t s);
 
 // Rotary + KV write.  qkv fp32 [rows, (Hq + 2 Hkv) h] (bias already added) ->
 //   q fp16 [rows, Hq h] rotated; k (rotated) and v written as bf16 to the cache of `ncopy` consecutive cache
@@ -118,8 +121,8 @@ hipError_t rl_rope_kv(const RopeArgs& a, hipStream_t s);
 // the LM head, scan it, and emit token and log-prob.  forced nullable.  Output index out_index[row].
 struct SampleArgs {
   const float2* partial; int ngroups;
-  const uint16_t* hfin; int d;          // fp16 [R, d] rows fed to the LM head GEMM
-  const uint16_t* lm_head; int vocab;   // fp16 [V, d]
+  const uint16_t* hfin; int d;          // fp16 [R, d] rows fed to the LM head GEMM (K-block major)
+  const uint16_t* lm_head; int vocab;   // fp16 [V, d] (K-block major)
   float temperature;
   const float* uniforms; const int* forced; const int* io_index;  // value index of row i: io_index[i] * io_stride + io_add
   int io_stride, io_add;

@@ -126,17 +126,17 @@ size_t carve(rlgen_ctx* c, char* base) {
   Carve k;
   c->status = k.take<unsigned>(base, 64);
   c->embed = k.take<uint16_t>(base, V * d);
-  c->lm_head = k.take<uint16_t>(base, V * d);
+  c->lm_head = k.take<uint16_t>(base, kblk_elems(V, d));
   c->fng = k.take<float>(base, d);
   c->fnb = k.take<float>(base, d);
   c->layers.resize(m.n_layers);
   for (auto& L : c->layers) {
     L.n1g = k.take<float>(base, d); L.n1b = k.take<float>(base, d);
     L.n2g = k.take<float>(base, d); L.n2b = k.take<float>(base, d);
-    L.wqkv = k.take<uint16_t>(base, nqkv * d); L.bqkv = k.take<float>(base, nqkv);
-    L.wo = k.take<uint16_t>(base, d * qd); L.bo = k.take<float>(base, d);
-    L.wup = k.take<uint16_t>(base, (llama ? 2 : 1) * F * d); L.bup = k.take<float>(base, F);
-    L.wdown = k.take<uint16_t>(base, d * F); L.bdown = k.take<float>(base, d);
+    L.wqkv = k.take<uint16_t>(base, kblk_elems(nqkv, d)); L.bqkv = k.take<float>(base, nqkv);
+    L.wo = k.take<uint16_t>(base, kblk_elems(d, qd)); L.bo = k.take<float>(base, d);
+    L.wup = k.take<uint16_t>(base, kblk_elems((llama ? 2 : 1) * F, d)); L.bup = k.take<float>(base, F);
+    L.wdown = k.take<uint16_t>(base, kblk_elems(d, F)); L.bdown = k.take<float>(base, d);
   }
   c->rope = k.take<float2>(base, (size_t)m.max_seq_len * (m.rotary_dim / 2 > 0 ? m.rotary_dim / 2 : 1));
   c->lay.Hkv = m.n_kv_heads;
@@ -152,13 +152,13 @@ size_t carve(rlgen_ctx* c, char* base) {
   c->d_lm_row = k.take<int>(base, R); c->d_target = k.take<int>(base, R); c->d_out_index = k.take<int>(base, R);
   c->d_jobs = k.take<AttnJob>(base, R / 16 + S + 1);
   c->x = k.take<float>(base, R * d);
-  c->n1 = k.take<uint16_t>(base, R * d);
-  c->n2 = k.take<uint16_t>(base, R * d);
+  c->n1 = k.take<uint16_t>(base, kblk_elems(R, d));
+  c->n2 = k.take<uint16_t>(base, kblk_elems(R, d));
   c->qkv = k.take<float>(base, R * nqkv);
   c->q = k.take<uint16_t>(base, R * qd);
-  c->attn = k.take<uint16_t>(base, R * qd);
-  c->act = k.take<uint16_t>(base, R * F);
-  c->hfin = k.take<uint16_t>(base, LM * d);
+  c->attn = k.take<uint16_t>(base, kblk_elems(R, qd));
+  c->act = k.take<uint16_t>(base, kblk_elems(R, F));
+  c->hfin = k.take<uint16_t>(base, kblk_elems(LM, d));
   c->partial = k.take<float2>(base, LM * (size_t)c->ngroups);
   c->target_logit = k.take<float>(base, LM);
   c->splitk_elems = (size_t)12 << 20;          // 48 MB of split-K partial sums
@@ -174,6 +174,7 @@ int pack_weights(rlgen_ctx* c, const rlgen_weights* w, hipStream_t st) {
   const int bf = m.weight_dtype == RLGEN_DTYPE_BF16;
   const size_t d = m.d_model, F = m.d_ffn, V = m.vocab, h = m.head_dim;
   const size_t qd = (size_t)m.n_q_heads * h, kvd = (size_t)m.n_kv_heads * h;
+  const int nqkv = (int)(qd + 2 * kvd);
   if (!w || !w->embed_in || !w->final_norm_g || !w->lm_head || !w->layers) return RLGEN_ERR_NULL;
   if (!llama && !w->final_norm_b) return RLGEN_ERR_NULL;
   for (int l = 0; l < m.n_layers; ++l) {
@@ -183,7 +184,7 @@ int pack_weights(rlgen_ctx* c, const rlgen_weights* w, hipStream_t st) {
       return RLGEN_ERR_NULL;
   }
   HIPCHK(rl_to_bf16(c->embed, w->embed_in, bf, V * d, st));
-  HIPCHK(rl_to_f16w(c->lm_head, w->lm_head, bf, V * d, st));
+  HIPCHK(rl_to_f16w(c->lm_head, w->lm_head, bf, (int)V, (int)d, (int)V, 0, st));
   HIPCHK(rl_to_f32(c->fng, w->final_norm_g, bf, d, st));
   if (!llama) HIPCHK(rl_to_f32(c->fnb, w->final_norm_b, bf, d, st));
   for (int l = 0; l < m.n_layers; ++l) {
@@ -191,15 +192,15 @@ int pack_weights(rlgen_ctx* c, const rlgen_weights* w, hipStream_t st) {
     LayerW& L = c->layers[l];
     HIPCHK(rl_to_f32(L.n1g, s.norm1_g, bf, d, st));
     HIPCHK(rl_to_f32(L.n2g, s.norm2_g, bf, d, st));
-    HIPCHK(rl_to_f16w(L.wqkv, s.wq, bf, qd * d, st));
-    HIPCHK(rl_to_f16w(L.wqkv + qd * d, s.wk, bf, kvd * d, st));
-    HIPCHK(rl_to_f16w(L.wqkv + (qd + kvd) * d, s.wv, bf, kvd * d, st));
-    HIPCHK(rl_to_f16w(L.wo, s.wo, bf, d * qd, st));
-    HIPCHK(rl_to_f16w(L.wdown, s.w_down, bf, d * F, st));
+    HIPCHK(rl_to_f16w(L.wqkv, s.wq, bf, (int)qd, (int)d, nqkv, 0, st));
+    HIPCHK(rl_to_f16w(L.wqkv, s.wk, bf, (int)kvd, (int)d, nqkv, (int)qd, st));
+    HIPCHK(rl_to_f16w(L.wqkv, s.wv, bf, (int)kvd, (int)d, nqkv, (int)(qd + kvd), st));
+    HIPCHK(rl_to_f16w(L.wo, s.wo, bf, (int)d, (int)qd, (int)d, 0, st));
+    HIPCHK(rl_to_f16w(L.wdown, s.w_down, bf, (int)d, (int)F, (int)d, 0, st));
     if (llama) {
       HIPCHK(rl_pack_gate_up(L.wup, s.w_gate, s.w_up, bf, (int)F, (int)d, st));
     } else {
-      HIPCHK(rl_to_f16w(L.wup, s.w_up, bf, F * d, st));
+      HIPCHK(rl_to_f16w(L.wup, s.w_up, bf, (int)F, (int)d, (int)F, 0, st));
       HIPCHK(rl_to_f32(L.n1b, s.norm1_b, bf, d, st));
       HIPCHK(rl_to_f32(L.n2b, s.norm2_b, bf, d, st));
       HIPCHK(rl_to_f32(L.bqkv, s.bq, bf, qd, st));
@@ -261,10 +262,10 @@ int run_layers(rlgen_ctx* c, int rows, bool decode, int t, int ncopy, bool use_c
   for (int l = 0; l < m.n_layers; ++l) {
     const LayerW& L = c->layers[l];
     uint16_t* kvl = c->kv + (use_cache_layers ? (size_t)c->lay.layer_stride * l : 0);
-    if (llama) HIPCHK(rl_norm(c->x, nullptr, rows, d, m.norm_eps, L.n1g, nullptr, c->n1, nullptr, nullptr, nullptr, st));
-    else HIPCHK(rl_norm(c->x, nullptr, rows, d, m.norm_eps, L.n1g, L.n1b, c->n1, L.n2g, L.n2b, c->n2, st));
+    if (llama) HIPCHK(rl_norm(c->x, nullptr, rows, d, m.norm_eps, L.n1g, nullptr, c->n1, nullptr, nullptr, nullptr, rows, 0, st));
+    else HIPCHK(rl_norm(c->x, nullptr, rows, d, m.norm_eps, L.n1g, L.n1b, c->n1, L.n2g, L.n2b, c->n2, rows, 0, st));
     GemmArgs g{};
-    g.A = c->n1; g.lda = d; g.W = L.wqkv; g.ldw = d; g.M = rows; g.N = nqkv; g.K = d;
+    g.A = c->n1; g.W = L.wqkv; g.M = rows; g.N = nqkv; g.K = d;
     g.bias = llama ? nullptr : L.bqkv; g.out = c->qkv; g.ldo = nqkv; g.ws = c->splitk; g.ws_elems = c->splitk_elems;
     HIPCHK(rl_gemm(g, EPI_F32, st));
     RopeArgs r{};
@@ -274,7 +275,7 @@ int run_layers(rlgen_ctx* c, int rows, bool decode, int t, int ncopy, bool use_c
     else { r.pos = c->d_pos; r.pos_add = 0; r.dst_seq = c->d_dst_seq; r.ncopy = ncopy; r.v_by_blocks = 1; r.jobs = c->d_jobs; r.njobs = njobs; }
     HIPCHK(rl_rope_kv(r, st));
     AttnArgs a{};
-    a.q = c->q; a.q_ld = qd; a.out = c->attn; a.out_ld = qd; a.kv = kvl; a.lay = c->lay;
+    a.q = c->q; a.q_ld = qd; a.out = c->attn; a.out_rows = rows; a.kv = kvl; a.lay = c->lay;
     a.kv_off = c->d_kv_off; a.kv_cap = c->d_kv_cap; a.Hq = m.n_q_heads; a.scale = 1.0f / sqrtf((float)h);
     if (decode) {
       a.ctx_base = c->d_ctx_base; a.ctx_add = t; a.S = rows; a.order = c->use_order ? c->d_order : nullptr;
@@ -296,34 +297,33 @@ int run_layers(rlgen_ctx* c, int rows, bool decode, int t, int ncopy, bool use_c
       HIPCHK(rl_attention_prefill(a, st));
     }
     g = GemmArgs{};
-    g.A = c->attn; g.lda = qd; g.W = L.wo; g.ldw = qd; g.M = rows; g.N = d; g.K = qd;
+    g.A = c->attn; g.W = L.wo; g.M = rows; g.N = d; g.K = qd;
     g.bias = llama ? nullptr : L.bo; g.out = c->x; g.ldo = d; g.ws = c->splitk; g.ws_elems = c->splitk_elems;
     HIPCHK(rl_gemm(g, EPI_RESID, st));
-    if (llama) HIPCHK(rl_norm(c->x, nullptr, rows, d, m.norm_eps, L.n2g, nullptr, c->n2, nullptr, nullptr, nullptr, st));
+    if (llama) HIPCHK(rl_norm(c->x, nullptr, rows, d, m.norm_eps, L.n2g, nullptr, c->n2, nullptr, nullptr, nullptr, rows, 0, st));
     g = GemmArgs{};
-    g.A = c->n2; g.lda = d; g.W = L.wup; g.ldw = d; g.M = rows; g.N = llama ? 2 * F : F; g.K = d;
+    g.A = c->n2; g.W = L.wup; g.M = rows; g.N = llama ? 2 * F : F; g.K = d;
     g.bias = llama ? nullptr : L.bup; g.out = c->act; g.ldo = F; g.ws = c->splitk; g.ws_elems = c->splitk_elems;
     HIPCHK(rl_gemm(g, llama ? EPI_SWIGLU_F16 : EPI_GELU_F16, st));
     g = GemmArgs{};
-    g.A = c->act; g.lda = F; g.W = L.wdown; g.ldw = F; g.M = rows; g.N = d; g.K = F;
+    g.A = c->act; g.W = L.wdown; g.M = rows; g.N = d; g.K = F;
     g.bias = llama ? nullptr : L.bdown; g.out = c->x; g.ldo = d; g.ws = c->splitk; g.ws_elems = c->splitk_elems;
     HIPCHK(rl_gemm(g, EPI_RESID, st));
   }
   return RLGEN_OK;
 }
 
-// Final norm of selected rows of c->x into c->hfin.
-int final_norm(rlgen_ctx* c, const int* row_index, int rows, uint16_t* out, hipStream_t st) {
+// Final norm of selected rows of c->x into rows out_row0.. of c->hfin (a K-block major matrix of out_rows rows).
+int final_norm(rlgen_ctx* c, const int* row_index, int rows, int out_rows, int out_row0, hipStream_t st) {
   const rlgen_model_cfg& m = c->cfg;
-  HIPCHK(rl_norm(c->x, row_index, rows, m.d_model, m.norm_eps, c->fng, m.arch == RLGEN_ARCH_LLAMA ? nullptr : c->fnb, out,
-                 nullptr, nullptr, nullptr, st));
+  HIPCHK(rl_norm(c->x, row_index, rows, m.d_model, m.norm_eps, c->fng, m.arch == RLGEN_ARCH_LLAMA ? nullptr : c->fnb, c->hfin,
+                 nullptr, nullptr, nullptr, out_rows, out_row0, st));
   return RLGEN_OK;
 }
 
 int lm_head_stats(rlgen_ctx* c, const uint16_t* hfin, int rows, float temperature, const int* target, hipStream_t st) {
   GemmArgs g{};
-  g.A = hfin; g.lda = c->cfg.d_model; g.W = c->lm_head; g.ldw = c->cfg.d_model;
-  g.M = rows; g.N = c->cfg.vocab; g.K = c->cfg.d_model;
+  g.A = hfin; g.W = c->lm_head;   g.M = rows; g.N = c->cfg.vocab; g.K = c->cfg.d_model;
   g.temperature = temperature; g.partial = c->partial; g.target = target; g.target_logit = c->target_logit;
   HIPCHK(rl_gemm(g, EPI_LMHEAD, st));
   return RLGEN_OK;
@@ -438,10 +438,10 @@ int score_impl(rlgen_ctx* c, const int32_t* seqs, const int32_t* seq_lens, const
     rc = run_layers(c, ch.rows, false, 0, 1, false, ch.jobs, st);
     if (rc) return rc;
     if (logits) {
-      rc = final_norm(c, c->d_lastrow + ch.first, ch.count, c->hfin, st);
+      rc = final_norm(c, c->d_lastrow + ch.first, ch.count, ch.count, 0, st);
       if (rc) return rc;
       GemmArgs g{};
-      g.A = c->hfin; g.lda = m.d_model; g.W = c->lm_head; g.ldw = m.d_model; g.M = ch.count; g.N = m.vocab; g.K = m.d_model;
+      g.A = c->hfin; g.W = c->lm_head; g.M = ch.count; g.N = m.vocab; g.K = m.d_model;
       g.out = logits + (size_t)ch.first * m.vocab; g.ldo = m.vocab;
       HIPCHK(rl_gemm(g, EPI_F32, st));
     } else {
@@ -452,7 +452,7 @@ int score_impl(rlgen_ctx* c, const int32_t* seqs, const int32_t* seq_lens, const
       }
       for (int r0 = 0; r0 < ch.lm_rows; r0 += c->LM) {
         const int nr = std::min(c->LM, ch.lm_rows - r0);
-        rc = final_norm(c, c->d_lm_row + r0, nr, c->hfin, st);
+        rc = final_norm(c, c->d_lm_row + r0, nr, nr, 0, st);
         if (rc) return rc;
         rc = lm_head_stats(c, c->hfin, nr, temperature, c->d_target + r0, st);
         if (rc) return rc;
@@ -579,7 +579,7 @@ int rlgen_generate(rlgen_ctx* c, const int32_t* prompts, const int32_t* prompt_l
     HIPCHK(rl_embed(c->x, c->embed, prompts, c->d_tok_index, ch.rows, m.d_model, m.vocab, c->status, st));
     rc = run_layers(c, ch.rows, false, 0, k, true, ch.jobs, st);
     if (rc) return rc;
-    rc = final_norm(c, c->d_lastrow + ch.first * k, ch.count * k, c->hfin + (size_t)ch.first * k * m.d_model, st);
+    rc = final_norm(c, c->d_lastrow + ch.first * k, ch.count * k, S, ch.first * k, st);
     if (rc) return rc;
   }
   if (c->timed) HIPCHK(hipEventRecord(c->ev_mid, st));
@@ -589,7 +589,7 @@ int rlgen_generate(rlgen_ctx* c, const int32_t* prompts, const int32_t* prompt_l
     HIPCHK(rl_embed(c->x, c->embed, c->d_next_token, nullptr, S, m.d_model, m.vocab, c->status, st));
     rc = run_layers(c, S, true, t, 1, true, 0, st);
     if (rc) return rc;
-    rc = final_norm(c, nullptr, S, c->hfin, st);
+    rc = final_norm(c, nullptr, S, S, 0, st);
     if (rc) return rc;
     rc = sample_rows(c, S, temperature, uniforms, forced, max_new, t, tokens, token_logprobs, c->d_next_token, st);
     if (rc) return rc;
@@ -619,7 +619,7 @@ int rlgen_debug_sample(rlgen_ctx* c, const float* hidden, int32_t R, float tempe
   hipStream_t st = (hipStream_t)hip_stream;
   const rlgen_model_cfg& m = c->cfg;
   HIPCHK(rl_norm(hidden, nullptr, R, m.d_model, m.norm_eps, c->fng, m.arch == RLGEN_ARCH_LLAMA ? nullptr : c->fnb, c->hfin,
-                 nullptr, nullptr, nullptr, st));
+                 nullptr, nullptr, nullptr, R, 0, st));
   return sample_rows(c, R, temperature, uniforms, forced, 1, 0, tokens, token_logprobs, nullptr, st);
 }
 

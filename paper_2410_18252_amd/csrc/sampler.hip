@@ -85,12 +85,10 @@ __global__ __launch_bounds__(256) void sample_kernel(SampleArgs a) {
   const int col = gmin * 64 + lane;
   float logit = -INFINITY;
   if (col < a.vocab) {
-    const uint16_t* w = a.lm_head + (size_t)col * a.d;
-    const uint16_t* hrow = a.hfin + (size_t)row * a.d;
     float acc = 0.f;
-    for (int k = 0; k < a.d; k += 8) {
-      const u32x4 wv = *(const u32x4*)(w + k);
-      const u32x4 hv = *(const u32x4*)(hrow + k);
+    for (int k = 0; k < a.d; k += 8) {      // both operands are K-block major: 64 lanes read 8 KB contiguous per K block
+      const u32x4 wv = *(const u32x4*)(a.lm_head + kblk_off(col, k, a.vocab));
+      const u32x4 hv = *(const u32x4*)(a.hfin + kblk_off(row, k, a.R));
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         acc += f16_bits_to_f32((uint16_t)(wv[e] & 0xffffu)) * f16_bits_to_f32((uint16_t)(hv[e] & 0xffffu));
