@@ -53,6 +53,16 @@ __global__ void fill_zero_kernel(u32x4* p, size_t n16) {
   for (; i < n16; i += stride) p[i] = u32x4{0, 0, 0, 0};
 }
 
+__global__ void fill_random_f16_kernel(uint16_t* p, size_t n, unsigned seed) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) {
+    unsigned x = (unsigned)i * 2654435761u + seed;
+    x ^= x >> 16; x *= 0x85ebca6bu; x ^= x >> 13;
+    p[i] = f32_to_f16_bits((x & 0xffff) / 65536.0f - 0.5f);
+  }
+}
+
 __global__ void embed_kernel(float* x, const uint16_t* E, const int* tokens, const int* tok_index, int rows, int d,
                              int vocab, unsigned* status) {
   const int row = blockIdx.x;
@@ -264,6 +274,11 @@ hipError_t rl_fill_zero(void* p, size_t bytes, hipStream_t s) {
   if (!bytes) return hipSuccess;
   if (bytes % 16 != 0 || ((uintptr_t)p) % 16 != 0) return hipErrorInvalidValue;
   hipLaunchKernelGGL(fill_zero_kernel, dim3(min(blocks_for(bytes / 16), 262144)), dim3(TPB), 0, s, (u32x4*)p, bytes / 16);
+  return hipGetLastError();
+}
+hipError_t rl_fill_random_f16(uint16_t* p, size_t n, unsigned seed, hipStream_t s) {
+  if (!n) return hipSuccess;
+  hipLaunchKernelGGL(fill_random_f16_kernel, dim3(min(blocks_for(n), 65536)), dim3(TPB), 0, s, p, n, seed);
   return hipGetLastError();
 }
 hipError_t rl_embed(float* x, const uint16_t* E, const int* tokens, const int* tok_index, int rows, int d, int vocab,

@@ -87,6 +87,8 @@ hipError_t rl_pack_gate_up(uint16_t* dst, const void* gate, const void* up, int 
 // cos/sin table [max_pos, r/2] (float2), angles pos * theta^(-2i/r) evaluated in fp64
 hipError_t rl_rope_table(float2* tab, int max_pos, int rotary_dim, float theta, hipStream_t s);
 hipError_t rl_fill_zero(void* p, size_t bytes, hipStream_t s);
+// n pseudo-random fp16 values in [-0.5, 0.5) (inputs for timing runs)
+hipError_t rl_fill_random_f16(uint16_t* p, size_t n, unsigned seed, hipStream_t s);
 
 // x[row, :] = float(E[tok[row]]), tok gathered as tokens[tok_index[row]] ; flags a bad id
 hipError_t rl_embed(float* x, const uint16_t* E, const int* tokens, const int* tok_index, int rows, int d,

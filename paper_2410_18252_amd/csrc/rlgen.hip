@@ -82,6 +82,8 @@ struct rlgen_ctx {
   bool profiling;
   std::vector<hipEvent_t> prof_events;
   size_t prof_used;
+  // tile shape and K split of each linear layer, measured at creation: [decode | prompt pass][which GEMM]
+  struct GemmChoice { int variant, splits; } tuned[2][5];
 };
 
 namespace {
@@ -251,6 +253,22 @@ __global__ void clamp_targets_kernel(int* target, int n, int vocab, unsigned* st
 
 struct Chunk { int first, count, rows, jobs, lm_rows; };
 
+enum { G_QKV = 0, G_O = 1, G_UP = 2, G_DOWN = 3, G_LMHEAD = 4 };
+
+hipError_t run_choice(const GemmArgs& g, int epi, int variant, int splits, hipStream_t st) {
+  if (variant < 0) return rl_gemm(g, epi, st);
+  if (splits >= 2) {
+    GemmArgs h = g;
+    h.splits = splits;
+    return rl_gemm_splitk(h, epi, variant, st);
+  }
+  return rl_gemm_variant(g, epi, variant, st);
+}
+hipError_t gemm(rlgen_ctx* c, int which, bool decode, const GemmArgs& g, int epi, hipStream_t st) {
+  const auto& ch = c->tuned[decode ? 0 : 1][which];
+  return run_choice(g, epi, ch.variant, ch.splits, st);
+}
+
 // One pass of all decoder blocks over `rows` packed rows held in c->x.
 //  decode: rows are sequences 0..rows-1 at step t (the token drawn at step t-1 enters at position
 //          ctx_base + t - 1); otherwise rows follow d_pos / d_dst_seq / d_jobs of the current chunk.
@@ -267,7 +285,7 @@ int run_layers(rlgen_ctx* c, int rows, bool decode, int t, int ncopy, bool use_c
     GemmArgs g{};
     g.A = c->n1; g.W = L.wqkv; g.M = rows; g.N = nqkv; g.K = d;
     g.bias = llama ? nullptr : L.bqkv; g.out = c->qkv; g.ldo = nqkv; g.ws = c->splitk; g.ws_elems = c->splitk_elems;
-    HIPCHK(rl_gemm(g, EPI_F32, st));
+    HIPCHK(gemm(c, G_QKV, decode, g, EPI_F32, st));
     RopeArgs r{};
     r.qkv = c->qkv; r.rows = rows; r.Hq = m.n_q_heads; r.Hkv = m.n_kv_heads; r.h = h; r.r = m.rotary_dim;
     r.table = c->rope; r.q = c->q; r.kv = kvl; r.lay = c->lay; r.kv_off = c->d_kv_off; r.kv_cap = c->d_kv_cap;
@@ -299,16 +317,16 @@ int run_layers(rlgen_ctx* c, int rows, bool decode, int t, int ncopy, bool use_c
     g = GemmArgs{};
     g.A = c->attn; g.W = L.wo; g.M = rows; g.N = d; g.K = qd;
     g.bias = llama ? nullptr : L.bo; g.out = c->x; g.ldo = d; g.ws = c->splitk; g.ws_elems = c->splitk_elems;
-    HIPCHK(rl_gemm(g, EPI_RESID, st));
+    HIPCHK(gemm(c, G_O, decode, g, EPI_RESID, st));
     if (llama) HIPCHK(rl_norm(c->x, nullptr, rows, d, m.norm_eps, L.n2g, nullptr, c->n2, nullptr, nullptr, nullptr, rows, 0, st));
     g = GemmArgs{};
     g.A = c->n2; g.W = L.wup; g.M = rows; g.N = llama ? 2 * F : F; g.K = d;
     g.bias = llama ? nullptr : L.bup; g.out = c->act; g.ldo = F; g.ws = c->splitk; g.ws_elems = c->splitk_elems;
-    HIPCHK(rl_gemm(g, llama ? EPI_SWIGLU_F16 : EPI_GELU_F16, st));
+    HIPCHK(gemm(c, G_UP, decode, g, llama ? EPI_SWIGLU_F16 : EPI_GELU_F16, st));
     g = GemmArgs{};
     g.A = c->act; g.W = L.wdown; g.M = rows; g.N = d; g.K = F;
     g.bias = llama ? nullptr : L.bdown; g.out = c->x; g.ldo = d; g.ws = c->splitk; g.ws_elems = c->splitk_elems;
-    HIPCHK(rl_gemm(g, EPI_RESID, st));
+    HIPCHK(gemm(c, G_DOWN, decode, g, EPI_RESID, st));
   }
   return RLGEN_OK;
 }
@@ -325,7 +343,7 @@ int lm_head_stats(rlgen_ctx* c, const uint16_t* hfin, int rows, float temperatur
   GemmArgs g{};
   g.A = hfin; g.W = c->lm_head;   g.M = rows; g.N = c->cfg.vocab; g.K = c->cfg.d_model;
   g.temperature = temperature; g.partial = c->partial; g.target = target; g.target_logit = c->target_logit;
-  HIPCHK(rl_gemm(g, EPI_LMHEAD, st));
+  HIPCHK(gemm(c, G_LMHEAD, rows <= c->cfg.max_seqs, g, EPI_LMHEAD, st));
   return RLGEN_OK;
 }
 
@@ -340,6 +358,71 @@ int sample_rows(rlgen_ctx* c, int rows, float temperature, const float* uniforms
   s.tokens = tokens; s.logprobs = logprobs; s.next_token = next_token; s.R = rows; s.status = c->status;
   HIPCHK(rl_sample(s, st));
   return RLGEN_OK;
+}
+
+// Times every tile shape (and K split) on each linear layer of this model at the row counts it will see --
+// max_seqs rows for a decode step, a full chunk for the prompt pass -- and keeps the fastest.  Inputs are the
+// activation scratch buffers filled with pseudo-random fp16; outputs land in scratch.
+int tune_gemms(rlgen_ctx* c, hipStream_t st) {
+  const rlgen_model_cfg& m = c->cfg;
+  const bool llama = m.arch == RLGEN_ARCH_LLAMA;
+  const int d = m.d_model, F = m.d_ffn, qd = m.n_q_heads * m.head_dim, nqkv = qd + 2 * m.n_kv_heads * m.head_dim;
+  HIPCHK(rl_fill_random_f16(c->n1, kblk_elems(c->R, d), 11, st));
+  HIPCHK(rl_fill_random_f16(c->n2, kblk_elems(c->R, d), 12, st));
+  HIPCHK(rl_fill_random_f16(c->attn, kblk_elems(c->R, qd), 13, st));
+  HIPCHK(rl_fill_random_f16(c->act, kblk_elems(c->R, F), 14, st));
+  HIPCHK(rl_fill_random_f16(c->hfin, kblk_elems(c->LM, d), 15, st));
+  HIPCHK(rl_fill_zero(c->x, align_up((size_t)c->R * d * 4, 16), st));
+  hipEvent_t e0, e1;
+  HIPCHK(hipEventCreate(&e0));
+  HIPCHK(hipEventCreate(&e1));
+  const LayerW& L = c->layers[0];
+  int rc = RLGEN_OK;
+  for (int mode = 0; mode < 2 && rc == RLGEN_OK; ++mode) {
+    for (int which = 0; which < 5 && rc == RLGEN_OK; ++which) {
+      GemmArgs g{};
+      int epi = EPI_F32;
+      g.M = mode == 0 ? m.max_seqs : c->R;
+      g.ws = c->splitk; g.ws_elems = c->splitk_elems;
+      switch (which) {
+        case G_QKV: g.A = c->n1; g.W = L.wqkv; g.N = nqkv; g.K = d; g.bias = llama ? nullptr : L.bqkv; g.out = c->qkv; g.ldo = nqkv; epi = EPI_F32; break;
+        case G_O: g.A = c->attn; g.W = L.wo; g.N = d; g.K = qd; g.bias = llama ? nullptr : L.bo; g.out = c->x; g.ldo = d; epi = EPI_RESID; break;
+        case G_UP: g.A = c->n2; g.W = L.wup; g.N = llama ? 2 * F : F; g.K = d; g.bias = llama ? nullptr : L.bup; g.out = c->act; g.ldo = F;
+                   epi = llama ? EPI_SWIGLU_F16 : EPI_GELU_F16; break;
+        case G_DOWN: g.A = c->act; g.W = L.wdown; g.N = d; g.K = F; g.bias = llama ? nullptr : L.bdown; g.out = c->x; g.ldo = d; epi = EPI_RESID;
+                     break;
+        case G_LMHEAD: g.A = c->hfin; g.W = c->lm_head; g.M = mode == 0 ? m.max_seqs : c->LM; g.N = m.vocab; g.K = d; g.temperature = 1.f;
+                       g.partial = c->partial; g.ws = nullptr; epi = EPI_LMHEAD; break;
+      }
+      const bool wide_only = epi == EPI_SWIGLU_F16 || epi == EPI_LMHEAD;
+      const int nk = (g.K + 63) / 64;
+      struct Cand { int variant, splits; };
+      std::vector<Cand> cands = {{0, 1}, {3, 1}, {5, 1}};
+      if (!wide_only) {
+        cands.push_back({7, 1});
+        const long long t7 = (long long)((g.M + 63) / 64) * ((g.N + 127) / 128);
+        if (g.ws && t7 <= 1024)
+          for (int sp : {2, 3, 4, 6, 8})
+            if (nk / sp >= 4 && (size_t)sp * g.M * g.N <= g.ws_elems) cands.push_back({7, sp});
+      }
+      float best = 1e30f;
+      rlgen_ctx::GemmChoice pick{-1, 1};
+      for (const Cand& cd : cands) {
+        bool ok = run_choice(g, epi, cd.variant, cd.splits, st) == hipSuccess;     // warm-up
+        if (ok) ok = hipEventRecord(e0, st) == hipSuccess;
+        for (int r = 0; ok && r < 3; ++r) ok = run_choice(g, epi, cd.variant, cd.splits, st) == hipSuccess;
+        if (ok) ok = hipEventRecord(e1, st) == hipSuccess && hipEventSynchronize(e1) == hipSuccess;
+        float ms = 0.f;
+        if (ok) ok = hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
+        if (!ok) { rc = RLGEN_ERR_DEVICE; break; }
+        if (ms < best) { best = ms; pick = {cd.variant, cd.splits}; }
+      }
+      c->tuned[mode][which] = pick;
+    }
+  }
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  return rc;
 }
 
 // Waits until the previous call's metadata upload has left the staging buffer.
@@ -507,6 +590,9 @@ int rlgen_create(const rlgen_model_cfg* cfg, const rlgen_weights* weights, void*
     return fail(RLGEN_ERR_DEVICE);
   c->timed = true;
   rc = pack_weights(c, weights, st);
+  if (rc) return fail(rc);
+  for (auto& row : c->tuned) for (auto& ch : row) ch = {-1, 1};
+  rc = tune_gemms(c, st);
   if (rc) return fail(rc);
   if (rl_fill_zero(c->status, 256, st) != hipSuccess) return fail(RLGEN_ERR_DEVICE);
   if (rl_rope_table(c->rope, cfg->max_seq_len, cfg->rotary_dim, cfg->rope_theta, st) != hipSuccess) return fail(RLGEN_ERR_DEVICE);
