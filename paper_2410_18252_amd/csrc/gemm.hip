@@ -42,7 +42,16 @@ __device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int spli
   tn = in_group / gsz;
 }
 
-__device__ __forceinline__ float gelu_erf(float v) { return 0.5f * v * (1.0f + erff(v * 0.70710678118654752f)); }
+// erf by the rational-exponential form of Abramowitz & Stegun 7.1.26 (absolute error < 1.5e-7, far below the
+// fp16 rounding of the result): a third of the instructions of the library erff, which matters in an epilogue.
+__device__ __forceinline__ float erf_as(float x) {
+  const float ax = fabsf(x);
+  const float t = __frcp_rn(1.0f + 0.3275911f * ax);
+  const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
+  const float r = 1.0f - poly * __expf(-ax * ax);
+  return copysignf(r, x);
+}
+__device__ __forceinline__ float gelu_erf(float v) { return 0.5f * v * (1.0f + erf_as(v * 0.70710678118654752f)); }
 __device__ __forceinline__ float silu(float v) { return v / (1.0f + __expf(-v)); }
 
 template <int BM, int BN, int WM, int WN, int EPI, bool KTAIL>
@@ -158,12 +167,15 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f16_kernel(GemmArgs g) {
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[kk & 1][i], fb[kk & 1][j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[kk & 1][j], fa[kk & 1][i], acc[i][j], 0, 0, 0);
     }
     __syncthreads();
   }
 
-  // ---- epilogue.  acc[i][j][e]: row = 8 (e / 4) + 4 (lane / 32) + e % 4, col = lane % 32 of the 32x32 tile
+  // ---- epilogue.  The products were issued as W_tile . A_tile^T, so acc[i][j][e] is C[m][n] with
+  // m = lane % 32 (row of the 32x32 tile) and n = 8 (e / 4) + 4 (lane / 32) + e % 4: every lane holds runs of four
+  // consecutive columns of one row, which makes outputs, bias and residual 16-byte accesses and turns the
+  // row-wise softmax statistics of the LM head into in-register reductions.
   const int wrow0 = row0 + wm * (BM / WM), wcol0 = col0 + wn * (BN / WN);
   if constexpr (EPI == EPI_LMHEAD) {
     // per row and per 64-column group: max and sum of exp of the tempered logits; optional capture
@@ -171,64 +183,88 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f16_kernel(GemmArgs g) {
     static_assert(TN % 2 == 0, "a wave must own whole 64-column groups");
     const int ngroups = (g.N + 63) >> 6;
 #pragma unroll
-    for (int gi = 0; gi < TN / 2; ++gi) {
-      const int group = (wcol0 >> 6) + gi;
+    for (int i = 0; i < TM; ++i) {
+      const int row = wrow0 + i * 32 + frow;
+      const int tgt = (g.target != nullptr && row < g.M) ? g.target[row] : -1;
 #pragma unroll
-      for (int i = 0; i < TM; ++i) {
+      for (int gi = 0; gi < TN / 2; ++gi) {
+        const int group = (wcol0 >> 6) + gi;
+        float l[32];
+        float mx = -INFINITY;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int row = wrow0 + i * 32 + 8 * (e >> 2) + 4 * fhalf + (e & 3);
-          float l[2];
-          float mx = -INFINITY;
+        for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
-          for (int jj = 0; jj < 2; ++jj) {
-            const int col = wcol0 + (2 * gi + jj) * 32 + frow;
-            l[jj] = col < g.N ? acc[i][2 * gi + jj][e] / g.temperature : -INFINITY;
-            mx = fmaxf(mx, l[jj]);
-            if (g.target != nullptr && row < g.M && col < g.N && g.target[row] == col) g.target_logit[row] = l[jj];
+          for (int e = 0; e < 16; ++e) {
+            const int col = wcol0 + (2 * gi + jj) * 32 + 8 * (e >> 2) + 4 * fhalf + (e & 3);
+            const float v = col < g.N ? acc[i][2 * gi + jj][e] / g.temperature : -INFINITY;
+            l[jj * 16 + e] = v;
+            mx = fmaxf(mx, v);
+            if (col == tgt) g.target_logit[row] = v;
           }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
+        float sum = 0.f;
 #pragma unroll
-          for (int o = 16; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, WAVE));
-          float s = 0.f;
-#pragma unroll
-          for (int jj = 0; jj < 2; ++jj) s += (l[jj] == -INFINITY) ? 0.f : __expf(l[jj] - mx);
-#pragma unroll
-          for (int o = 16; o > 0; o >>= 1) s += __shfl_xor(s, o, WAVE);
-          if (frow == 0 && row < g.M && group < ngroups)
-            g.partial[(size_t)row * ngroups + group] = make_float2(mx, s);
-        }
+        for (int e = 0; e < 32; ++e) sum += (l[e] == -INFINITY) ? 0.f : __expf(l[e] - mx);
+        sum += __shfl_xor(sum, 32, WAVE);
+        if (fhalf == 0 && row < g.M && group < ngroups) g.partial[(size_t)row * ngroups + group] = make_float2(mx, sum);
       }
     }
   } else {
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
+      const int row = wrow0 + i * 32 + frow;
+      if (row >= g.M) continue;
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
-        const int col = wcol0 + j * 32 + frow;
-        if (col >= g.N) continue;
-        const float b = g.bias ? g.bias[col] : 0.f;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int row = wrow0 + i * 32 + 8 * (e >> 2) + 4 * fhalf + (e & 3);
-          if (row >= g.M) continue;
-          float v = acc[i][j][e] + b;
+        for (int q = 0; q < 4; ++q) {
+          const int col = wcol0 + j * 32 + 8 * q + 4 * fhalf;       // first of four consecutive columns
+          if (col >= g.N) continue;
+          const bool full = col + 3 < g.N;
+          f32x4 v;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) v[r] = acc[i][j][4 * q + r];
           if constexpr (EPI == EPI_PARTIAL) {
-            g.ws[((size_t)split * g.M + row) * g.N + col] = acc[i][j][e];
-          } else if constexpr (EPI == EPI_F32) {
-            ((float*)g.out)[(size_t)row * g.ldo + col] = v;
-          } else if constexpr (EPI == EPI_RESID) {
+            float* p = g.ws + ((size_t)split * g.M + row) * g.N + col;
+            if (full && (g.N & 3) == 0) *(f32x4*)p = v;
+            else
+              for (int r = 0; r < 4 && col + r < g.N; ++r) p[r] = v[r];
+            continue;
+          }
+          if (g.bias) {
+            if (full) v += *(const f32x4*)(g.bias + col);
+            else
+              for (int r = 0; r < 4 && col + r < g.N; ++r) v[r] += g.bias[col + r];
+          }
+          if constexpr (EPI == EPI_F32 || EPI == EPI_RESID) {
             float* p = (float*)g.out + (size_t)row * g.ldo + col;
-            *p = *p + v;
+            if (full && (g.ldo & 3) == 0) {
+              if constexpr (EPI == EPI_RESID) v += *(const f32x4*)p;
+              *(f32x4*)p = v;
+            } else {
+              for (int r = 0; r < 4 && col + r < g.N; ++r) p[r] = (EPI == EPI_RESID ? p[r] : 0.f) + v[r];
+            }
           } else if constexpr (EPI == EPI_GELU_F16) {
-            ((uint16_t*)g.out)[kblk_off(row, col, g.M)] = f32_to_f16_bits(gelu_erf(v));
+            uint16_t* p = (uint16_t*)g.out + kblk_off(row, col, g.M);     // four columns never straddle a K block
+            if (full) {
+              u32x2 w;
+              w[0] = pack_f16x2(gelu_erf(v[0]), gelu_erf(v[1]));
+              w[1] = pack_f16x2(gelu_erf(v[2]), gelu_erf(v[3]));
+              *(u32x2*)p = w;
+            } else {
+              for (int r = 0; r < 4 && col + r < g.N; ++r) p[r] = f32_to_f16_bits(gelu_erf(v[r]));
+            }
           } else if constexpr (EPI == EPI_SWIGLU_F16) {
             // weight rows come in blocks of 32: block 2b = gate rows [32b, 32b+32), block 2b+1 = the
             // matching up rows, so tile j (even) and tile j+1 hold gate and up of the same features.
             static_assert(TN % 2 == 0, "a wave must own gate and up of the same features");
             if ((j & 1) == 0) {
-              const float up = acc[i][j + 1 < TN ? j + 1 : j][e];
-              const int f = ((wcol0 + j * 32) >> 1) + frow;
-              ((uint16_t*)g.out)[kblk_off(row, f, g.M)] = f32_to_f16_bits(silu(v) * up);
+              const int f = ((wcol0 + j * 32) >> 1) + 8 * q + 4 * fhalf;
+              u32x2 w;
+              const int ju = j + 1 < TN ? j + 1 : j;
+              w[0] = pack_f16x2(silu(v[0]) * acc[i][ju][4 * q], silu(v[1]) * acc[i][ju][4 * q + 1]);
+              w[1] = pack_f16x2(silu(v[2]) * acc[i][ju][4 * q + 2], silu(v[3]) * acc[i][ju][4 * q + 3]);
+              *(u32x2*)((uint16_t*)g.out + kblk_off(row, f, g.M)) = w;
             }
           }
         }

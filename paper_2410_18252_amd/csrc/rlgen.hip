@@ -7,6 +7,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <cstdio>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -405,17 +406,28 @@ int tune_gemms(rlgen_ctx* c, hipStream_t st) {
           for (int sp : {2, 3, 4, 6, 8})
             if (nk / sp >= 4 && (size_t)sp * g.M * g.N <= g.ws_elems) cands.push_back({7, sp});
       }
-      float best = 1e30f;
-      rlgen_ctx::GemmChoice pick{-1, 1};
-      for (const Cand& cd : cands) {
-        bool ok = run_choice(g, epi, cd.variant, cd.splits, st) == hipSuccess;     // warm-up
-        if (ok) ok = hipEventRecord(e0, st) == hipSuccess;
-        for (int r = 0; ok && r < 3; ++r) ok = run_choice(g, epi, cd.variant, cd.splits, st) == hipSuccess;
-        if (ok) ok = hipEventRecord(e1, st) == hipSuccess && hipEventSynchronize(e1) == hipSuccess;
-        float ms = 0.f;
-        if (ok) ok = hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
-        if (!ok) { rc = RLGEN_ERR_DEVICE; break; }
-        if (ms < best) { best = ms; pick = {cd.variant, cd.splits}; }
+      // clocks drift with load, so the candidates take turns: one warm-up each, then three rounds in which
+      // every candidate is timed over two launches; the smallest total wins
+      std::vector<float> total(cands.size(), 0.f);
+      bool ok = true;
+      for (size_t i = 0; ok && i < cands.size(); ++i) ok = run_choice(g, epi, cands[i].variant, cands[i].splits, st) == hipSuccess;
+      for (int round = 0; ok && round < 3; ++round)
+        for (size_t i = 0; ok && i < cands.size(); ++i) {
+          ok = hipEventRecord(e0, st) == hipSuccess;
+          for (int r = 0; ok && r < 2; ++r) ok = run_choice(g, epi, cands[i].variant, cands[i].splits, st) == hipSuccess;
+          if (ok) ok = hipEventRecord(e1, st) == hipSuccess && hipEventSynchronize(e1) == hipSuccess;
+          float ms = 0.f;
+          if (ok) ok = hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
+          total[i] += ms;
+        }
+      if (!ok) { rc = RLGEN_ERR_DEVICE; break; }
+      size_t bi = 0;
+      for (size_t i = 1; i < cands.size(); ++i) if (total[i] < total[bi]) bi = i;
+      rlgen_ctx::GemmChoice pick{cands[bi].variant, cands[bi].splits};
+      if (getenv("RLGEN_DEBUG_TUNE")) {
+        fprintf(stderr, "rlgen tune: mode %d gemm %d M=%d N=%d K=%d:", mode, which, g.M, g.N, g.K);
+        for (size_t i = 0; i < cands.size(); ++i) fprintf(stderr, " v%d/s%d=%.0fus%s", cands[i].variant, cands[i].splits, total[i] / 6 * 1e3, i == bi ? "*" : "");
+        fprintf(stderr, "\n");
       }
       c->tuned[mode][which] = pick;
     }
