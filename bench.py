@@ -38,6 +38,9 @@ def main():
     ap.add_argument("--max-new", type=int, default=0, help="override the workload's number of new tokens (profiling runs)")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not bracket the decode-attention launches with HIP events (for rocprofv3 --pmc runs)")
+    ap.add_argument("--share-prompt-kv", action="store_true",
+                    help="the k samples of a prompt read one copy of the prompt's keys/values (not the headline layout)")
+    ap.add_argument("--k", type=int, default=0, help="override the workload's samples per prompt")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1")
@@ -50,16 +53,21 @@ def main():
     if args.max_new:
         import dataclasses
         w = dataclasses.replace(w, max_new=args.max_new, name=f"{w.name}-maxnew{args.max_new}")
+    if args.k:
+        import dataclasses
+        w = dataclasses.replace(w, k=args.k, name=f"{w.name}-k{args.k}")
     m = w.model
+    share = 1 if args.share_prompt_kv else 0
     t0 = time.time()
     W = make_weights(m, w.seed_weights, w.bf16_weights, threads=16)
     arr, lens = make_prompts(w)
     u = make_uniforms(w)
     B, k, T = w.n_prompts, w.k, w.max_new
     S = B * k
-    kv_tokens = int(sum(k * ((int(n) + T + 31) // 32 * 32) for n in lens))
+    r32 = lambda n: (int(n) + 31) // 32 * 32
+    kv_tokens = int(sum(r32(n) + k * r32(T) for n in lens)) if share else int(sum(k * r32(int(n) + T) for n in lens))
     cfg = R.make_cfg(m, weight_dtype=R.DTYPE_BF16 if W.is_bf16 else R.DTYPE_F32, max_seqs=S,
-                     max_seq_len=int(lens.max()) + T, max_kv_tokens=kv_tokens)
+                     max_seq_len=int(lens.max()) + T, max_kv_tokens=kv_tokens, share_prompt_kv=share)
     dev = R.upload_weights(W.tensors)
     pol = R.Policy(cfg, dev)
     del dev
@@ -107,18 +115,20 @@ def main():
     seq_len = np.repeat(lens.astype(np.int64), k)
     per_key = 2 * 2 * m.n_kv_heads * m.head_dim                    # K and V, 2 bytes each
     qo = 2 * 2 * S * m.n_q_heads * m.head_dim
-    bytes_per_launch = np.mean([per_key * int((seq_len + t).sum()) + qo for t in range(1, T)]) if T > 1 else 0.0
+    # with a shared prompt cache a launch reads each prompt's keys once, and t new keys per sequence
+    keys = (lambda t: int(lens.astype(np.int64).sum()) + S * t) if share else (lambda t: int((seq_len + t).sum()))
+    bytes_per_launch = np.mean([per_key * keys(t) + qo for t in range(1, T)]) if T > 1 else 0.0
     attn_us = 1e3 * attn_ms / max(attn_launches, 1)
     achieved = bytes_per_launch / (attn_us * 1e-6) / 1e9 if attn_launches else 0.0
     roofline = {"bound": "hbm", "kernel": "attention_kernel<HD,decode>", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": int(round(TRAFFIC_OVER_ALGORITHMIC * bytes_per_launch)) if args.config == 4 else None,
+                "traffic": int(round(TRAFFIC_OVER_ALGORITHMIC * bytes_per_launch)) if args.config == 4 and not share and not args.k else None,
                 "algorithmic_bytes_per_launch": int(bytes_per_launch),
                 "avg_launch_us": round(attn_us, 2), "launches": attn_launches}
 
     # whole decode phase: weights once per step + KV, over the measured decode time
     wbytes = 2 * (m.n_params - m.vocab * m.d_model)                # all matrices but the embedding table
-    decode_bytes = sum(wbytes + m.n_layers * (per_key * int((seq_len + t).sum()) + per_key * S) for t in range(1, T))
+    decode_bytes = sum(wbytes + m.n_layers * (per_key * keys(t) + per_key * S) for t in range(1, T))
     decode_gbs = decode_bytes / (np.mean(decode_ms) * 1e-3) / 1e9 if T > 1 else 0.0
 
     result = {
@@ -128,6 +138,7 @@ def main():
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": w.name, "prompts": B, "k": k, "max_new": T, "prompt_len": [w.prompt_len_lo, w.prompt_len_hi],
                    "temperature": w.temperature, "generated_tokens_per_step": S * T,
+                   "kv_layout": "prompt cache shared by the k samples" if share else "one contiguous cache per sequence",
                    "storage": "bf16 weights (held as fp16, exact) and bf16 KV cache; fp16 MFMA inputs, fp32 accumulation"},
         "prefill_ms": round(float(np.mean(prefill_ms)), 2), "decode_ms": round(float(np.mean(decode_ms)), 2),
         "decode_algorithmic_GBps": round(decode_gbs, 1), "decode_frac_of_hbm_peak": round(decode_gbs / HBM_PEAK_GBS, 4),

@@ -69,7 +69,13 @@ typedef struct {
                               to a multiple of 32                                                */
   int32_t max_batch_tokens;/* rows processed at once by prefill / score; >= max_seq_len;
                               0 selects a default                                                */
-  int32_t reserved;
+  int32_t share_prompt_kv; /* 0: every sequence owns a contiguous cache holding prompt and new tokens.
+                              1: rlgen_generate stores a prompt's keys/values once and its k samples
+                              read them together (the k samples of a prompt condition on the same
+                              prefix: Section 2.1, Section 4.2); results are the same up to rounding
+                              order.  Then k * (n_q_heads / n_kv_heads) <= 16 is required and the
+                              max_kv_tokens need is sum over prompts of round32(prompt_len) +
+                              prompts * k * round32(max_new).  rlgen_score is unaffected.        */
 } rlgen_model_cfg;
 
 /* Per-layer tensors, row-major, linear layers stored [out, in] and applied as y = W x + b.
@@ -126,7 +132,8 @@ int rlgen_update_weights(rlgen_ctx *ctx, const rlgen_weights *weights, void *hip
  *  token_logprobs out [B, k, max_new] fp32 = log softmax(z / temperature)[token]
  *
  * The k samples of one prompt share one prompt pass.  Errors: NULL, BAD_ARG (B, k, max_new < 1,
- * prompt_len < 1, prompt_stride < max prompt_len, temperature not finite or <= 0), CAPACITY, DEVICE. */
+ * prompt_len < 1, prompt_stride < max prompt_len, temperature not finite or <= 0, or with
+ * share_prompt_kv k * (n_q_heads / n_kv_heads) > 16), CAPACITY, DEVICE. */
 int rlgen_generate(rlgen_ctx *ctx, const int32_t *prompts, const int32_t *prompt_lens, int32_t B,
                    int32_t prompt_stride, int32_t k, int32_t max_new, float temperature,
                    const float *uniforms, const int32_t *forced, int32_t *tokens,

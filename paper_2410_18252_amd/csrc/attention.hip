@@ -16,6 +16,8 @@
 // fragment P^T the second product needs: probabilities never leave registers.
 // Decode with one kv head serving G query heads (grouped-query attention) puts the G heads in the
 // columns, so K/V are read once per group; with G = 1 the query is replicated over the columns.
+// With a shared prompt cache (share_k = K samples per prompt) the K samples sit in the columns as well:
+// the prompt's stream is read once for all of them, then each sample's short stream of new tokens.
 #include "kernels.h"
 
 #ifndef ATTN_PREFETCH
@@ -42,35 +44,51 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a) {
   const int Hkv = a.lay.Hkv, G = a.Hq / Hkv;
   const int job = blockIdx.x * 4 + wave;
 
-  int cache_seq, kvh, qrow, qhead, qpos, maxkeys;
+  // A job streams one or more segments.  Segment i is the stream of cache sequence seg_seq(i) with seg_len(i)
+  // keys; column c takes part in it if seg_col(i) < 0 or seg_col(i) == c / G (its sample).
+  int kvh, qrow, qhead, qpos, nseg;
+  int seq0, len0;           // first segment
+  int sfx_seq0 = 0, sfx_len = 0;   // shared-prompt decode: segments 1.. are the samples' own suffix streams
   bool store_col;
   if constexpr (DECODE) {
-    if (job >= a.S * Hkv) return;
+    const int units = a.share_k ? a.S / a.share_k : a.S;       // prompts or sequences
+    if (job >= units * Hkv) return;
     const int slot = job / Hkv;
     kvh = job - slot * Hkv;
-    const int s = a.order ? a.order[slot] : slot;     // longest contexts first: the tail of the launch is short jobs
-    cache_seq = s;
-    const int ctx = a.ctx_base[s] + a.ctx_add;
-    qrow = s;
+    const int u = a.order ? a.order[slot] : slot;     // longest contexts first: the tail of the launch is short jobs
+    if (a.share_k) {
+      // the K samples of prompt u sit in the MFMA columns (next to the G query heads of the kv head): the
+      // prompt's keys and values are read once for all of them, then each sample's own new tokens
+      const int j = (c / G) % a.share_k;
+      qrow = u * a.share_k + j;
+      seq0 = u;
+      len0 = a.ctx_base[u * a.share_k];
+      sfx_seq0 = units + u * a.share_k;
+      sfx_len = a.ctx_add;
+      nseg = 1 + a.share_k;
+      store_col = c < G * a.share_k;
+    } else {
+      qrow = u;
+      seq0 = u;
+      len0 = a.ctx_base[u] + a.ctx_add;
+      nseg = 1;
+      store_col = c < G;
+    }
     qhead = kvh * G + (c % G);
-    qpos = ctx - 1;
-    maxkeys = ctx;
-    store_col = c < G;
+    qpos = 0x7fffffff;      // a decode query sees every key of its segments
   } else {
     if (job >= a.njobs * a.Hq) return;
     const AttnJob jb = a.jobs[job / a.Hq];
     qhead = job % a.Hq;
     kvh = qhead / G;
-    cache_seq = jb.cache_seq;
+    seq0 = jb.cache_seq;
     const int tok = jb.qblock * 16 + c;
     store_col = tok < jb.len;
     qpos = min(tok, jb.len - 1);
     qrow = jb.row0 + qpos;
-    maxkeys = min(jb.qblock * 16 + 16, jb.len);
+    len0 = min(jb.qblock * 16 + 16, jb.len);
+    nseg = 1;
   }
-  const int cap = a.kv_cap[cache_seq];
-  const long long off = a.kv_off[cache_seq];
-  const uint16_t* __restrict__ st = a.kv + a.lay.stream(off, cap, kvh);
 
   // query fragments (B operand): lane (c, g) holds q[col c][32 i + 8 g .. + 7]
   f16x8 qf[KSTEPS];
@@ -91,7 +109,16 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a) {
   for (int t = 0; t < VT; ++t) o[t] = f32x4{0.f, 0.f, 0.f, 0.f};
   float m = -INFINITY, lsum = 0.f;
 
-  const int nsb = (maxkeys + 31) >> 5;
+  for (int seg = 0; seg < nseg; ++seg) {
+    const int cache_seq = seg == 0 ? seq0 : sfx_seq0 + seg - 1;
+    const int nkeys = seg == 0 ? len0 : sfx_len;
+    const bool mine = seg == 0 || (c / G) % a.share_k == seg - 1;     // does column c attend to this segment
+    const int cap = a.kv_cap[cache_seq];
+    const long long off = a.kv_off[cache_seq];
+    const uint16_t* __restrict__ st = a.kv + a.lay.stream(off, cap, kvh);
+    const int klimit = mine ? min(nkeys - 1, qpos) : -1;               // last visible key index for this column
+
+  const int nsb = (nkeys + 31) >> 5;
   // the whole next super-block (32 keys, 32 values) is requested before the current one is consumed
   auto load_sb = [&](int sb, u32x4 (&kraw)[2][KSTEPS], u32x4 (&vraw)[VT]) {
     const uint16_t* kb = st + (size_t)sb * 64 * HD;      // 32 keys, then the 32 values of the same positions
@@ -109,7 +136,7 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a) {
   u32x4 kraw[2][KSTEPS], vraw[VT];
 #if ATTN_PREFETCH
   u32x4 knext[2][KSTEPS], vnext[VT];
-  load_sb(0, kraw, vraw);
+  if (nsb > 0) load_sb(0, kraw, vraw);
 #endif
   for (int sb = 0; sb < nsb; ++sb) {
 #if ATTN_PREFETCH
@@ -134,19 +161,20 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const int key = sb * 32 + 8 * g + 4 * t + j;
-        const float v = key <= qpos ? sc[t][j] * a.scale : -INFINITY;
+        const float v = key <= klimit ? sc[t][j] * a.scale : -INFINITY;
         p[4 * t + j] = v;
         bmax = fmaxf(bmax, v);
       }
     bmax = fmaxf(bmax, __shfl_xor(bmax, 16, WAVE));
     bmax = fmaxf(bmax, __shfl_xor(bmax, 32, WAVE));
-    const float mnew = fmaxf(m, bmax);      // finite from the first super-block on: key 0 is visible to every column
-    const float alpha = __expf(m - mnew);
+    const float mnew = fmaxf(m, bmax);
+    // a column that has seen no key yet (m and mnew both -inf) keeps alpha = 1 and p = 0
+    const float alpha = mnew == -INFINITY ? 1.f : __expf(m - mnew);
     m = mnew;
     float psum = 0.f;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      p[e] = __expf(p[e] - mnew);
+      p[e] = mnew == -INFINITY ? 0.f : __expf(p[e] - mnew);
       psum += p[e];
     }
     lsum = lsum * alpha + psum;
@@ -167,6 +195,7 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a) {
     for (int t = 0; t < VT; ++t) vraw[t] = vnext[t];
 #endif
   }
+  }   // segments
   lsum += __shfl_xor(lsum, 16, WAVE);
   lsum += __shfl_xor(lsum, 32, WAVE);
   const float inv = 1.0f / lsum;
@@ -196,5 +225,8 @@ hipError_t dispatch(const AttnArgs& a, int jobs, hipStream_t s) {
 
 }  // namespace
 
-hipError_t rl_attention_decode(const AttnArgs& a, hipStream_t s) { return dispatch<true>(a, a.S * a.lay.Hkv, s); }
+hipError_t rl_attention_decode(const AttnArgs& a, hipStream_t s) {
+  if (a.share_k && (a.S % a.share_k != 0 || a.share_k * (a.Hq / a.lay.Hkv) > 16)) return hipErrorInvalidValue;
+  return dispatch<true>(a, (a.share_k ? a.S / a.share_k : a.S) * a.lay.Hkv, s);
+}
 hipError_t rl_attention_prefill(const AttnArgs& a, hipStream_t s) { return dispatch<false>(a, a.njobs * a.Hq, s); }

@@ -178,6 +178,7 @@ __global__ void rope_kv_kernel(RopeArgs a) {
     return;
   }
   const int s0 = a.dst_seq[row];
+  const int slotpos = pos - (a.slot_sub ? a.slot_sub[row] : 0);     // where in the stream the token goes
   for (int cpy = 0; cpy < a.ncopy; ++cpy) {
     const int s = s0 + cpy;
     const long long off = a.kv_off[s];
@@ -187,11 +188,11 @@ __global__ void rope_kv_kernel(RopeArgs a) {
       u32x4 w;
 #pragma unroll
       for (int e = 0; e < 4; ++e) w[e] = pack_bf16x2(v[2 * e], v[2 * e + 1]);
-      *(u32x4*)(st + a.lay.k_elem(pos, chunk * 8)) = w;
+      *(u32x4*)(st + a.lay.k_elem(slotpos, chunk * 8)) = w;
     } else {
       uint16_t* st = a.kv + a.lay.stream(off, cap, slot - a.Hq - a.Hkv);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) st[a.lay.v_elem(pos, chunk * 8 + e)] = f32_to_bf16_bits(v[e]);
+      for (int e = 0; e < 8; ++e) st[a.lay.v_elem(slotpos, chunk * 8 + e)] = f32_to_bf16_bits(v[e]);
     }
   }
 }

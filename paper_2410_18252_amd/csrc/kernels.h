@@ -67,7 +67,10 @@ struct AttnArgs {
   float scale;
   // decode: one query row per sequence, keys 0 .. ctx_base[s] + ctx_add - 1
   const int* ctx_base; int ctx_add; int S;
-  const int* order;                   // nullable [S]: sequence handled by slot i
+  const int* order;                   // nullable [S] (or [prompts] when share_k): unit handled by slot i
+  // shared prompt cache: 0 = off.  K = samples per prompt: sequence s = prompt * K + j; cache sequence `prompt`
+  // holds the prompt's keys (ctx_base[prompt * K] of them), cache sequence S / K + s the ctx_add new tokens of s
+  int share_k;
   // prefill
   const AttnJob* jobs; int njobs;
 };
@@ -111,6 +114,7 @@ struct RopeArgs {
   const int* dst_seq;            // [rows] first cache sequence receiving the row's k, v
   int ncopy;
   int pos_add;                   // added to pos[] (decode step)
+  const int* slot_sub;           // nullable [rows]: cache slot = position - slot_sub[row] (shared prompt cache)
   uint16_t* q;                   // out
   uint16_t* kv; KvLayout lay; const int* kv_off; const int* kv_cap;
   // prompt pass: V is written by a second kernel, one block per 16-token job (dst_seq[row] == jobs[].cache_seq)

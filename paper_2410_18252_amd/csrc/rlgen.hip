@@ -65,6 +65,7 @@ struct rlgen_ctx {
   SeqMeta* d_meta;
   int *d_kv_off, *d_kv_cap, *d_ctx_base, *d_iota, *d_lastrow, *d_order;
   bool use_order;
+  int share_k;            // samples per prompt of the running generate call when prompts share their cache, else 0
   int *d_tok_index, *d_pos, *d_dst_seq, *d_lm_row, *d_target, *d_out_index, *d_next_token;
   AttnJob* d_jobs;
   // activations
@@ -109,6 +110,7 @@ int check_cfg(const rlgen_model_cfg* c) {
   if (c->max_kv_tokens > (1LL << 30) || c->max_seqs > (1 << 20) || c->max_seq_len > (1 << 20)) return RLGEN_ERR_BAD_CFG;
   if (c->max_batch_tokens != 0 && c->max_batch_tokens < c->max_seq_len) return RLGEN_ERR_BAD_CFG;
   if (c->max_batch_tokens > (1 << 22)) return RLGEN_ERR_BAD_CFG;
+  if (c->share_prompt_kv != 0 && c->share_prompt_kv != 1) return RLGEN_ERR_BAD_CFG;
   return RLGEN_OK;
 }
 
@@ -147,7 +149,7 @@ size_t carve(rlgen_ctx* c, char* base) {
   c->lay.layer_stride = 2LL * m.max_kv_tokens * m.n_kv_heads * m.head_dim;
   c->kv = k.take<uint16_t>(base, (size_t)c->lay.layer_stride * m.n_layers);
   c->d_meta = k.take<SeqMeta>(base, S);
-  c->d_kv_off = k.take<int>(base, S); c->d_kv_cap = k.take<int>(base, S);
+  c->d_kv_off = k.take<int>(base, 2 * S); c->d_kv_cap = k.take<int>(base, 2 * S);   // prompt + per-sequence streams
   c->d_ctx_base = k.take<int>(base, S); c->d_iota = k.take<int>(base, S);
   c->d_lastrow = k.take<int>(base, S); c->d_next_token = k.take<int>(base, S);
   c->d_order = k.take<int>(base, S);
@@ -290,7 +292,10 @@ int run_layers(rlgen_ctx* c, int rows, bool decode, int t, int ncopy, bool use_c
     RopeArgs r{};
     r.qkv = c->qkv; r.rows = rows; r.Hq = m.n_q_heads; r.Hkv = m.n_kv_heads; r.h = h; r.r = m.rotary_dim;
     r.table = c->rope; r.q = c->q; r.kv = kvl; r.lay = c->lay; r.kv_off = c->d_kv_off; r.kv_cap = c->d_kv_cap;
-    if (decode) { r.pos = c->d_ctx_base; r.pos_add = t - 1; r.dst_seq = c->d_iota; r.ncopy = 1; }
+    if (decode) {
+      r.pos = c->d_ctx_base; r.pos_add = t - 1; r.dst_seq = c->d_iota; r.ncopy = 1;
+      r.slot_sub = c->share_k ? c->d_ctx_base : nullptr;     // new tokens start at slot 0 of their own stream
+    }
     else { r.pos = c->d_pos; r.pos_add = 0; r.dst_seq = c->d_dst_seq; r.ncopy = ncopy; r.v_by_blocks = 1; r.jobs = c->d_jobs; r.njobs = njobs; }
     HIPCHK(rl_rope_kv(r, st));
     AttnArgs a{};
@@ -298,6 +303,7 @@ int run_layers(rlgen_ctx* c, int rows, bool decode, int t, int ncopy, bool use_c
     a.kv_off = c->d_kv_off; a.kv_cap = c->d_kv_cap; a.Hq = m.n_q_heads; a.scale = 1.0f / sqrtf((float)h);
     if (decode) {
       a.ctx_base = c->d_ctx_base; a.ctx_add = t; a.S = rows; a.order = c->use_order ? c->d_order : nullptr;
+      a.share_k = c->share_k;
       hipEvent_t e0 = nullptr, e1 = nullptr;
       if (c->profiling) {
         while (c->prof_events.size() < c->prof_used + 2) {
@@ -454,18 +460,18 @@ Staged stage_views(rlgen_ctx* c) {
   char* p = c->h_stage;
   Staged s;
   s.meta = (SeqMeta*)p; p += align_up(S * sizeof(SeqMeta));
-  s.kv_off = (int*)p; p += align_up(S * 4);
-  s.kv_cap = (int*)p; p += align_up(S * 4);
+  s.kv_off = (int*)p; p += align_up(2 * S * 4);
+  s.kv_cap = (int*)p; p += align_up(2 * S * 4);
   s.ctx_base = (int*)p; p += align_up(S * 4);
   s.iota = (int*)p; p += align_up(S * 4);
   s.lastrow = (int*)p; p += align_up(S * 4);
   s.order = (int*)p;
   return s;
 }
-int stage_upload(rlgen_ctx* c, const Staged& s, int nmeta, int nseq, hipStream_t st) {
+int stage_upload(rlgen_ctx* c, const Staged& s, int nmeta, int nseq, int nstreams, hipStream_t st) {
   HIPCHK(hipMemcpyAsync(c->d_meta, s.meta, (size_t)nmeta * sizeof(SeqMeta), hipMemcpyHostToDevice, st));
-  HIPCHK(hipMemcpyAsync(c->d_kv_off, s.kv_off, (size_t)nseq * 4, hipMemcpyHostToDevice, st));
-  HIPCHK(hipMemcpyAsync(c->d_kv_cap, s.kv_cap, (size_t)nseq * 4, hipMemcpyHostToDevice, st));
+  HIPCHK(hipMemcpyAsync(c->d_kv_off, s.kv_off, (size_t)nstreams * 4, hipMemcpyHostToDevice, st));
+  HIPCHK(hipMemcpyAsync(c->d_kv_cap, s.kv_cap, (size_t)nstreams * 4, hipMemcpyHostToDevice, st));
   HIPCHK(hipMemcpyAsync(c->d_ctx_base, s.ctx_base, (size_t)nseq * 4, hipMemcpyHostToDevice, st));
   HIPCHK(hipMemcpyAsync(c->d_iota, s.iota, (size_t)nseq * 4, hipMemcpyHostToDevice, st));
   HIPCHK(hipMemcpyAsync(c->d_lastrow, s.lastrow, (size_t)nseq * 4, hipMemcpyHostToDevice, st));
@@ -518,7 +524,7 @@ int score_impl(rlgen_ctx* c, const int32_t* seqs, const int32_t* seq_lens, const
     cur.count++; cur.rows += len; cur.jobs += (len + 15) / 16; cur.lm_rows += nlm;
   }
   chunks.push_back(cur);
-  rc = stage_upload(c, s, N, N, st);
+  rc = stage_upload(c, s, N, N, N, st);
   if (rc) return rc;
   if (c->timed) HIPCHK(hipEventRecord(c->ev_start, st));
   if (!logits) {
@@ -590,7 +596,7 @@ int rlgen_create(const rlgen_model_cfg* cfg, const rlgen_weights* weights, void*
   carve(c, c->ws);
   hipStream_t st = (hipStream_t)hip_stream;
   const size_t S = cfg->max_seqs;
-  c->stage_bytes = align_up(S * sizeof(SeqMeta)) + 6 * align_up(S * 4);
+  c->stage_bytes = align_up(S * sizeof(SeqMeta)) + 4 * align_up(S * 4) + 2 * align_up(2 * S * 4);
   auto fail = [&](int code) {
     rlgen_destroy(c);
     return code;
@@ -628,11 +634,15 @@ int rlgen_generate(rlgen_ctx* c, const int32_t* prompts, const int32_t* prompt_l
   if (B < 1 || k < 1 || max_new < 1 || prompt_stride < 1) return RLGEN_ERR_BAD_ARG;
   if (!(temperature > 0.f) || !std::isfinite(temperature)) return RLGEN_ERR_BAD_ARG;
   if ((long long)B * k > m.max_seqs) return RLGEN_ERR_CAPACITY;
+  // shared prompt cache: one stream per prompt plus one short stream of new tokens per sequence; the k samples
+  // of a prompt and the query heads of a kv head share the 16 columns of the attention MFMA
+  const bool share = m.share_prompt_kv != 0;
+  if (share && (long long)k * (m.n_q_heads / m.n_kv_heads) > 16) return RLGEN_ERR_BAD_ARG;
   long long kvtok = 0;
   for (int b = 0; b < B; ++b) {
     if (prompt_lens[b] < 1 || prompt_lens[b] > prompt_stride) return RLGEN_ERR_BAD_ARG;
     if ((long long)prompt_lens[b] + max_new > m.max_seq_len) return RLGEN_ERR_CAPACITY;
-    kvtok += (long long)k * round32(prompt_lens[b] + max_new);
+    kvtok += share ? round32(prompt_lens[b]) + (long long)k * round32(max_new) : (long long)k * round32(prompt_lens[b] + max_new);
   }
   if (kvtok > m.max_kv_tokens) return RLGEN_ERR_CAPACITY;
   hipStream_t st = (hipStream_t)hip_stream;
@@ -650,23 +660,43 @@ int rlgen_generate(rlgen_ctx* c, const int32_t* prompts, const int32_t* prompt_l
       cur = Chunk{b, 0, 0, 0, 0};
     }
     SeqMeta& e = s.meta[b];
-    e.row0 = cur.rows; e.len = len; e.src_off = b * prompt_stride; e.cache_seq = b * k; e.job0 = cur.jobs;
+    e.row0 = cur.rows; e.len = len; e.src_off = b * prompt_stride; e.cache_seq = share ? b : b * k; e.job0 = cur.jobs;
     e.lm0 = 0; e.score_from = len; e.out_off = 0;
+    if (share) {
+      s.kv_off[b] = (int)off; s.kv_cap[b] = round32(len);
+      off += round32(len);
+    }
     for (int j = 0; j < k; ++j) {
       const int q = b * k + j;
-      s.kv_off[q] = (int)off; s.kv_cap[q] = round32(len + max_new);
-      s.ctx_base[q] = len; s.iota[q] = q; s.lastrow[q] = cur.rows + len - 1;
-      off += round32(len + max_new);
+      s.ctx_base[q] = len; s.lastrow[q] = cur.rows + len - 1;
+      if (share) {
+        s.iota[q] = B + q;       // the stream that takes sequence q's new tokens
+      } else {
+        s.iota[q] = q;
+        s.kv_off[q] = (int)off; s.kv_cap[q] = round32(len + max_new);
+        off += round32(len + max_new);
+      }
     }
     cur.count++; cur.rows += len; cur.jobs += (len + 15) / 16;
   }
   chunks.push_back(cur);
   // decode attention takes the sequences longest context first when there are few jobs per CU, so that the
   // launch does not end on a handful of long ones
-  for (int q = 0; q < S; ++q) s.order[q] = q;
-  std::stable_sort(s.order, s.order + S, [&](int x, int y) { return s.ctx_base[x] > s.ctx_base[y]; });
-  c->use_order = (long long)S * m.n_kv_heads <= 8192;
-  rc = stage_upload(c, s, B, S, st);
+  if (share) {
+    for (int q = 0; q < S; ++q) {
+      s.kv_off[B + q] = (int)off; s.kv_cap[B + q] = round32(max_new);
+      off += round32(max_new);
+    }
+    for (int b = 0; b < B; ++b) s.order[b] = b;
+    std::stable_sort(s.order, s.order + B, [&](int x, int y) { return prompt_lens[x] > prompt_lens[y]; });
+    c->use_order = (long long)B * m.n_kv_heads <= 8192;
+  } else {
+    for (int q = 0; q < S; ++q) s.order[q] = q;
+    std::stable_sort(s.order, s.order + S, [&](int x, int y) { return s.ctx_base[x] > s.ctx_base[y]; });
+    c->use_order = (long long)S * m.n_kv_heads <= 8192;
+  }
+  c->share_k = share ? k : 0;
+  rc = stage_upload(c, s, B, S, share ? B + S : S, st);
   if (rc) return rc;
   c->prof_used = 0;
   if (c->timed) HIPCHK(hipEventRecord(c->ev_start, st));
@@ -675,7 +705,7 @@ int rlgen_generate(rlgen_ctx* c, const int32_t* prompts, const int32_t* prompt_l
     rc = expand(c, ch, prompts, false, st);
     if (rc) return rc;
     HIPCHK(rl_embed(c->x, c->embed, prompts, c->d_tok_index, ch.rows, m.d_model, m.vocab, c->status, st));
-    rc = run_layers(c, ch.rows, false, 0, k, true, ch.jobs, st);
+    rc = run_layers(c, ch.rows, false, 0, share ? 1 : k, true, ch.jobs, st);
     if (rc) return rc;
     rc = final_norm(c, c->d_lastrow + ch.first * k, ch.count * k, S, ch.first * k, st);
     if (rc) return rc;

@@ -285,3 +285,84 @@ def test_dpo_loss_and_sequence_logprob_match_oracle():
         got = r.rlgen_dpo_loss(dev_f32(a), dev_f32(b), dev_f32(c), dev_f32(d), beta).cpu().numpy()
         ref = O.dpo_pair_loss(a.astype(np.float64), b.astype(np.float64), c.astype(np.float64), d.astype(np.float64), beta)
         assert np.abs(got - ref).max() < 1e-5 * max(1.0, np.abs(ref).max())
+
+
+# ---------------------------------------------------------------- prompt cache shared by the k samples of a prompt
+@pytest.fixture(scope="module", params=list(GPU_SHAPES))
+def shared(request):
+    m = GPU_SHAPES[request.param]
+    W = scaled_bf16_weights(m)
+    pol = make_policy(W, max_seqs=20, max_seq_len=112, max_kv_tokens=2048, max_batch_tokens=112, share_prompt_kv=1)
+    yield m, W, O.Decoder(W, m), pol
+    pol.close()
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 5])
+def test_shared_prompt_cache_matches_oracle(shared, k):
+    """The k samples of a prompt read one copy of the prompt's keys and values; 35 new tokens cross a
+    32-key block of the per-sample streams."""
+    m, W, dec, pol = shared
+    G = m.n_q_heads // m.n_kv_heads
+    rng = np.random.default_rng(40 + k)
+    B, T, temp = 4, (35 if k == 3 else 6), 0.7
+    prompts = rand_seqs(rng, m.vocab, [31, 1, 64, 70])
+    arr, lens = padded(prompts, pad=-1)
+    u = rng.random((B, k, T), dtype=np.float32)
+    r = R()
+    if k * G > 16:
+        with pytest.raises(r.RlgenError) as e:
+            r.rlgen_generate(pol, dev_i32(arr), lens, k, T, temp, dev_f32(u))
+        assert e.value.code == r.ERR_BAD_ARG
+        return
+    t_o, l_o, margins, _, _ = oracle_generate_batch(dec, arr, lens, k, T, temp, u)
+    forced = np.where(margins > MARGIN, -1, t_o).astype(np.int32)
+    t_g, l_g = r.rlgen_generate(pol, dev_i32(arr), lens, k, T, temp, dev_f32(u), dev_i32(forced))
+    t_g, l_g = t_g.cpu().numpy(), l_g.cpu().numpy()
+    report("generate-shared-forced", err=np.abs(l_g - l_o).max(), mismatches=(t_g != t_o).sum(), k=k, h=m.head_dim)
+    np.testing.assert_array_equal(t_g, t_o)
+    assert np.abs(l_g - l_o).max() < TOL_LOGPROB
+    # unforced: a valid draw under the oracle's CDF along the GPU's own path
+    t_f, l_f = r.rlgen_generate(pol, dev_i32(arr), lens, k, T, temp, dev_f32(u))
+    t_f, l_f = t_f.cpu().numpy(), l_f.cpu().numpy()
+    _, l_t, _, _, buckets = oracle_generate_batch(dec, arr, lens, k, T, temp, u, forced=t_f, with_buckets=True)
+    assert (buckets[..., 0] - MARGIN <= u).all() and (u <= buckets[..., 1] + MARGIN).all()
+    assert np.abs(l_f - l_t).max() < TOL_LOGPROB
+    # scoring (per-sequence cache, prompt-pass kernels) agrees with the shared-cache decode
+    full = [np.concatenate([prompts[b], t_f[b, j]]) for b in range(B) for j in range(k)]
+    farr, flens = padded(full)
+    sc = r.rlgen_score(pol, dev_i32(farr), flens, temp, np.repeat(lens, k)).cpu().numpy()
+    for i in range(B * k):
+        P = flens[i] - T
+        assert np.abs(sc[i, P:flens[i]] - l_f.reshape(B * k, T)[i]).max() < TOL_LOGPROB
+    # deterministic, and independent of what else is in the batch
+    order = [2, 0, 3, 1]
+    arr2, lens2 = padded([prompts[i] for i in order], pad=10 ** 7)
+    t_2, l_2 = r.rlgen_generate(pol, dev_i32(arr2), lens2, k, T, temp, dev_f32(u[order]))
+    assert np.array_equal(t_2.cpu().numpy(), t_f[order]) and np.array_equal(l_2.cpu().numpy(), l_f[order])
+    assert r.rlgen_status(pol) == 0
+
+
+def test_shared_prompt_cache_capacity(shared):
+    """Cache need = sum of prompts rounded to 32 + sequences * new tokens rounded to 32 (here against 2048)."""
+    m, W, dec, pol = shared
+    r = R()
+    arr = np.zeros((8, 100), np.int32)
+    lens = np.full(8, 100, np.int32)
+
+    def run(B, k, T):
+        return r.rlgen_generate(pol, dev_i32(arr[:B]), lens[:B], k, T, 0.7, dev_f32(np.full((B, k, T), 0.5, np.float32)))
+
+    t, l = run(8, 2, 12)                       # 8 * 128 + 16 * 32 = 1536
+    assert np.isfinite(l.cpu().numpy()).all()
+    run(8, 2, 12)
+    with pytest.raises(r.RlgenError) as e:
+        run(8, 2, 13)                          # 100 + 13 > max_seq_len
+    assert e.value.code == r.ERR_CAPACITY
+    arr = np.zeros((16, 60), np.int32)
+    lens = np.full(16, 60, np.int32)
+    run(16, 1, 40)                             # 16 * 64 + 16 * 64 = 2048
+    arr = np.zeros((16, 70), np.int32)
+    lens = np.full(16, 70, np.int32)
+    with pytest.raises(r.RlgenError) as e:
+        run(16, 1, 40)                         # 16 * 96 + 16 * 64 = 2560 (one stream per sequence would need 16 * 128)
+    assert e.value.code == r.ERR_CAPACITY
