@@ -171,7 +171,10 @@ int rlgen_dpo_loss(const float *pol_pos, const float *ref_pos, const float *pol_
 
 /* Per-phase device times of the last rlgen_generate / rlgen_score on this context, in ms (any
  * pointer may be null).  Synchronises the events it reads.  decode_attn_ms / decode_attn_launches
- * cover the decode-attention kernel alone and are filled only while profiling is on. */
+ * cover the decode-attention kernel alone and are filled only while profiling is on:
+ * rlgen_set_profiling(ctx, n) with n >= 1 brackets every n-th decode-attention launch (rotating
+ * over the layers from step to step) with events on the call's stream; decode_attn_ms is the sum
+ * over the decode_attn_launches bracketed launches.  Each bracketed launch costs about 10 us. */
 int rlgen_get_timings(rlgen_ctx *ctx, float *prefill_ms, float *decode_ms, float *decode_attn_ms,
                       int32_t *decode_attn_launches);
 int rlgen_set_profiling(rlgen_ctx *ctx, int32_t on);

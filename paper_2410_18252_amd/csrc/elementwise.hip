@@ -13,19 +13,25 @@ __global__ void to_bf16_kernel(uint16_t* dst, const void* src, int src_is_bf16, 
   for (; i < n; i += stride)
     dst[i] = src_is_bf16 ? ((const uint16_t*)src)[i] : f32_to_bf16_bits(((const float*)src)[i]);
 }
-__global__ void to_f16w_kernel(uint16_t* dst, const void* src, int src_is_bf16, int rows, int K, int rows_total, int row0) {
+__global__ void to_f16w_kernel(uint16_t* dst, const void* src, int src_is_bf16, int rows, int K, int rows_total, int row0,
+                               int perm_h, int perm_r) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const size_t n = (size_t)rows * K, stride = (size_t)gridDim.x * blockDim.x;
   for (; i < n; i += stride) {
     const uint16_t b = src_is_bf16 ? ((const uint16_t*)src)[i] : f32_to_bf16_bits(((const float*)src)[i]);
-    dst[kblk_off(row0 + (int)(i / K), (int)(i % K), rows_total)] = f32_to_f16_bits(bf16_bits_to_f32(b));
+    int row = (int)(i / K);
+    if (perm_h > 0) row = row / perm_h * perm_h + qkv_packed_pos(row % perm_h, perm_r);
+    dst[kblk_off(row0 + row, (int)(i % K), rows_total)] = f32_to_f16_bits(bf16_bits_to_f32(b));
   }
 }
-__global__ void to_f32_kernel(float* dst, const void* src, int src_is_bf16, size_t n) {
+__global__ void to_f32_kernel(float* dst, const void* src, int src_is_bf16, size_t n, int perm_h, int perm_r) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const size_t stride = (size_t)gridDim.x * blockDim.x;
-  for (; i < n; i += stride)
-    dst[i] = src_is_bf16 ? bf16_bits_to_f32(((const uint16_t*)src)[i]) : ((const float*)src)[i];
+  for (; i < n; i += stride) {
+    const float v = src_is_bf16 ? bf16_bits_to_f32(((const uint16_t*)src)[i]) : ((const float*)src)[i];
+    const size_t o = perm_h > 0 ? i / perm_h * perm_h + qkv_packed_pos((int)(i % perm_h), perm_r) : i;
+    dst[o] = v;
+  }
 }
 __global__ void pack_gate_up_kernel(uint16_t* dst, const void* gate, const void* up, int src_is_bf16, int F, int d) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -226,6 +232,54 @@ __global__ __launch_bounds__(256) void rope_v_prefill_kernel(RopeArgs a) {
   }
 }
 
+// The same from staged bf16 rows [k heads | v heads] (fused QKV projection): keys move as 16-byte units of 8 head
+// dims, values are gathered over 8 tokens as above.
+__global__ __launch_bounds__(256) void kv_prefill_kernel(RopeArgs a) {
+  const AttnJob jb = a.jobs[blockIdx.x];
+  const int per_group = a.Hkv * a.h;
+  const size_t ld = (size_t)2 * per_group;
+  const int ntok = min(16, jb.len - jb.qblock * 16);
+  const int nch = per_group >> 3;                       // 16-byte units of one token's keys (or values)
+  const float inv_h = 1.0f / (float)a.h;
+  const uint16_t* stage = a.kvstage + (size_t)(jb.row0 + jb.qblock * 16) * ld;
+  for (int item = threadIdx.x; item < ntok * nch; item += blockDim.x) {
+    const int tok = item / nch, unit = item - tok * nch;
+    const int head = (int)(((float)(unit << 3) + 0.5f) * inv_h), dim = (unit << 3) - head * a.h;
+    const u32x4 w = *(const u32x4*)(stage + (size_t)tok * ld + (unit << 3));
+    const long long o = a.lay.k_elem(jb.qblock * 16 + tok, dim);
+    for (int cpy = 0; cpy < a.ncopy; ++cpy) {
+      const int s = jb.cache_seq + cpy;
+      *(u32x4*)(a.kv + a.lay.stream(a.kv_off[s], a.kv_cap[s], head) + o) = w;
+    }
+  }
+  // values: a thread takes 8 head dims of 8 consecutive tokens (8 row-contiguous 16-byte loads), transposes them
+  // in registers and writes the 8 units (one per head dim, 8 keys each), which are 128 contiguous bytes
+  for (int item = threadIdx.x; item < 2 * nch; item += blockDim.x) {
+    const int grp = item / nch, unit = item - grp * nch;
+    if (grp * 8 >= ntok) continue;
+    const int head = (int)(((float)(unit << 3) + 0.5f) * inv_h), dim = (unit << 3) - head * a.h;
+    u32x4 b[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      b[i] = grp * 8 + i < ntok ? *(const u32x4*)(stage + (size_t)(grp * 8 + i) * ld + per_group + (unit << 3)) : u32x4{0, 0, 0, 0};
+    u32x4 w[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const uint32_t lo = b[2 * e][j >> 1], hi = b[2 * e + 1][j >> 1];
+        w[j][e] = (j & 1) ? ((lo >> 16) | (hi & 0xffff0000u)) : ((lo & 0xffffu) | (hi << 16));
+      }
+    const long long o = a.lay.v_elem(jb.qblock * 16 + grp * 8, dim);
+    for (int cpy = 0; cpy < a.ncopy; ++cpy) {
+      const int s = jb.cache_seq + cpy;
+      u32x4* dst = (u32x4*)(a.kv + a.lay.stream(a.kv_off[s], a.kv_cap[s], head) + o);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) dst[j] = w[j];
+    }
+  }
+}
+
 __global__ void sequence_logprob_kernel(const float* tlp, const int* from, const int* lens, int N, int stride, float* out) {
   const int n = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (n >= N) return;
@@ -249,15 +303,19 @@ hipError_t rl_to_bf16(uint16_t* dst, const void* src, int src_is_bf16, size_t n,
   hipLaunchKernelGGL(to_bf16_kernel, dim3(min(blocks_for(n), 65536)), dim3(TPB), 0, s, dst, src, src_is_bf16, n);
   return hipGetLastError();
 }
-hipError_t rl_to_f16w(uint16_t* dst, const void* src, int src_is_bf16, int rows, int K, int rows_total, int row0, hipStream_t s) {
+hipError_t rl_to_f16w(uint16_t* dst, const void* src, int src_is_bf16, int rows, int K, int rows_total, int row0, hipStream_t s,
+                      int perm_h, int perm_r) {
+  if (perm_h > 0 && (rows % perm_h != 0 || perm_r % 4 != 0 || perm_r > perm_h)) return hipErrorInvalidValue;
   const size_t n = (size_t)rows * K;
   if (!n) return hipSuccess;
-  hipLaunchKernelGGL(to_f16w_kernel, dim3(min(blocks_for(n), 65536)), dim3(TPB), 0, s, dst, src, src_is_bf16, rows, K, rows_total, row0);
+  hipLaunchKernelGGL(to_f16w_kernel, dim3(min(blocks_for(n), 65536)), dim3(TPB), 0, s, dst, src, src_is_bf16, rows, K, rows_total, row0,
+                     perm_h, perm_r);
   return hipGetLastError();
 }
-hipError_t rl_to_f32(float* dst, const void* src, int src_is_bf16, size_t n, hipStream_t s) {
+hipError_t rl_to_f32(float* dst, const void* src, int src_is_bf16, size_t n, hipStream_t s, int perm_h, int perm_r) {
   if (!n) return hipSuccess;
-  hipLaunchKernelGGL(to_f32_kernel, dim3(min(blocks_for(n), 65536)), dim3(TPB), 0, s, dst, src, src_is_bf16, n);
+  if (perm_h > 0 && (n % perm_h != 0 || perm_r % 4 != 0 || perm_r > perm_h)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(to_f32_kernel, dim3(min(blocks_for(n), 65536)), dim3(TPB), 0, s, dst, src, src_is_bf16, n, perm_h, perm_r);
   return hipGetLastError();
 }
 hipError_t rl_pack_gate_up(uint16_t* dst, const void* gate, const void* up, int src_is_bf16, int F, int d, hipStream_t s) {
@@ -310,6 +368,12 @@ hipError_t rl_rope_kv(const RopeArgs& a, hipStream_t s) {
   if (!total) return hipSuccess;
   hipLaunchKernelGGL(rope_kv_kernel, dim3(blocks_for(total)), dim3(TPB), 0, s, a);
   if (a.v_by_blocks && a.njobs > 0) hipLaunchKernelGGL(rope_v_prefill_kernel, dim3(a.njobs), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+hipError_t rl_kv_prefill(const RopeArgs& a, hipStream_t s) {
+  if (a.njobs <= 0) return hipSuccess;
+  if (!a.kvstage || !a.jobs || a.h % 8 != 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(kv_prefill_kernel, dim3(a.njobs), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 hipError_t rl_sequence_logprob(const float* tlp, const int* from, const int* lens, int N, int stride, float* out, hipStream_t s) {

@@ -214,6 +214,29 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f16_kernel(GemmArgs g) {
     for (int i = 0; i < TM; ++i) {
       const int row = wrow0 + i * 32 + frow;
       if (row >= g.M) continue;
+      // EPI_QKV: this row's rotary table row, its q and staging rows, and where its key / value start inside
+      // kv head 0's stream of its cache sequence (the parts of KvLayout::k_elem / v_elem that depend on the
+      // slot alone; kv heads are per_head elements apart)
+      [[maybe_unused]] const float2* rope_row = nullptr;
+      [[maybe_unused]] uint16_t *q_row = nullptr, *stage_row = nullptr, *k_row = nullptr, *v_row = nullptr;
+      [[maybe_unused]] int per_head = 0;
+      if constexpr (EPI == EPI_QKV) {
+        const QkvEpi& e = g.qe;
+        const int qpos = e.pos[row] + e.pos_add;
+        rope_row = e.table + (size_t)qpos * (e.r >> 1);
+        q_row = e.q + (size_t)row * (e.Hq * e.h);
+        if (e.kvstage) {
+          stage_row = e.kvstage + (size_t)row * (2 * e.Hkv * e.h);
+        } else {
+          const int seq = e.dst_seq[row];
+          const int slot = qpos - (e.slot_sub ? e.slot_sub[row] : 0);
+          const int cap = e.kv_cap[seq];
+          uint16_t* base = e.kv + e.lay.seq_base(e.kv_off[seq]);
+          k_row = base + e.lay.k_elem(slot, 0);
+          v_row = base + e.lay.v_elem(slot, 0);
+          per_head = 2 * cap * e.h;
+        }
+      }
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
 #pragma unroll
@@ -243,6 +266,41 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f16_kernel(GemmArgs g) {
               *(f32x4*)p = v;
             } else {
               for (int r = 0; r < 4 && col + r < g.N; ++r) p[r] = (EPI == EPI_RESID ? p[r] : 0.f) + v[r];
+            }
+          } else if constexpr (EPI == EPI_QKV) {
+            // head dims of a group of four packed columns: a rotary group holds the pairs (d0, d0 + r/2) and
+            // (d0 + 1, d0 + 1 + r/2) as (v0, v2) and (v1, v3); any other group holds four consecutive dims
+            const QkvEpi& e = g.qe;
+            const int head = (int)(((float)col + 0.5f) * e.inv_h);
+            const int p0 = col - head * e.h;
+            const bool is_v = head >= e.Hq + e.Hkv;
+            int d0 = p0, d1 = p0 + 2;                         // dims of (v0, v1) and of (v2, v3)
+            if (!is_v && p0 < e.r) {
+              d0 = p0 >> 1;
+              d1 = d0 + (e.r >> 1);
+              const f32x4 cs = *(const f32x4*)(rope_row + d0);     // cos, sin of pairs d0 and d0 + 1
+              const float lo0 = v[0] * cs[0] - v[2] * cs[1], hi0 = v[2] * cs[0] + v[0] * cs[1];
+              const float lo1 = v[1] * cs[2] - v[3] * cs[3], hi1 = v[3] * cs[2] + v[1] * cs[3];
+              v[0] = lo0; v[1] = lo1; v[2] = hi0; v[3] = hi1;
+            }
+            if (head < e.Hq) {
+              uint16_t* qp = q_row + head * e.h;
+              *(uint32_t*)(qp + d0) = pack_f16x2(v[0], v[1]);
+              *(uint32_t*)(qp + d1) = pack_f16x2(v[2], v[3]);
+            } else if (e.kvstage) {
+              // prompt pass: keys (rotated) and values as bf16 rows [k heads | v heads]; a second kernel moves them
+              // into the cache layout, to every copy, in 16-byte units
+              uint16_t* sp = stage_row + (head - e.Hq) * e.h;
+              *(uint32_t*)(sp + d0) = pack_bf16x2(v[0], v[1]);
+              *(uint32_t*)(sp + d1) = pack_bf16x2(v[2], v[3]);
+            } else if (!is_v) {
+              uint16_t* st = k_row + (size_t)(head - e.Hq) * per_head;
+              *(uint32_t*)(st + ((d0 >> 3) << 7) + (d0 & 7)) = pack_bf16x2(v[0], v[1]);
+              *(uint32_t*)(st + ((d1 >> 3) << 7) + (d1 & 7)) = pack_bf16x2(v[2], v[3]);
+            } else {
+              uint16_t* st = v_row + (size_t)(head - e.Hq - e.Hkv) * per_head + ((p0 >> 4) << 9) + ((p0 & 15) << 3);
+#pragma unroll
+              for (int r = 0; r < 4; ++r) st[r << 3] = f32_to_bf16_bits(v[r]);
             }
           } else if constexpr (EPI == EPI_GELU_F16) {
             uint16_t* p = (uint16_t*)g.out + kblk_off(row, col, g.M);     // four columns never straddle a K block
@@ -349,6 +407,13 @@ hipError_t rl_gemm_variant(const GemmArgs& g, int epi, int variant, hipStream_t 
       return launch_variant<EPI_SWIGLU_F16>(g, variant, s);
     case EPI_LMHEAD: return launch_variant<EPI_LMHEAD>(g, variant, s);
     case EPI_PARTIAL: return launch_variant<EPI_PARTIAL>(g, variant, s);
+    case EPI_QKV: {
+      const QkvEpi& e = g.qe;
+      if (e.r % 4 != 0 || e.h % 16 != 0 || g.N != (e.Hq + 2 * e.Hkv) * e.h || !e.q || !e.pos || (e.r > 0 && !e.table) ||
+          (!e.kvstage && (!e.kv || !e.dst_seq || !e.kv_off || !e.kv_cap)))
+        return hipErrorInvalidValue;
+      return launch_variant<EPI_QKV>(g, variant, s);
+    }
   }
   return hipErrorInvalidValue;
 }
@@ -377,7 +442,7 @@ hipError_t rl_gemm(const GemmArgs& g, int epi, hipStream_t s) {
   else if (tiles(256, 128) >= 200) variant = 5;
   else if (tiles(128, 128) >= 400 || wide_only) variant = 0;
   else variant = 7;
-  if (variant == 7 && g.ws) {
+  if (variant == 7 && g.ws && epi != EPI_QKV) {
     // few 64x128 tiles (three fit on a CU): cut K so that about 800 blocks exist, each keeping >= 4 K tiles;
     // with more than one tile per CU already, only a long K is worth the second pass over the partial sums
     const long long t = tiles(64, 128);

@@ -34,7 +34,35 @@ struct KvLayout {
 };
 
 // ------------------------------------------------------------------ GEMM
-enum { EPI_F32 = 0, EPI_RESID = 1, EPI_GELU_F16 = 2, EPI_SWIGLU_F16 = 3, EPI_LMHEAD = 4, EPI_PARTIAL = 5 };
+enum { EPI_F32 = 0, EPI_RESID = 1, EPI_GELU_F16 = 2, EPI_SWIGLU_F16 = 3, EPI_LMHEAD = 4, EPI_PARTIAL = 5, EPI_QKV = 6 };
+
+// Epilogue of the fused QKV projection (EPI_QKV): bias, rotary embedding and the writes of q (fp16) and of k, v
+// (bf16, into the cache) happen on the accumulators.  For that the weight rows of every query and key head are
+// stored in the order qkv_packed_dim() gives: the rotary pairs (i, i + r/2), (i + 1, i + 1 + r/2) of a head sit
+// in four consecutive output columns, which one lane holds.  Requires r % 4 == 0.
+struct QkvEpi {
+  int Hq, Hkv, h, r;
+  float inv_h;                   // 1 / h
+  const float2* table;           // [max_pos, r/2] cos, sin
+  const int* pos; int pos_add;   // position of row i = pos[i] + pos_add
+  uint16_t* q;                   // out: fp16 [M, Hq h], head dims in natural order
+  // prompt pass: k (rotated) and v as bf16 [M, 2 Hkv h] (k heads, then v heads) for rl_kv_prefill
+  uint16_t* kvstage;
+  // decode (kvstage null): k, v straight into the cache of sequence dst_seq[i] at slot position - slot_sub[i]
+  const int* dst_seq; const int* slot_sub;   // slot_sub nullable
+  uint16_t* kv; KvLayout lay; const int* kv_off; const int* kv_cap;
+};
+// head dim held by packed position p of a query / key head (identity for p >= r)
+__host__ __device__ __forceinline__ int qkv_packed_dim(int p, int r) {
+  return p >= r ? p : 2 * (p >> 2) + (p & 1) + ((p & 2) ? (r >> 1) : 0);
+}
+// and its inverse: packed position of head dim `dim`
+__host__ __device__ __forceinline__ int qkv_packed_pos(int dim, int r) {
+  if (dim >= r) return dim;
+  const int half = r >> 1, i = dim < half ? dim : dim - half;
+  return 4 * (i >> 1) + (i & 1) + (dim < half ? 0 : 2);
+}
+
 struct GemmArgs {
   const void* A;                // [M, K] fp16, K-block major (kblk_off with rows = M)
   const void* W;                // [N, K] fp16, K-block major (rows = N)
@@ -49,6 +77,7 @@ struct GemmArgs {
   float* target_logit;          // [M]
   // split-K scratch (nullable: no split-K): fp32 [splits, M, N], ws_elems floats available
   float* ws; size_t ws_elems; int splits;
+  QkvEpi qe;                    // EPI_QKV only (out / ldo unused)
 };
 hipError_t rl_gemm(const GemmArgs& g, int epi, hipStream_t s);
 // the same with an explicit tile shape (tuning and tests): 0 = 128x128, 1 = 256x128, 2 = 256x256, ...
@@ -82,9 +111,12 @@ hipError_t rl_attention_prefill(const AttnArgs& a, hipStream_t s);
 hipError_t rl_to_bf16(uint16_t* dst, const void* src, int src_is_bf16, size_t n, hipStream_t s);
 // dst fp16 K-block major [rows_total, K] <- the bf16 values of src [rows, K] row-major placed at rows
 // row0 .. row0 + rows - 1 (fp32 sources are first rounded to bf16, nearest even)
-hipError_t rl_to_f16w(uint16_t* dst, const void* src, int src_is_bf16, int rows, int K, int rows_total, int row0, hipStream_t s);
+// perm_h > 0: source row head * perm_h + dim lands at row head * perm_h + qkv_packed_pos(dim, perm_r)
+hipError_t rl_to_f16w(uint16_t* dst, const void* src, int src_is_bf16, int rows, int K, int rows_total, int row0, hipStream_t s,
+                      int perm_h = 0, int perm_r = 0);
 // dst fp32 <- src (fp32 copied, or bf16 expanded); n elements
-hipError_t rl_to_f32(float* dst, const void* src, int src_is_bf16, size_t n, hipStream_t s);
+// perm_h > 0: element head * perm_h + dim lands at head * perm_h + qkv_packed_pos(dim, perm_r)
+hipError_t rl_to_f32(float* dst, const void* src, int src_is_bf16, size_t n, hipStream_t s, int perm_h = 0, int perm_r = 0);
 // gate/up rows interleaved in blocks of 32 rows: dst [2F, d] fp16 (bf16 values), K-block major
 hipError_t rl_pack_gate_up(uint16_t* dst, const void* gate, const void* up, int src_is_bf16, int F, int d, hipStream_t s);
 // cos/sin table [max_pos, r/2] (float2), angles pos * theta^(-2i/r) evaluated in fp64
@@ -119,7 +151,10 @@ struct RopeArgs {
   uint16_t* kv; KvLayout lay; const int* kv_off; const int* kv_cap;
   // prompt pass: V is written by a second kernel, one block per 16-token job (dst_seq[row] == jobs[].cache_seq)
   int v_by_blocks; const AttnJob* jobs; int njobs;
+  const uint16_t* kvstage;       // rl_kv_prefill: bf16 [rows, 2 Hkv h], rotated k heads then v heads
 };
+// Moves the staged keys and values of a prompt pass into the cache layout, to every copy; one block per 16-token job.
+hipError_t rl_kv_prefill(const RopeArgs& a, hipStream_t s);
 hipError_t rl_rope_kv(const RopeArgs& a, hipStream_t s);
 
 // Sampling phase 2 (after the EPI_LMHEAD GEMM): per row, combine the per-64-column partials into

@@ -65,6 +65,7 @@ struct rlgen_ctx {
   SeqMeta* d_meta;
   int *d_kv_off, *d_kv_cap, *d_ctx_base, *d_iota, *d_lastrow, *d_order;
   bool use_order;
+  bool fused_qkv;         // rotary_dim % 4 == 0: rotary embedding and cache writes run in the QKV GEMM's epilogue
   int share_k;            // samples per prompt of the running generate call when prompts share their cache, else 0
   int *d_tok_index, *d_pos, *d_dst_seq, *d_lm_row, *d_target, *d_out_index, *d_next_token;
   AttnJob* d_jobs;
@@ -81,7 +82,7 @@ struct rlgen_ctx {
   // timings
   hipEvent_t ev_start, ev_mid, ev_end;
   bool timed;
-  bool profiling;
+  int profiling;          // n > 0: every n-th decode-attention launch is bracketed with events
   std::vector<hipEvent_t> prof_events;
   size_t prof_used;
   // tile shape and K split of each linear layer, measured at creation: [decode | prompt pass][which GEMM]
@@ -197,8 +198,10 @@ int pack_weights(rlgen_ctx* c, const rlgen_weights* w, hipStream_t st) {
     LayerW& L = c->layers[l];
     HIPCHK(rl_to_f32(L.n1g, s.norm1_g, bf, d, st));
     HIPCHK(rl_to_f32(L.n2g, s.norm2_g, bf, d, st));
-    HIPCHK(rl_to_f16w(L.wqkv, s.wq, bf, (int)qd, (int)d, nqkv, 0, st));
-    HIPCHK(rl_to_f16w(L.wqkv, s.wk, bf, (int)kvd, (int)d, nqkv, (int)qd, st));
+    // fused QKV epilogue: query and key rows of a head in the order that puts rotary pairs side by side
+    const int ph = c->fused_qkv ? (int)h : 0, pr = m.rotary_dim;
+    HIPCHK(rl_to_f16w(L.wqkv, s.wq, bf, (int)qd, (int)d, nqkv, 0, st, ph, pr));
+    HIPCHK(rl_to_f16w(L.wqkv, s.wk, bf, (int)kvd, (int)d, nqkv, (int)qd, st, ph, pr));
     HIPCHK(rl_to_f16w(L.wqkv, s.wv, bf, (int)kvd, (int)d, nqkv, (int)(qd + kvd), st));
     HIPCHK(rl_to_f16w(L.wo, s.wo, bf, (int)d, (int)qd, (int)d, 0, st));
     HIPCHK(rl_to_f16w(L.wdown, s.w_down, bf, (int)d, (int)F, (int)d, 0, st));
@@ -208,8 +211,8 @@ int pack_weights(rlgen_ctx* c, const rlgen_weights* w, hipStream_t st) {
       HIPCHK(rl_to_f16w(L.wup, s.w_up, bf, (int)F, (int)d, (int)F, 0, st));
       HIPCHK(rl_to_f32(L.n1b, s.norm1_b, bf, d, st));
       HIPCHK(rl_to_f32(L.n2b, s.norm2_b, bf, d, st));
-      HIPCHK(rl_to_f32(L.bqkv, s.bq, bf, qd, st));
-      HIPCHK(rl_to_f32(L.bqkv + qd, s.bk, bf, kvd, st));
+      HIPCHK(rl_to_f32(L.bqkv, s.bq, bf, qd, st, ph, pr));
+      HIPCHK(rl_to_f32(L.bqkv + qd, s.bk, bf, kvd, st, ph, pr));
       HIPCHK(rl_to_f32(L.bqkv + qd + kvd, s.bv, bf, kvd, st));
       HIPCHK(rl_to_f32(L.bo, s.bo, bf, d, st));
       HIPCHK(rl_to_f32(L.bup, s.b_up, bf, F, st));
@@ -237,6 +240,19 @@ __global__ void expand_kernel(const SeqMeta* meta, int first, const int* tokens,
       target[i] = tokens[m.src_off + t];
       out_index[i] = m.out_off + t;
     }
+  }
+}
+// Row arrays for the timing runs of the fused QKV projection: consecutive rows belong to different cache sequences
+// (as in a decode step), row i being slot (i / nseq) % npos of sequence i % nseq.
+__global__ void tune_rows_kernel(int* pos, int* dst_seq, int* kv_off, int* kv_cap, int rows, int nseq, int npos) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < rows) {
+    dst_seq[i] = i % nseq;
+    pos[i] = (i / nseq) % npos;
+  }
+  if (i < nseq) {
+    kv_off[i] = 32 * i;
+    kv_cap[i] = 32;
   }
 }
 __global__ void fill_f32_kernel(float* p, size_t n, float v) {
@@ -272,6 +288,14 @@ hipError_t gemm(rlgen_ctx* c, int which, bool decode, const GemmArgs& g, int epi
   return run_choice(g, epi, ch.variant, ch.splits, st);
 }
 
+QkvEpi qkv_epilogue(const RopeArgs& r, uint16_t* kvstage) {
+  QkvEpi e{};
+  e.Hq = r.Hq; e.Hkv = r.Hkv; e.h = r.h; e.r = r.r; e.inv_h = 1.0f / (float)r.h;
+  e.table = r.table; e.pos = r.pos; e.pos_add = r.pos_add; e.slot_sub = r.slot_sub; e.dst_seq = r.dst_seq;
+  e.q = r.q; e.kv = r.kv; e.lay = r.lay; e.kv_off = r.kv_off; e.kv_cap = r.kv_cap; e.kvstage = kvstage;
+  return e;
+}
+
 // One pass of all decoder blocks over `rows` packed rows held in c->x.
 //  decode: rows are sequences 0..rows-1 at step t (the token drawn at step t-1 enters at position
 //          ctx_base + t - 1); otherwise rows follow d_pos / d_dst_seq / d_jobs of the current chunk.
@@ -288,7 +312,6 @@ int run_layers(rlgen_ctx* c, int rows, bool decode, int t, int ncopy, bool use_c
     GemmArgs g{};
     g.A = c->n1; g.W = L.wqkv; g.M = rows; g.N = nqkv; g.K = d;
     g.bias = llama ? nullptr : L.bqkv; g.out = c->qkv; g.ldo = nqkv; g.ws = c->splitk; g.ws_elems = c->splitk_elems;
-    HIPCHK(gemm(c, G_QKV, decode, g, EPI_F32, st));
     RopeArgs r{};
     r.qkv = c->qkv; r.rows = rows; r.Hq = m.n_q_heads; r.Hkv = m.n_kv_heads; r.h = h; r.r = m.rotary_dim;
     r.table = c->rope; r.q = c->q; r.kv = kvl; r.lay = c->lay; r.kv_off = c->d_kv_off; r.kv_cap = c->d_kv_cap;
@@ -297,7 +320,19 @@ int run_layers(rlgen_ctx* c, int rows, bool decode, int t, int ncopy, bool use_c
       r.slot_sub = c->share_k ? c->d_ctx_base : nullptr;     // new tokens start at slot 0 of their own stream
     }
     else { r.pos = c->d_pos; r.pos_add = 0; r.dst_seq = c->d_dst_seq; r.ncopy = ncopy; r.v_by_blocks = 1; r.jobs = c->d_jobs; r.njobs = njobs; }
-    HIPCHK(rl_rope_kv(r, st));
+    if (c->fused_qkv) {
+      // the prompt pass leaves k and v as bf16 rows in the (otherwise unused) fp32 qkv buffer for the block-wise writer
+      g.qe = qkv_epilogue(r, decode ? nullptr : (uint16_t*)c->qkv);
+      g.ws = nullptr;
+      HIPCHK(gemm(c, G_QKV, decode, g, EPI_QKV, st));
+      if (!decode) {
+        r.kvstage = (const uint16_t*)c->qkv;
+        HIPCHK(rl_kv_prefill(r, st));
+      }
+    } else {
+      HIPCHK(gemm(c, G_QKV, decode, g, EPI_F32, st));
+      HIPCHK(rl_rope_kv(r, st));
+    }
     AttnArgs a{};
     a.q = c->q; a.q_ld = qd; a.out = c->attn; a.out_rows = rows; a.kv = kvl; a.lay = c->lay;
     a.kv_off = c->d_kv_off; a.kv_cap = c->d_kv_cap; a.Hq = m.n_q_heads; a.scale = 1.0f / sqrtf((float)h);
@@ -305,7 +340,7 @@ int run_layers(rlgen_ctx* c, int rows, bool decode, int t, int ncopy, bool use_c
       a.ctx_base = c->d_ctx_base; a.ctx_add = t; a.S = rows; a.order = c->use_order ? c->d_order : nullptr;
       a.share_k = c->share_k;
       hipEvent_t e0 = nullptr, e1 = nullptr;
-      if (c->profiling) {
+      if (c->profiling > 0 && (l + t) % c->profiling == 0) {
         while (c->prof_events.size() < c->prof_used + 2) {
           hipEvent_t e;
           HIPCHK(hipEventCreate(&e));
@@ -380,6 +415,12 @@ int tune_gemms(rlgen_ctx* c, hipStream_t st) {
   HIPCHK(rl_fill_random_f16(c->act, kblk_elems(c->R, F), 14, st));
   HIPCHK(rl_fill_random_f16(c->hfin, kblk_elems(c->LM, d), 15, st));
   HIPCHK(rl_fill_zero(c->x, align_up((size_t)c->R * d * 4, 16), st));
+  {
+    const int tseq = (int)std::min<long long>(m.max_seqs, m.max_kv_tokens / 32);
+    hipLaunchKernelGGL(tune_rows_kernel, dim3((c->R + 255) / 256), dim3(256), 0, st, c->d_pos, c->d_dst_seq, c->d_kv_off,
+                       c->d_kv_cap, c->R, tseq, std::min(32, m.max_seq_len));
+    HIPCHK(hipGetLastError());
+  }
   hipEvent_t e0, e1;
   HIPCHK(hipEventCreate(&e0));
   HIPCHK(hipEventCreate(&e1));
@@ -392,7 +433,19 @@ int tune_gemms(rlgen_ctx* c, hipStream_t st) {
       g.M = mode == 0 ? m.max_seqs : c->R;
       g.ws = c->splitk; g.ws_elems = c->splitk_elems;
       switch (which) {
-        case G_QKV: g.A = c->n1; g.W = L.wqkv; g.N = nqkv; g.K = d; g.bias = llama ? nullptr : L.bqkv; g.out = c->qkv; g.ldo = nqkv; epi = EPI_F32; break;
+        case G_QKV:
+          g.A = c->n1; g.W = L.wqkv; g.N = nqkv; g.K = d; g.bias = llama ? nullptr : L.bqkv; g.out = c->qkv; g.ldo = nqkv; epi = EPI_F32;
+          if (c->fused_qkv) {
+            // rows spread over `tseq` cache sequences of 32 slots each, as tune_rows_kernel laid out
+            RopeArgs r{};
+            r.Hq = m.n_q_heads; r.Hkv = m.n_kv_heads; r.h = m.head_dim; r.r = m.rotary_dim; r.table = c->rope; r.q = c->q;
+            r.kv = c->kv; r.lay = c->lay; r.kv_off = c->d_kv_off; r.kv_cap = c->d_kv_cap;
+            r.pos = c->d_pos; r.dst_seq = c->d_dst_seq; r.ncopy = 1;
+            g.qe = qkv_epilogue(r, mode == 0 ? nullptr : (uint16_t*)c->qkv);
+            g.ws = nullptr;          // the fused epilogue has no split-K form
+            epi = EPI_QKV;
+          }
+          break;
         case G_O: g.A = c->attn; g.W = L.wo; g.N = d; g.K = qd; g.bias = llama ? nullptr : L.bo; g.out = c->x; g.ldo = d; epi = EPI_RESID; break;
         case G_UP: g.A = c->n2; g.W = L.wup; g.N = llama ? 2 * F : F; g.K = d; g.bias = llama ? nullptr : L.bup; g.out = c->act; g.ldo = F;
                    epi = llama ? EPI_SWIGLU_F16 : EPI_GELU_F16; break;
@@ -408,7 +461,7 @@ int tune_gemms(rlgen_ctx* c, hipStream_t st) {
       if (!wide_only) {
         cands.push_back({7, 1});
         const long long t7 = (long long)((g.M + 63) / 64) * ((g.N + 127) / 128);
-        if (g.ws && t7 <= 1024)
+        if (g.ws && t7 <= 1024 && epi != EPI_QKV)
           for (int sp : {2, 3, 4, 6, 8})
             if (nk / sp >= 4 && (size_t)sp * g.M * g.N <= g.ws_elems) cands.push_back({7, sp});
       }
@@ -607,13 +660,14 @@ int rlgen_create(const rlgen_model_cfg* cfg, const rlgen_weights* weights, void*
       hipEventCreate(&c->ev_end) != hipSuccess)
     return fail(RLGEN_ERR_DEVICE);
   c->timed = true;
+  c->fused_qkv = cfg->rotary_dim % 4 == 0 && !getenv("RLGEN_UNFUSED_QKV");
   rc = pack_weights(c, weights, st);
   if (rc) return fail(rc);
+  if (rl_rope_table(c->rope, cfg->max_seq_len, cfg->rotary_dim, cfg->rope_theta, st) != hipSuccess) return fail(RLGEN_ERR_DEVICE);
   for (auto& row : c->tuned) for (auto& ch : row) ch = {-1, 1};
   rc = tune_gemms(c, st);
   if (rc) return fail(rc);
   if (rl_fill_zero(c->status, 256, st) != hipSuccess) return fail(RLGEN_ERR_DEVICE);
-  if (rl_rope_table(c->rope, cfg->max_seq_len, cfg->rotary_dim, cfg->rope_theta, st) != hipSuccess) return fail(RLGEN_ERR_DEVICE);
   // The cache must hold finite values everywhere: a partly filled super-block is read whole and the
   // unused keys are masked to probability zero, which only cancels finite values.
   if (rl_fill_zero(c->kv, (size_t)c->lay.layer_stride * cfg->n_layers * 2, st) != hipSuccess) return fail(RLGEN_ERR_DEVICE);
@@ -788,7 +842,7 @@ int rlgen_get_timings(rlgen_ctx* c, float* prefill_ms, float* decode_ms, float* 
 
 int rlgen_set_profiling(rlgen_ctx* c, int32_t on) {
   if (!c) return RLGEN_ERR_NULL;
-  c->profiling = on != 0;
+  c->profiling = on > 0 ? on : 0;
   if (!on) c->prof_used = 0;
   return RLGEN_OK;
 }

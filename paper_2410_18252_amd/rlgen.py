@@ -259,8 +259,9 @@ def rlgen_get_timings(p: Policy):
     return {"prefill_ms": a.value, "decode_ms": b.value, "decode_attn_ms": c.value, "decode_attn_launches": n.value}
 
 
-def rlgen_set_profiling(p: Policy, on: bool):
-    _check(lib.rlgen_set_profiling(p.ctx, 1 if on else 0), "rlgen_set_profiling")
+def rlgen_set_profiling(p: Policy, every: int):
+    """every >= 1: bracket every `every`-th decode-attention launch with events; 0 / False: off."""
+    _check(lib.rlgen_set_profiling(p.ctx, int(every)), "rlgen_set_profiling")
 
 
 def rlgen_status(p: Policy) -> int:

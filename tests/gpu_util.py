@@ -29,6 +29,7 @@ def R():
 GPU_SHAPES = {
     "neox-h16-raggedV": ModelShape(ARCH_NEOX, 2, 64, 4, 4, 16, 128, 200, rotary_dim=4),
     "neox-h80": ModelShape(ARCH_NEOX, 2, 160, 2, 2, 80, 320, 321, rotary_dim=20),
+    "neox-h32-rot6": ModelShape(ARCH_NEOX, 2, 64, 2, 2, 32, 128, 150, rotary_dim=6),     # rotary_dim % 4 != 0: unfused rotary path
     "neox-h256": ModelShape(ARCH_NEOX, 1, 256, 1, 1, 256, 256, 130, rotary_dim=64),
     "llama-gqa4-h16": ModelShape(ARCH_LLAMA, 2, 128, 8, 2, 16, 96, 500, rotary_dim=16, rope_theta=500000.0),
     "llama-gqa2-h128": ModelShape(ARCH_LLAMA, 2, 256, 2, 1, 128, 64, 64, rotary_dim=128, rope_theta=500000.0),
