@@ -242,8 +242,15 @@ __global__ __launch_bounds__(256) void kv_prefill_kernel(RopeArgs a) {
   const int nch = per_group >> 3;                       // 16-byte units of one token's keys (or values)
   const float inv_h = 1.0f / (float)a.h;
   const uint16_t* stage = a.kvstage + (size_t)(jb.row0 + jb.qblock * 16) * ld;
-  for (int item = threadIdx.x; item < ntok * nch; item += blockDim.x) {
-    const int tok = item / nch, unit = item - tok * nch;
+  // the job's items are spread over gridDim.y blocks: the copies are latency-bound, so more blocks in flight
+  const int first = threadIdx.x + blockDim.x * blockIdx.y, step = blockDim.x * gridDim.y;
+  // keys: items ordered as the cache stores them -- (head, 8-dim chunk, t, row) with 8 rows of a 16-token job
+  // contiguous -- so that eight lanes write one 128-byte line; the staged rows are read in 16-byte pieces
+#pragma unroll 2
+  for (int item = first; item < 16 * nch; item += step) {
+    const int r8 = item & 7, t = (item >> 3) & 1, unit = item >> 4;
+    const int tok = 8 * (r8 >> 2) + 4 * t + (r8 & 3);
+    if (tok >= ntok) continue;
     const int head = (int)(((float)(unit << 3) + 0.5f) * inv_h), dim = (unit << 3) - head * a.h;
     const u32x4 w = *(const u32x4*)(stage + (size_t)tok * ld + (unit << 3));
     const long long o = a.lay.k_elem(jb.qblock * 16 + tok, dim);
@@ -254,7 +261,7 @@ __global__ __launch_bounds__(256) void kv_prefill_kernel(RopeArgs a) {
   }
   // values: a thread takes 8 head dims of 8 consecutive tokens (8 row-contiguous 16-byte loads), transposes them
   // in registers and writes the 8 units (one per head dim, 8 keys each), which are 128 contiguous bytes
-  for (int item = threadIdx.x; item < 2 * nch; item += blockDim.x) {
+  for (int item = first; item < 2 * nch; item += step) {
     const int grp = item / nch, unit = item - grp * nch;
     if (grp * 8 >= ntok) continue;
     const int head = (int)(((float)(unit << 3) + 0.5f) * inv_h), dim = (unit << 3) - head * a.h;
@@ -373,7 +380,7 @@ hipError_t rl_rope_kv(const RopeArgs& a, hipStream_t s) {
 hipError_t rl_kv_prefill(const RopeArgs& a, hipStream_t s) {
   if (a.njobs <= 0) return hipSuccess;
   if (!a.kvstage || !a.jobs || a.h % 8 != 0) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(kv_prefill_kernel, dim3(a.njobs), dim3(256), 0, s, a);
+  hipLaunchKernelGGL(kv_prefill_kernel, dim3(a.njobs, 8), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 hipError_t rl_sequence_logprob(const float* tlp, const int* from, const int* lens, int N, int stride, float* out, hipStream_t s) {

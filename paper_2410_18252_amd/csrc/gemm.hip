@@ -54,14 +54,23 @@ __device__ __forceinline__ float erf_as(float x) {
 __device__ __forceinline__ float gelu_erf(float v) { return 0.5f * v * (1.0f + erf_as(v * 0.70710678118654752f)); }
 __device__ __forceinline__ float silu(float v) { return v / (1.0f + __expf(-v)); }
 
-template <int BM, int BN, int WM, int WN, int EPI, bool KTAIL>
+template <int N>
+__device__ __forceinline__ void wait_loads_then_barrier() {
+  // all but the N most recent vector-memory loads of this wave have landed; then every wave of the block is here
+  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
+// NS = 0: tiles travel global -> registers -> LDS (two LDS stages).  NS >= 2: NS LDS stages filled by direct
+// global -> LDS loads, issued NS - 1 K steps ahead (needs K % 64 == 0).
+template <int BM, int BN, int WM, int WN, int EPI, bool KTAIL, int NS = 0>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_f16_kernel(GemmArgs g) {
   constexpr int NT = WM * WN * 64;               // threads
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;   // 32x32 MFMA tiles per wave in each direction
   constexpr int RPP = NT / 8;                    // rows covered by one pass of 16-byte loads
   constexpr int PA = BM / RPP, PB = BN / RPP;
   static_assert(PA >= 1 && PB >= 1 && TM >= 1 && TN >= 1, "tile too small for the thread count");
-  extern __shared__ __attribute__((aligned(16))) uint16_t lds[];   // 2 x (BM + BN) x BK
+  static_assert(NS == 0 || (NS >= 2 && NS <= 4 && !KTAIL), "direct loads need whole K tiles");
+  extern __shared__ __attribute__((aligned(16))) uint16_t lds[];   // max(2, NS) x (BM + BN) x BK
   constexpr int STAGE = (BM + BN) * BK;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -132,18 +141,12 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f16_kernel(GemmArgs g) {
   const int nk_all = (g.K + BK - 1) / BK;
   const int kt0 = (int)((long long)split * nk_all / splits);          // this block's share of the K tiles
   const int nk = (int)((long long)(split + 1) * nk_all / splits);
-  load_global(kt0);
-  store_lds(kt0 & 1);
-  __syncthreads();
-
   const int frow = lane & 31, fhalf = lane >> 5;
-  for (int kt = kt0; kt < nk; ++kt) {
-    const int cur = kt & 1;
-    if (kt + 1 < nk) load_global(kt + 1);
-    const uint16_t* la = lds + cur * STAGE + (wm * (BM / WM)) * BK;
-    const uint16_t* lb = lds + cur * STAGE + BM * BK + (wn * (BN / WN)) * BK;
-    // fragments of step kk + 1 are fetched from LDS while the MFMAs of step kk run; the next tile moves
-    // from registers to the other LDS buffer under the last MFMAs of this one
+  // one K step on the LDS stage `buf`; `mid` runs between the last two MFMA groups
+  auto k_step = [&](int buf, auto&& mid) {
+    const uint16_t* la = lds + buf * STAGE + (wm * (BM / WM)) * BK;
+    const uint16_t* lb = lds + buf * STAGE + BM * BK + (wn * (BN / WN)) * BK;
+    // fragments of step kk + 1 are fetched from LDS while the MFMAs of step kk run
     f16x8 fa[2][TM], fb[2][TN];
     auto load_frags = [&](int kk, int slot) {
       const int chunk = kk * 2 + fhalf;
@@ -162,14 +165,65 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f16_kernel(GemmArgs g) {
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
       if (kk + 1 < BK / 16) load_frags(kk + 1, (kk + 1) & 1);
-      if (kk == BK / 16 - 2 && kt + 1 < nk) store_lds(cur ^ 1);
+      if (kk == BK / 16 - 2) mid();
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[kk & 1][j], fa[kk & 1][i], acc[i][j], 0, 0, 0);
     }
+  };
+
+  if constexpr (NS == 0) {
+    load_global(kt0);
+    store_lds(kt0 & 1);
     __syncthreads();
+    for (int kt = kt0; kt < nk; ++kt) {
+      const int cur = kt & 1;
+      if (kt + 1 < nk) load_global(kt + 1);
+      // the next tile moves from registers to the other LDS buffer under the last MFMAs of this one
+      k_step(cur, [&] { if (kt + 1 < nk) store_lds(cur ^ 1); });
+      __syncthreads();
+    }
+  } else {
+    // Direct loads: a wave instruction moves 64 16-byte chunks = 8 tile rows into 1 KB of LDS in lane order, so
+    // the XOR swizzle is applied on the source side: the lane that fills chunk position p of row r fetches chunk
+    // p ^ swz(r).  Rows advance by a multiple of 16 per pass, which leaves swz(r) unchanged.
+    static_assert(RPP % 16 == 0, "the swizzle must not depend on the pass");
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const int lrow = wave_u * 8 + (lane >> 3);
+    const int schunk = (lane & 7) ^ swz(lrow);
+    const uint16_t* qa[PA];
+    const uint16_t* qb[PB];
+#pragma unroll
+    for (int i = 0; i < PA; ++i) qa[i] = A + (size_t)min(row0 + lrow + RPP * i, g.M - 1) * 64 + schunk * 8;
+#pragma unroll
+    for (int i = 0; i < PB; ++i) qb[i] = W + (size_t)min(col0 + lrow + RPP * i, g.N - 1) * 64 + schunk * 8;
+    typedef const __attribute__((address_space(1))) void* gptr_t;
+    typedef __attribute__((address_space(3))) void* lptr_t;
+    auto issue = [&](int kt, int buf) {
+      uint16_t* la = lds + buf * STAGE + wave_u * 8 * BK;
+#pragma unroll
+      for (int i = 0; i < PA; ++i)
+        __builtin_amdgcn_global_load_lds((gptr_t)(qa[i] + kt * ka), (lptr_t)(la + i * RPP * BK), 16, 0, 0);
+#pragma unroll
+      for (int i = 0; i < PB; ++i)
+        __builtin_amdgcn_global_load_lds((gptr_t)(qb[i] + kt * kw), (lptr_t)(la + (BM + i * RPP) * BK), 16, 0, 0);
+    };
+    constexpr int L = PA + PB;                      // loads per wave and stage
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s)
+      if (kt0 + s < nk) issue(kt0 + s, s);
+    for (int kt = kt0; kt < nk; ++kt) {
+      // stage kt must have landed; up to NS - 2 younger stages may still be in flight
+      const int younger = min(nk - 1 - kt, NS - 2);
+      if (younger >= 2) wait_loads_then_barrier<2 * L>();
+      else if (younger == 1) wait_loads_then_barrier<L>();
+      else wait_loads_then_barrier<0>();
+      // every wave has left stage kt - 1: its buffer takes stage kt + NS - 1
+      if (kt + NS - 1 < nk) issue(kt + NS - 1, (kt - kt0 + NS - 1) % NS);
+      k_step((kt - kt0) % NS, [] {});
+    }
   }
 
   // ---- epilogue.  The products were issued as W_tile . A_tile^T, so acc[i][j][e] is C[m][n] with
@@ -352,26 +406,29 @@ __global__ void splitk_epilogue_kernel(GemmArgs g) {
   }
 }
 
-template <int BM, int BN, int WM, int WN, int EPI, bool KTAIL>
+template <int BM, int BN, int WM, int WN, int EPI, bool KTAIL, int NS = 0>
 hipError_t launch_k(const GemmArgs& g, hipStream_t s) {
-  constexpr size_t lds_bytes = 2 * (size_t)(BM + BN) * BK * sizeof(uint16_t);
+  constexpr size_t lds_bytes = (NS ? NS : 2) * (size_t)(BM + BN) * BK * sizeof(uint16_t);
+  static_assert(lds_bytes <= 160 * 1024, "LDS of one CU");
   static bool configured = false;
   if (!configured) {
     if (lds_bytes > 65536) {
-      hipError_t e = hipFuncSetAttribute((const void*)gemm_f16_kernel<BM, BN, WM, WN, EPI, KTAIL>,
+      hipError_t e = hipFuncSetAttribute((const void*)gemm_f16_kernel<BM, BN, WM, WN, EPI, KTAIL, NS>,
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
       if (e != hipSuccess) return e;
     }
     configured = true;
   }
   const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN) * (EPI == EPI_PARTIAL ? g.splits : 1);
-  hipLaunchKernelGGL((gemm_f16_kernel<BM, BN, WM, WN, EPI, KTAIL>), dim3(tiles), dim3(WM * WN * 64), lds_bytes, s, g);
+  hipLaunchKernelGGL((gemm_f16_kernel<BM, BN, WM, WN, EPI, KTAIL, NS>), dim3(tiles), dim3(WM * WN * 64), lds_bytes, s, g);
   return hipGetLastError();
 }
 
+// Whole K tiles take the direct-load pipeline with two LDS stages (more stages measured slower: the extra LDS
+// costs a resident block); a ragged K falls back to register staging, which can zero-fill the tail.
 template <int BM, int BN, int WM, int WN, int EPI>
 hipError_t launch(const GemmArgs& g, hipStream_t s) {
-  return g.K % BK == 0 ? launch_k<BM, BN, WM, WN, EPI, false>(g, s) : launch_k<BM, BN, WM, WN, EPI, true>(g, s);
+  return g.K % BK == 0 ? launch_k<BM, BN, WM, WN, EPI, false, 2>(g, s) : launch_k<BM, BN, WM, WN, EPI, true, 0>(g, s);
 }
 
 template <int EPI>
