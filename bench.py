@@ -45,6 +45,7 @@ def main():
                     help="do not bracket the decode-attention launches with HIP events (for rocprofv3 --pmc runs)")
     ap.add_argument("--share-prompt-kv", action="store_true",
                     help="the k samples of a prompt read one copy of the prompt's keys/values (not the headline layout)")
+    ap.add_argument("--max-batch-tokens", type=int, default=0, help="rows per prompt-pass chunk (0 = the library's default)")
     ap.add_argument("--k", type=int, default=0, help="override the workload's samples per prompt")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -72,7 +73,8 @@ def main():
     r32 = lambda n: (int(n) + 31) // 32 * 32
     kv_tokens = int(sum(r32(n) + k * r32(T) for n in lens)) if share else int(sum(k * r32(int(n) + T) for n in lens))
     cfg = R.make_cfg(m, weight_dtype=R.DTYPE_BF16 if W.is_bf16 else R.DTYPE_F32, max_seqs=S,
-                     max_seq_len=int(lens.max()) + T, max_kv_tokens=kv_tokens, share_prompt_kv=share)
+                     max_seq_len=int(lens.max()) + T, max_kv_tokens=kv_tokens, share_prompt_kv=share,
+                     max_batch_tokens=args.max_batch_tokens)
     dev = R.upload_weights(W.tensors)
     pol = R.Policy(cfg, dev)
     del dev
@@ -123,13 +125,22 @@ def main():
     # with a shared prompt cache a launch reads each prompt's keys once, and t new keys per sequence
     keys = (lambda t: int(lens.astype(np.int64).sum()) + S * t) if share else (lambda t: int((seq_len + t).sum()))
     bytes_per_launch = np.mean([per_key * keys(t) + qo for t in range(1, T)]) if T > 1 else 0.0
-    attn_us = 1e3 * attn_ms / max(attn_launches, 1)
-    achieved = bytes_per_launch / (attn_us * 1e-6) / 1e9 if attn_launches else 0.0
-    roofline = {"bound": "hbm", "kernel": "attention_kernel<HD,decode>", "achieved": round(achieved, 1),
+    # A batch of >= 256 sequences decodes as two halves on two streams: every layer and step then has two attention
+    # launches, each over half of the bytes, running beside the other half's linear layers.
+    halves = max(1, round(attn_launches * EVENT_EVERY / max(1, args.steps * m.n_layers * (T - 1))))
+    bytes_per_launch /= halves
+
+    def roofline_of(ms, launches, extra):
+        us = 1e3 * ms / max(launches, 1)
+        achieved = bytes_per_launch / (us * 1e-6) / 1e9 if launches else 0.0
+        return {"bound": "hbm", "kernel": "attention_kernel<HD,decode>", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": int(round(TRAFFIC_OVER_ALGORITHMIC * bytes_per_launch)) if args.config == 4 and not share and not args.k else None,
-                "algorithmic_bytes_per_launch": int(bytes_per_launch),
-                "avg_launch_us": round(attn_us, 2), "launches": attn_launches}
+                "algorithmic_bytes_per_launch": int(bytes_per_launch), "avg_launch_us": round(us, 2), "launches": launches, **extra}
+
+    roofline = roofline_of(attn_ms, attn_launches, {
+        "launches_per_layer_and_step": halves,
+        "concurrency": "timed region: each launch shares the GPU with the other half's GEMMs" if halves > 1 else "none"})
 
     # whole decode phase: weights once per step + KV, over the measured decode time
     wbytes = 2 * (m.n_params - m.vocab * m.d_model)                # all matrices but the embedding table
@@ -150,6 +161,18 @@ def main():
         "setup_s": round(setup_s, 1),
         "roofline": roofline,
     }
+    if halves > 1 and not args.no_kernel_events:
+        # the same kernel with nothing beside it: one more pass (not part of `value`) with the two-stream decode
+        # switched off, so that a launch covers the whole batch and runs alone
+        R.rlgen_set_decode_split(pol, False)
+        R.rlgen_set_profiling(pol, EVENT_EVERY)
+        step()
+        tm = R.rlgen_get_timings(pol)
+        R.rlgen_set_profiling(pol, 0)
+        R.rlgen_set_decode_split(pol, True)
+        bytes_per_launch *= halves
+        result["roofline_kernel_alone"] = roofline_of(tm["decode_attn_ms"], tm["decode_attn_launches"], {
+            "decode_ms": round(tm["decode_ms"], 2), "concurrency": "extra pass, whole batch per launch, single stream"})
 
     if not args.no_cpu_baseline:
         from oracle import decoder as O

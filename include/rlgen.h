@@ -68,7 +68,7 @@ typedef struct {
   int64_t max_kv_tokens;   /* capacity: sum over sequences of (prompt_len + max_new) rounded up
                               to a multiple of 32                                                */
   int32_t max_batch_tokens;/* rows processed at once by prefill / score; >= max_seq_len;
-                              0 selects a default                                                */
+                              0 selects a default (32768, or max_seqs * max_seq_len if smaller)      */
   int32_t share_prompt_kv; /* 0: every sequence owns a contiguous cache holding prompt and new tokens.
                               1: rlgen_generate stores a prompt's keys/values once and its k samples
                               read them together (the k samples of a prompt condition on the same
@@ -178,6 +178,13 @@ int rlgen_dpo_loss(const float *pol_pos, const float *ref_pos, const float *pol_
 int rlgen_get_timings(rlgen_ctx *ctx, float *prefill_ms, float *decode_ms, float *decode_attn_ms,
                       int32_t *decode_attn_launches);
 int rlgen_set_profiling(rlgen_ctx *ctx, int32_t on);
+
+/* rlgen_generate decodes a batch of 256 or more sequences as two halves on two internal streams
+ * (forked from and joined to the call's stream), so that one half's cache-streaming attention runs
+ * beside the other half's linear layers.  on = 0 turns that off for later calls on this context
+ * (every kernel then runs alone on the call's stream, which is what a per-kernel measurement
+ * needs); on != 0 turns it back on.  Results do not depend on it. */
+int rlgen_set_decode_split(rlgen_ctx *ctx, int32_t on);
 
 /* Synchronises `hip_stream` and returns RLGEN_ERR_DEVICE if a kernel has flagged a bad token id or
  * uniform since the context was created (sticky), else RLGEN_OK. */

@@ -63,7 +63,7 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a) {
       qrow = u * a.share_k + j;
       seq0 = u;
       len0 = a.ctx_base[u * a.share_k];
-      sfx_seq0 = units + u * a.share_k;
+      sfx_seq0 = a.sfx_first + u * a.share_k;
       sfx_len = a.ctx_add;
       nseg = 1 + a.share_k;
       store_col = c < G * a.share_k;

@@ -98,8 +98,8 @@ struct AttnArgs {
   const int* ctx_base; int ctx_add; int S;
   const int* order;                   // nullable [S] (or [prompts] when share_k): unit handled by slot i
   // shared prompt cache: 0 = off.  K = samples per prompt: sequence s = prompt * K + j; cache sequence `prompt`
-  // holds the prompt's keys (ctx_base[prompt * K] of them), cache sequence S / K + s the ctx_add new tokens of s
-  int share_k;
+  // holds the prompt's keys (ctx_base[prompt * K] of them), cache sequence sfx_first + s the ctx_add new tokens of s
+  int share_k, sfx_first;
   // prefill
   const AttnJob* jobs; int njobs;
 };

@@ -69,11 +69,26 @@ struct rlgen_ctx {
   int share_k;            // samples per prompt of the running generate call when prompts share their cache, else 0
   int *d_tok_index, *d_pos, *d_dst_seq, *d_lm_row, *d_target, *d_out_index, *d_next_token;
   AttnJob* d_jobs;
-  // activations
+  // activations: the set in use (see Bufs / use_set)
   float *x, *qkv, *target_logit, *splitk;
   size_t splitk_elems;
   uint16_t *n1, *n2, *q, *attn, *act, *hfin;
   float2* partial;
+  // Set 0 serves the prompt pass, scoring and a decode of the whole batch.  A large decode batch is cut in two
+  // halves that run on two internal streams with sets 1 and 2: while one half streams its KV cache (HBM-bound),
+  // the other half's linear layers (matrix-core-bound) share the machine with it.
+  struct Bufs {
+    float *x, *qkv, *target_logit, *splitk;
+    size_t splitk_elems;
+    uint16_t *n1, *n2, *q, *attn, *act, *hfin;
+    float2* partial;
+  } set[3];
+  int Sg;                 // rows of sets 1 and 2
+  hipStream_t gstream[2];
+  hipEvent_t ev_fork, ev_join[2];
+  bool have_streams;
+  int split_min_seqs;
+  bool split_off;         // rlgen_set_decode_split(ctx, 0)
   // host staging (pinned)
   char* h_stage;
   size_t stage_bytes;
@@ -115,13 +130,21 @@ int check_cfg(const rlgen_model_cfg* c) {
   return RLGEN_OK;
 }
 
+void use_set(rlgen_ctx* c, int i) {
+  const rlgen_ctx::Bufs& b = c->set[i];
+  c->x = b.x; c->qkv = b.qkv; c->target_logit = b.target_logit; c->splitk = b.splitk; c->splitk_elems = b.splitk_elems;
+  c->n1 = b.n1; c->n2 = b.n2; c->q = b.q; c->attn = b.attn; c->act = b.act; c->hfin = b.hfin; c->partial = b.partial;
+}
+
 // Lays the workspace out; with base == nullptr only the size is computed.
 size_t carve(rlgen_ctx* c, char* base) {
   const rlgen_model_cfg& m = c->cfg;
   const size_t d = m.d_model, F = m.d_ffn, V = m.vocab, h = m.head_dim;
   const size_t qd = (size_t)m.n_q_heads * h, kvd = (size_t)m.n_kv_heads * h, nqkv = qd + 2 * kvd;
   const bool llama = m.arch == RLGEN_ARCH_LLAMA;
-  int mbt = m.max_batch_tokens ? m.max_batch_tokens : 16384;
+  // default chunk: 32768 rows (128 row tiles of 256: the tile count of every linear layer is then a multiple of
+  // the 256 CUs when its width is a multiple of 512), but no more than a call can ever hold
+  int mbt = m.max_batch_tokens ? m.max_batch_tokens : (int)std::min<long long>(32768, (long long)m.max_seqs * m.max_seq_len);
   if (mbt < m.max_seq_len) mbt = m.max_seq_len;
   c->R = mbt > m.max_seqs ? mbt : m.max_seqs;
   c->LM = c->R < 4096 ? c->R : 4096;
@@ -157,18 +180,24 @@ size_t carve(rlgen_ctx* c, char* base) {
   c->d_tok_index = k.take<int>(base, R); c->d_pos = k.take<int>(base, R); c->d_dst_seq = k.take<int>(base, R);
   c->d_lm_row = k.take<int>(base, R); c->d_target = k.take<int>(base, R); c->d_out_index = k.take<int>(base, R);
   c->d_jobs = k.take<AttnJob>(base, R / 16 + S + 1);
-  c->x = k.take<float>(base, R * d);
-  c->n1 = k.take<uint16_t>(base, kblk_elems(R, d));
-  c->n2 = k.take<uint16_t>(base, kblk_elems(R, d));
-  c->qkv = k.take<float>(base, R * nqkv);
-  c->q = k.take<uint16_t>(base, R * qd);
-  c->attn = k.take<uint16_t>(base, kblk_elems(R, qd));
-  c->act = k.take<uint16_t>(base, kblk_elems(R, F));
-  c->hfin = k.take<uint16_t>(base, kblk_elems(LM, d));
-  c->partial = k.take<float2>(base, LM * (size_t)c->ngroups);
-  c->target_logit = k.take<float>(base, LM);
-  c->splitk_elems = (size_t)12 << 20;          // 48 MB of split-K partial sums
-  c->splitk = k.take<float>(base, c->splitk_elems);
+  c->Sg = (2 * m.max_seqs + 2) / 3 + 1;        // the larger half: ceil(B / 2) prompts of B >= 2, k samples each
+  for (int i = 0; i < 3; ++i) {
+    const size_t rows = i == 0 ? R : (size_t)c->Sg, lm = i == 0 ? LM : (size_t)c->Sg;
+    rlgen_ctx::Bufs& b = c->set[i];
+    b.x = k.take<float>(base, rows * d);
+    b.n1 = k.take<uint16_t>(base, kblk_elems(rows, d));
+    b.n2 = k.take<uint16_t>(base, kblk_elems(rows, d));
+    b.qkv = k.take<float>(base, rows * nqkv);
+    b.q = k.take<uint16_t>(base, rows * qd);
+    b.attn = k.take<uint16_t>(base, kblk_elems(rows, qd));
+    b.act = k.take<uint16_t>(base, kblk_elems(rows, F));
+    b.hfin = k.take<uint16_t>(base, kblk_elems(lm, d));
+    b.partial = k.take<float2>(base, lm * (size_t)c->ngroups);
+    b.target_logit = k.take<float>(base, lm);
+    b.splitk_elems = (size_t)(i == 0 ? 12 : 6) << 20;          // 48 / 24 MB of split-K partial sums
+    b.splitk = k.take<float>(base, b.splitk_elems);
+  }
+  use_set(c, 0);
   return k.off;
 }
 
@@ -299,7 +328,14 @@ QkvEpi qkv_epilogue(const RopeArgs& r, uint16_t* kvstage) {
 // One pass of all decoder blocks over `rows` packed rows held in c->x.
 //  decode: rows are sequences 0..rows-1 at step t (the token drawn at step t-1 enters at position
 //          ctx_base + t - 1); otherwise rows follow d_pos / d_dst_seq / d_jobs of the current chunk.
-int run_layers(rlgen_ctx* c, int rows, bool decode, int t, int ncopy, bool use_cache_layers, int njobs, hipStream_t st) {
+// A decode step covers sequences g0 .. g0 + rows - 1 (all of the call's, or one half); with a shared prompt cache
+// these are the samples of prompts b0 .. of the call's B prompts.
+struct DecView { int g0, b0, B; };
+// Below this many sequences a decode step is too short to gain from running as two concurrent halves.
+constexpr int DECODE_SPLIT_MIN_SEQS = 256;     // RLGEN_DECODE_SPLIT_MIN overrides it at context creation
+
+int run_layers(rlgen_ctx* c, int rows, bool decode, int t, int ncopy, bool use_cache_layers, int njobs, hipStream_t st,
+               DecView dv = DecView{0, 0, 0}) {
   const rlgen_model_cfg& m = c->cfg;
   const bool llama = m.arch == RLGEN_ARCH_LLAMA;
   const int d = m.d_model, F = m.d_ffn, h = m.head_dim;
@@ -316,8 +352,8 @@ int run_layers(rlgen_ctx* c, int rows, bool decode, int t, int ncopy, bool use_c
     r.qkv = c->qkv; r.rows = rows; r.Hq = m.n_q_heads; r.Hkv = m.n_kv_heads; r.h = h; r.r = m.rotary_dim;
     r.table = c->rope; r.q = c->q; r.kv = kvl; r.lay = c->lay; r.kv_off = c->d_kv_off; r.kv_cap = c->d_kv_cap;
     if (decode) {
-      r.pos = c->d_ctx_base; r.pos_add = t - 1; r.dst_seq = c->d_iota; r.ncopy = 1;
-      r.slot_sub = c->share_k ? c->d_ctx_base : nullptr;     // new tokens start at slot 0 of their own stream
+      r.pos = c->d_ctx_base + dv.g0; r.pos_add = t - 1; r.dst_seq = c->d_iota + dv.g0; r.ncopy = 1;
+      r.slot_sub = c->share_k ? c->d_ctx_base + dv.g0 : nullptr;     // new tokens start at slot 0 of their own stream
     }
     else { r.pos = c->d_pos; r.pos_add = 0; r.dst_seq = c->d_dst_seq; r.ncopy = ncopy; r.v_by_blocks = 1; r.jobs = c->d_jobs; r.njobs = njobs; }
     if (c->fused_qkv) {
@@ -337,8 +373,11 @@ int run_layers(rlgen_ctx* c, int rows, bool decode, int t, int ncopy, bool use_c
     a.q = c->q; a.q_ld = qd; a.out = c->attn; a.out_rows = rows; a.kv = kvl; a.lay = c->lay;
     a.kv_off = c->d_kv_off; a.kv_cap = c->d_kv_cap; a.Hq = m.n_q_heads; a.scale = 1.0f / sqrtf((float)h);
     if (decode) {
-      a.ctx_base = c->d_ctx_base; a.ctx_add = t; a.S = rows; a.order = c->use_order ? c->d_order : nullptr;
-      a.share_k = c->share_k;
+      // the kernel indexes sequences (prompts, if shared) from 0: hand it the arrays at this view's first entry
+      const int u0 = c->share_k ? dv.b0 : dv.g0;
+      a.kv_off = c->d_kv_off + u0; a.kv_cap = c->d_kv_cap + u0;
+      a.ctx_base = c->d_ctx_base + dv.g0; a.ctx_add = t; a.S = rows; a.order = c->use_order ? c->d_order + u0 : nullptr;
+      a.share_k = c->share_k; a.sfx_first = c->share_k ? dv.B + dv.g0 - dv.b0 : 0;
       hipEvent_t e0 = nullptr, e1 = nullptr;
       if (c->profiling > 0 && (l + t) % c->profiling == 0) {
         while (c->prof_events.size() < c->prof_used + 2) {
@@ -430,7 +469,9 @@ int tune_gemms(rlgen_ctx* c, hipStream_t st) {
     for (int which = 0; which < 5 && rc == RLGEN_OK; ++which) {
       GemmArgs g{};
       int epi = EPI_F32;
-      g.M = mode == 0 ? m.max_seqs : c->R;
+      // a decode step sees max_seqs rows, or about half of them when the batch is split in two
+      const int dec_rows = (c->have_streams && m.max_seqs >= c->split_min_seqs) ? (m.max_seqs + 1) / 2 : m.max_seqs;
+      g.M = mode == 0 ? dec_rows : c->R;
       g.ws = c->splitk; g.ws_elems = c->splitk_elems;
       switch (which) {
         case G_QKV:
@@ -451,7 +492,7 @@ int tune_gemms(rlgen_ctx* c, hipStream_t st) {
                    epi = llama ? EPI_SWIGLU_F16 : EPI_GELU_F16; break;
         case G_DOWN: g.A = c->act; g.W = L.wdown; g.N = d; g.K = F; g.bias = llama ? nullptr : L.bdown; g.out = c->x; g.ldo = d; epi = EPI_RESID;
                      break;
-        case G_LMHEAD: g.A = c->hfin; g.W = c->lm_head; g.M = mode == 0 ? m.max_seqs : c->LM; g.N = m.vocab; g.K = d; g.temperature = 1.f;
+        case G_LMHEAD: g.A = c->hfin; g.W = c->lm_head; g.M = mode == 0 ? dec_rows : c->LM; g.N = m.vocab; g.K = d; g.temperature = 1.f;
                        g.partial = c->partial; g.ws = nullptr; epi = EPI_LMHEAD; break;
       }
       const bool wide_only = epi == EPI_SWIGLU_F16 || epi == EPI_LMHEAD;
@@ -660,6 +701,18 @@ int rlgen_create(const rlgen_model_cfg* cfg, const rlgen_weights* weights, void*
       hipEventCreate(&c->ev_end) != hipSuccess)
     return fail(RLGEN_ERR_DEVICE);
   c->timed = true;
+  // two internal streams (default priority) for the halves of a large decode batch
+  if (!getenv("RLGEN_NO_DECODE_SPLIT")) {
+    if (hipStreamCreateWithFlags(&c->gstream[0], hipStreamNonBlocking) != hipSuccess ||
+        hipStreamCreateWithFlags(&c->gstream[1], hipStreamNonBlocking) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_join[0], hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_join[1], hipEventDisableTiming) != hipSuccess)
+      return fail(RLGEN_ERR_DEVICE);
+    c->have_streams = true;
+    const char* e = getenv("RLGEN_DECODE_SPLIT_MIN");
+    c->split_min_seqs = e && atoi(e) >= 2 ? atoi(e) : DECODE_SPLIT_MIN_SEQS;
+  }
   c->fused_qkv = cfg->rotary_dim % 4 == 0 && !getenv("RLGEN_UNFUSED_QKV");
   rc = pack_weights(c, weights, st);
   if (rc) return fail(rc);
@@ -734,20 +787,26 @@ int rlgen_generate(rlgen_ctx* c, const int32_t* prompts, const int32_t* prompt_l
     cur.count++; cur.rows += len; cur.jobs += (len + 15) / 16;
   }
   chunks.push_back(cur);
-  // decode attention takes the sequences longest context first when there are few jobs per CU, so that the
-  // launch does not end on a handful of long ones
-  if (share) {
+  if (share)
     for (int q = 0; q < S; ++q) {
       s.kv_off[B + q] = (int)off; s.kv_cap[B + q] = round32(max_new);
       off += round32(max_new);
     }
-    for (int b = 0; b < B; ++b) s.order[b] = b;
-    std::stable_sort(s.order, s.order + B, [&](int x, int y) { return prompt_lens[x] > prompt_lens[y]; });
-    c->use_order = (long long)B * m.n_kv_heads <= 8192;
-  } else {
-    for (int q = 0; q < S; ++q) s.order[q] = q;
-    std::stable_sort(s.order, s.order + S, [&](int x, int y) { return s.ctx_base[x] > s.ctx_base[y]; });
-    c->use_order = (long long)S * m.n_kv_heads <= 8192;
+  // A large batch decodes as two halves (whole prompts each) on two streams.  Each half's attention launch takes
+  // its sequences (prompts, if they share their cache) longest context first when there are few jobs per CU, so
+  // that the launch does not end on a handful of long ones; the order is local to the half.
+  const int ngroups = (c->have_streams && !c->split_off && B >= 2 && S >= c->split_min_seqs) ? 2 : 1;
+  const int Bh = ngroups == 2 ? (B + 1) / 2 : B;       // (B + 1) / 2 * k <= (max_seqs + 1) / 2 rows for k >= 1, B * k <= max_seqs
+  {
+    const int unit_k = share ? 1 : k;                 // order entries per prompt
+    for (int gi = 0; gi < ngroups; ++gi) {
+      const int u0 = (gi == 0 ? 0 : Bh) * unit_k, n = (gi == 0 ? Bh : B - Bh) * unit_k;
+      for (int i = 0; i < n; ++i) s.order[u0 + i] = i;
+      std::stable_sort(s.order + u0, s.order + u0 + n, [&](int x, int y) {
+        return prompt_lens[(u0 + x) / unit_k] > prompt_lens[(u0 + y) / unit_k];
+      });
+    }
+    c->use_order = (long long)(share ? B : S) * m.n_kv_heads <= 8192 * ngroups;
   }
   c->share_k = share ? k : 0;
   rc = stage_upload(c, s, B, S, share ? B + S : S, st);
@@ -767,14 +826,38 @@ int rlgen_generate(rlgen_ctx* c, const int32_t* prompts, const int32_t* prompt_l
   if (c->timed) HIPCHK(hipEventRecord(c->ev_mid, st));
   rc = sample_rows(c, S, temperature, uniforms, forced, max_new, 0, tokens, token_logprobs, c->d_next_token, st);
   if (rc) return rc;
-  for (int t = 1; t < max_new; ++t) {
-    HIPCHK(rl_embed(c->x, c->embed, c->d_next_token, nullptr, S, m.d_model, m.vocab, c->status, st));
-    rc = run_layers(c, S, true, t, 1, true, 0, st);
+  // one decode step of sequences g0 .. g0 + n - 1 on stream gs, with the activation set in use
+  auto decode_step = [&](int t, DecView dv, int n, hipStream_t gs) -> int {
+    HIPCHK(rl_embed(c->x, c->embed, c->d_next_token + dv.g0, nullptr, n, m.d_model, m.vocab, c->status, gs));
+    int r2 = run_layers(c, n, true, t, 1, true, 0, gs, dv);
+    if (r2) return r2;
+    r2 = final_norm(c, nullptr, n, n, 0, gs);
+    if (r2) return r2;
+    const size_t o = (size_t)dv.g0 * max_new;
+    return sample_rows(c, n, temperature, uniforms + o, forced ? forced + o : nullptr, max_new, t, tokens + o, token_logprobs + o,
+                       c->d_next_token + dv.g0, gs);
+  };
+  if (ngroups == 2 && max_new > 1) {
+    HIPCHK(hipEventRecord(c->ev_fork, st));
+    for (int gi = 0; gi < 2; ++gi) HIPCHK(hipStreamWaitEvent(c->gstream[gi], c->ev_fork, 0));
+    for (int t = 1; t < max_new && rc == RLGEN_OK; ++t)
+      for (int gi = 0; gi < 2 && rc == RLGEN_OK; ++gi) {
+        use_set(c, 1 + gi);
+        const int b0 = gi == 0 ? 0 : Bh, nb = gi == 0 ? Bh : B - Bh;
+        rc = decode_step(t, DecView{b0 * k, b0, B}, nb * k, c->gstream[gi]);
+      }
+    use_set(c, 0);
+    // join also after an error: the caller's stream must not run ahead of work already queued
+    for (int gi = 0; gi < 2; ++gi) {
+      HIPCHK(hipEventRecord(c->ev_join[gi], c->gstream[gi]));
+      HIPCHK(hipStreamWaitEvent(st, c->ev_join[gi], 0));
+    }
     if (rc) return rc;
-    rc = final_norm(c, nullptr, S, S, 0, st);
-    if (rc) return rc;
-    rc = sample_rows(c, S, temperature, uniforms, forced, max_new, t, tokens, token_logprobs, c->d_next_token, st);
-    if (rc) return rc;
+  } else {
+    for (int t = 1; t < max_new; ++t) {
+      rc = decode_step(t, DecView{0, 0, B}, S, st);
+      if (rc) return rc;
+    }
   }
   if (c->timed) HIPCHK(hipEventRecord(c->ev_end, st));
   return RLGEN_OK;
@@ -847,6 +930,12 @@ int rlgen_set_profiling(rlgen_ctx* c, int32_t on) {
   return RLGEN_OK;
 }
 
+int rlgen_set_decode_split(rlgen_ctx* c, int32_t on) {
+  if (!c) return RLGEN_ERR_NULL;
+  c->split_off = on == 0;
+  return RLGEN_OK;
+}
+
 int rlgen_status(rlgen_ctx* c, void* hip_stream) {
   if (!c) return RLGEN_ERR_NULL;
   unsigned v = 0;
@@ -879,6 +968,14 @@ void rlgen_destroy(rlgen_ctx* c) {
   if (c->ev_mid) (void)hipEventDestroy(c->ev_mid);
   if (c->ev_end) (void)hipEventDestroy(c->ev_end);
   for (hipEvent_t e : c->prof_events) (void)hipEventDestroy(e);
+  if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
+  for (int i = 0; i < 2; ++i) {
+    if (c->ev_join[i]) (void)hipEventDestroy(c->ev_join[i]);
+    if (c->gstream[i]) {
+      (void)hipStreamSynchronize(c->gstream[i]);
+      (void)hipStreamDestroy(c->gstream[i]);
+    }
+  }
   if (c->h_stage) (void)hipHostFree(c->h_stage);
   delete c;
 }

@@ -366,3 +366,36 @@ def test_shared_prompt_cache_capacity(shared):
     with pytest.raises(r.RlgenError) as e:
         run(16, 1, 40)                         # 16 * 96 + 16 * 64 = 2560 (one stream per sequence would need 16 * 128)
     assert e.value.code == r.ERR_CAPACITY
+
+
+# ---------------------------------------------------------------- large batches decode as two concurrent halves
+@pytest.mark.parametrize("share", [0, 1])
+@pytest.mark.parametrize("name", ["neox-h80", "llama-gqa4-h16"])
+def test_split_decode_matches_oracle_and_unsplit(name, share, monkeypatch):
+    """The two-stream decode normally starts at 256 sequences; the threshold is lowered so that a batch the
+    oracle can follow takes it (odd prompt count: the halves differ in size)."""
+    monkeypatch.setenv("RLGEN_DECODE_SPLIT_MIN", "2")
+    m = GPU_SHAPES[name]
+    W = scaled_bf16_weights(m)
+    dec = O.Decoder(W, m)
+    pol = make_policy(W, max_seqs=12, max_seq_len=80, max_batch_tokens=80, share_prompt_kv=share)
+    try:
+        rng = np.random.default_rng(77)
+        B, k, T, temp = 5, 2, 7, 0.7
+        prompts = rand_seqs(rng, m.vocab, [30, 1, 33, 64, 71])
+        arr, lens = padded(prompts, pad=-1)
+        u = rng.random((B, k, T), dtype=np.float32)
+        r = R()
+        t_o, l_o, margins, _, _ = oracle_generate_batch(dec, arr, lens, k, T, temp, u)
+        forced = np.where(margins > MARGIN, -1, t_o).astype(np.int32)
+        t_g, l_g = r.rlgen_generate(pol, dev_i32(arr), lens, k, T, temp, dev_f32(u), dev_i32(forced))
+        np.testing.assert_array_equal(t_g.cpu().numpy(), t_o)
+        assert np.abs(l_g.cpu().numpy() - l_o).max() < TOL_LOGPROB
+        t_a, l_a = r.rlgen_generate(pol, dev_i32(arr), lens, k, T, temp, dev_f32(u))
+        r.rlgen_set_decode_split(pol, False)
+        t_b, l_b = r.rlgen_generate(pol, dev_i32(arr), lens, k, T, temp, dev_f32(u))
+        r.rlgen_set_decode_split(pol, True)
+        assert torch.equal(t_a, t_b) and torch.equal(l_a, l_b)          # bit for bit
+        assert r.rlgen_status(pol) == 0
+    finally:
+        pol.close()
