@@ -46,6 +46,10 @@ def main():
     ap.add_argument("--share-prompt-kv", action="store_true",
                     help="the k samples of a prompt read one copy of the prompt's keys/values (not the headline layout)")
     ap.add_argument("--max-batch-tokens", type=int, default=0, help="rows per prompt-pass chunk (0 = the library's default)")
+    ap.add_argument("--no-alone-pass", action="store_true",
+                    help="skip the extra pass that times the attention kernel with nothing beside it")
+    ap.add_argument("--no-decode-split", action="store_true",
+                    help="decode the whole batch on one stream (every kernel runs alone; slower)")
     ap.add_argument("--k", type=int, default=0, help="override the workload's samples per prompt")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -95,6 +99,8 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    if args.no_decode_split:
+        R.rlgen_set_decode_split(pol, False)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -161,7 +167,7 @@ def main():
         "setup_s": round(setup_s, 1),
         "roofline": roofline,
     }
-    if halves > 1 and not args.no_kernel_events:
+    if halves > 1 and not args.no_kernel_events and not args.no_alone_pass:
         # the same kernel with nothing beside it: one more pass (not part of `value`) with the two-stream decode
         # switched off, so that a launch covers the whole batch and runs alone
         R.rlgen_set_decode_split(pol, False)
