@@ -480,6 +480,7 @@ hipError_t rl_gemm_variant(const GemmArgs& g, int epi, int variant, hipStream_t 
 hipError_t rl_gemm_splitk(const GemmArgs& g, int epi, int variant, hipStream_t s) {
   if (g.M <= 0 || g.N <= 0) return hipSuccess;
   if (g.splits < 2 || !g.ws || (epi != EPI_F32 && epi != EPI_RESID && epi != EPI_GELU_F16)) return hipErrorInvalidValue;
+  if ((size_t)g.splits * g.M * g.N > g.ws_elems) return hipErrorInvalidValue;      // the partial sums must fit
   hipError_t e = rl_gemm_variant(g, EPI_PARTIAL, variant, s);
   if (e != hipSuccess) return e;
   const size_t n = (size_t)g.M * g.N;

@@ -101,7 +101,9 @@ struct rlgen_ctx {
   std::vector<hipEvent_t> prof_events;
   size_t prof_used;
   // tile shape and K split of each linear layer, measured at creation: [decode | prompt pass][which GEMM]
-  struct GemmChoice { int variant, splits; } tuned[2][5];
+  // [decode of max_seqs rows | prompt pass | decode of half of max_seqs rows][which GEMM]
+  struct GemmChoice { int variant, splits; } tuned[3][5];
+  bool half_rows;         // the decode steps being enqueued cover half of the batch
 };
 
 namespace {
@@ -194,7 +196,7 @@ size_t carve(rlgen_ctx* c, char* base) {
     b.hfin = k.take<uint16_t>(base, kblk_elems(lm, d));
     b.partial = k.take<float2>(base, lm * (size_t)c->ngroups);
     b.target_logit = k.take<float>(base, lm);
-    b.splitk_elems = (size_t)(i == 0 ? 12 : 6) << 20;          // 48 / 24 MB of split-K partial sums
+    b.splitk_elems = (size_t)12 << 20;          // 48 MB of split-K partial sums
     b.splitk = k.take<float>(base, b.splitk_elems);
   }
   use_set(c, 0);
@@ -313,7 +315,7 @@ hipError_t run_choice(const GemmArgs& g, int epi, int variant, int splits, hipSt
   return rl_gemm_variant(g, epi, variant, st);
 }
 hipError_t gemm(rlgen_ctx* c, int which, bool decode, const GemmArgs& g, int epi, hipStream_t st) {
-  const auto& ch = c->tuned[decode ? 0 : 1][which];
+  const auto& ch = c->tuned[decode ? (c->half_rows ? 2 : 0) : 1][which];
   return run_choice(g, epi, ch.variant, ch.splits, st);
 }
 
@@ -465,13 +467,19 @@ int tune_gemms(rlgen_ctx* c, hipStream_t st) {
   HIPCHK(hipEventCreate(&e1));
   const LayerW& L = c->layers[0];
   int rc = RLGEN_OK;
-  for (int mode = 0; mode < 2 && rc == RLGEN_OK; ++mode) {
+  const bool tune_half = c->have_streams && m.max_seqs >= c->split_min_seqs;
+  for (int which = 0; which < 5; ++which) c->tuned[2][which] = {-1, 1};
+  // The half-batch decode is tuned first; the whole-batch decode may then pick another tile shape but keeps the
+  // K split, so that a sequence's arithmetic (the order of its sums) does not depend on how the batch was cut.
+  const int modes[3] = {2, 0, 1};
+  for (int mi = tune_half ? 0 : 1; mi < 3 && rc == RLGEN_OK; ++mi) {
+    const int mode = modes[mi];
     for (int which = 0; which < 5 && rc == RLGEN_OK; ++which) {
       GemmArgs g{};
       int epi = EPI_F32;
       // a decode step sees max_seqs rows, or about half of them when the batch is split in two
-      const int dec_rows = (c->have_streams && m.max_seqs >= c->split_min_seqs) ? (m.max_seqs + 1) / 2 : m.max_seqs;
-      g.M = mode == 0 ? dec_rows : c->R;
+      const int dec_rows = mode == 2 ? (m.max_seqs + 1) / 2 : m.max_seqs;
+      g.M = mode != 1 ? dec_rows : c->R;
       g.ws = c->splitk; g.ws_elems = c->splitk_elems;
       switch (which) {
         case G_QKV:
@@ -482,7 +490,7 @@ int tune_gemms(rlgen_ctx* c, hipStream_t st) {
             r.Hq = m.n_q_heads; r.Hkv = m.n_kv_heads; r.h = m.head_dim; r.r = m.rotary_dim; r.table = c->rope; r.q = c->q;
             r.kv = c->kv; r.lay = c->lay; r.kv_off = c->d_kv_off; r.kv_cap = c->d_kv_cap;
             r.pos = c->d_pos; r.dst_seq = c->d_dst_seq; r.ncopy = 1;
-            g.qe = qkv_epilogue(r, mode == 0 ? nullptr : (uint16_t*)c->qkv);
+            g.qe = qkv_epilogue(r, mode != 1 ? nullptr : (uint16_t*)c->qkv);
             g.ws = nullptr;          // the fused epilogue has no split-K form
             epi = EPI_QKV;
           }
@@ -492,7 +500,7 @@ int tune_gemms(rlgen_ctx* c, hipStream_t st) {
                    epi = llama ? EPI_SWIGLU_F16 : EPI_GELU_F16; break;
         case G_DOWN: g.A = c->act; g.W = L.wdown; g.N = d; g.K = F; g.bias = llama ? nullptr : L.bdown; g.out = c->x; g.ldo = d; epi = EPI_RESID;
                      break;
-        case G_LMHEAD: g.A = c->hfin; g.W = c->lm_head; g.M = mode == 0 ? dec_rows : c->LM; g.N = m.vocab; g.K = d; g.temperature = 1.f;
+        case G_LMHEAD: g.A = c->hfin; g.W = c->lm_head; g.M = mode != 1 ? dec_rows : c->LM; g.N = m.vocab; g.K = d; g.temperature = 1.f;
                        g.partial = c->partial; g.ws = nullptr; epi = EPI_LMHEAD; break;
       }
       const bool wide_only = epi == EPI_SWIGLU_F16 || epi == EPI_LMHEAD;
@@ -504,7 +512,16 @@ int tune_gemms(rlgen_ctx* c, hipStream_t st) {
         const long long t7 = (long long)((g.M + 63) / 64) * ((g.N + 127) / 128);
         if (g.ws && t7 <= 1024 && epi != EPI_QKV)
           for (int sp : {2, 3, 4, 6, 8})
-            if (nk / sp >= 4 && (size_t)sp * g.M * g.N <= g.ws_elems) cands.push_back({7, sp});
+            // what the half batch picks the whole batch must be able to run too (same K split)
+            if (nk / sp >= 4 && (size_t)sp * (mode == 2 ? m.max_seqs : g.M) * g.N <= g.ws_elems) cands.push_back({7, sp});
+      }
+      if (mode == 0 && tune_half) {
+        const int keep = c->tuned[2][which].splits;
+        std::vector<Cand> same;
+        if (keep >= 2) same.push_back({7, keep});     // fits: the half-batch candidates were sized for max_seqs rows
+        else
+          for (const Cand& cd : cands) if (cd.splits == 1) same.push_back(cd);
+        cands = same;
       }
       // clocks drift with load, so the candidates take turns: one warm-up each, then three rounds in which
       // every candidate is timed over two launches; the smallest total wins
@@ -795,7 +812,19 @@ int rlgen_generate(rlgen_ctx* c, const int32_t* prompts, const int32_t* prompt_l
   // A large batch decodes as two halves (whole prompts each) on two streams.  Each half's attention launch takes
   // its sequences (prompts, if they share their cache) longest context first when there are few jobs per CU, so
   // that the launch does not end on a handful of long ones; the order is local to the half.
-  const int ngroups = (c->have_streams && !c->split_off && B >= 2 && S >= c->split_min_seqs) ? 2 : 1;
+  // Splitting reads the weights twice per step, so it pays only when the cache traffic of a step dwarfs them.
+  bool split = c->have_streams && !c->split_off && B >= 2 && S >= c->split_min_seqs;
+  if (split && c->split_min_seqs == DECODE_SPLIT_MIN_SEQS) {
+    const double qd = (double)m.n_q_heads * m.head_dim, kvd = (double)m.n_kv_heads * m.head_dim;
+    const double per_layer = (qd + 2 * kvd) * m.d_model + qd * m.d_model +
+                             (m.arch == RLGEN_ARCH_LLAMA ? 3.0 : 2.0) * m.d_ffn * (double)m.d_model;
+    const double weight_bytes = 2.0 * (per_layer * m.n_layers + (double)m.vocab * m.d_model);
+    double ctx = 0;
+    for (int b = 0; b < B; ++b) ctx += (share ? 1.0 : (double)k) * prompt_lens[b] + (double)k * max_new * 0.5;
+    const double kv_bytes = 4.0 * kvd * ctx * m.n_layers;
+    split = kv_bytes >= 4.0 * weight_bytes;
+  }
+  const int ngroups = split ? 2 : 1;
   const int Bh = ngroups == 2 ? (B + 1) / 2 : B;       // (B + 1) / 2 * k <= (max_seqs + 1) / 2 rows for k >= 1, B * k <= max_seqs
   {
     const int unit_k = share ? 1 : k;                 // order entries per prompt
@@ -843,10 +872,12 @@ int rlgen_generate(rlgen_ctx* c, const int32_t* prompts, const int32_t* prompt_l
     for (int t = 1; t < max_new && rc == RLGEN_OK; ++t)
       for (int gi = 0; gi < 2 && rc == RLGEN_OK; ++gi) {
         use_set(c, 1 + gi);
+        c->half_rows = c->tuned[2][0].variant >= 0;
         const int b0 = gi == 0 ? 0 : Bh, nb = gi == 0 ? Bh : B - Bh;
         rc = decode_step(t, DecView{b0 * k, b0, B}, nb * k, c->gstream[gi]);
       }
     use_set(c, 0);
+    c->half_rows = false;
     // join also after an error: the caller's stream must not run ahead of work already queued
     for (int gi = 0; gi < 2; ++gi) {
       HIPCHK(hipEventRecord(c->ev_join[gi], c->gstream[gi]));
