@@ -169,6 +169,14 @@ int rlgen_sequence_logprob(const float *token_logprobs, const int32_t *from, con
 int rlgen_dpo_loss(const float *pol_pos, const float *ref_pos, const float *pol_neg,
                    const float *ref_neg, int32_t P, float beta, float *loss, void *hip_stream);
 
+/* Which two of a prompt's k completions are trained on (Section 2.1: the two samples ranked by reward;
+ * Section 4.2: of K = 4 samples the highest and the lowest rewarded).  rewards [B, k] fp32 (the caller's
+ * reward model; no NaN), idx_pos / idx_neg [B] int32 out, all DEVICE: idx_pos[b] = first index of the
+ * maximum, idx_neg[b] = last index of the minimum (so they differ whenever k >= 2).
+ * Errors: NULL, BAD_ARG (B or k < 1), DEVICE. */
+int rlgen_select_pairs(const float *rewards, int32_t B, int32_t k, int32_t *idx_pos, int32_t *idx_neg,
+                       void *hip_stream);
+
 /* Per-phase device times of the last rlgen_generate / rlgen_score on this context, in ms (any
  * pointer may be null).  Synchronises the events it reads.  decode_attn_ms / decode_attn_launches
  * cover the decode-attention kernel alone and are filled only while profiling is on:

@@ -242,15 +242,30 @@ def cdf_bucket(logp, tok):
     return (float(C[tok - 1]) if tok > 0 else 0.0), float(C[tok])
 
 
+def greedy_pick(z):
+    """Greedy decoding (Section 5.2: evaluation draws one completion per question greedily): the first index of
+    the largest logit; its log-prob is taken under softmax(z) (temperature 1); the margin is the gap to the
+    runner-up logit."""
+    z = np.asarray(z, np.float64)
+    tok = int(np.argmax(z))
+    rest = np.delete(z, tok)
+    margin = float(z[tok] - rest.max()) if len(rest) else np.inf
+    return tok, margin
+
+
 def generate(dec: Decoder, prompt, k, max_new, temperature, uniforms, forced=None,
-             return_final_logits=False, buckets=None):
+             return_final_logits=False, buckets=None, eos=-1):
     """K completions of `max_new` tokens for one prompt (Algorithm 1, procedure Generate).
 
     uniforms: [k, max_new]; forced: optional [k, max_new] ints, entries >= 0 replace the draw.
     Returns tokens [k, max_new] int32, logprobs [k, max_new] float32 (of the emitted token under
     softmax(z / T)), margins [k, max_new] float64 (of the oracle's own draw).  The prompt is
     processed once; each sample continues from a copy of its KV cache.  If `buckets` is a float64
-    array [k, max_new, 2] it receives the CDF interval of every emitted token."""
+    array [k, max_new, 2] it receives the CDF interval of every emitted token.
+    temperature == 0 decodes greedily (greedy_pick; uniforms are ignored).
+    eos >= 0: a completion ends with its first `eos` token (the completions the paper scores end in an EOS token
+    or are penalised for lacking one, Appendix A.1 / A.2 hyper-parameter tables); the remaining entries are
+    filled with `eos` at log-prob 0 and margin inf."""
     uniforms = np.asarray(uniforms)
     assert uniforms.shape == (k, max_new)
     base = KVCache(dec.m.n_layers)
@@ -261,16 +276,27 @@ def generate(dec: Decoder, prompt, k, max_new, temperature, uniforms, forced=Non
     final_logits = []
     for j in range(k):
         cache, x = base.copy(), x_last
+        done = False
         for t in range(max_new):
+            if done:
+                toks[j, t], lps[j, t], margins[j, t] = eos, 0.0, np.inf
+                if buckets is not None:
+                    buckets[j, t] = (0.0, 1.0)
+                continue
             z = dec.logits(x)[0]
-            logp = tempered_log_softmax(z, temperature)
-            tok, margins[j, t] = sample_inverse_cdf(logp, uniforms[j, t])
+            if temperature == 0:
+                logp = tempered_log_softmax(z, 1.0)
+                tok, margins[j, t] = greedy_pick(z)
+            else:
+                logp = tempered_log_softmax(z, temperature)
+                tok, margins[j, t] = sample_inverse_cdf(logp, uniforms[j, t])
             if forced is not None and forced[j][t] >= 0:
                 tok = int(forced[j][t])
             toks[j, t], lps[j, t] = tok, logp[tok]
             if buckets is not None:
                 buckets[j, t] = cdf_bucket(logp, tok)
-            if t + 1 < max_new or return_final_logits:
+            done = eos >= 0 and tok == eos
+            if (t + 1 < max_new and not done) or return_final_logits:
                 x = dec.forward([tok], cache)
         if return_final_logits:
             final_logits.append(dec.logits(x)[0])
@@ -322,6 +348,21 @@ def dpo_pair_loss(lp_pol_pos, lp_ref_pos, lp_pol_neg, lp_ref_neg, beta):
     Arguments are sequence log-probabilities (sums of response-token log-probs), float64."""
     d = beta * ((np.asarray(lp_pol_pos, np.float64) - lp_ref_pos) - (np.asarray(lp_pol_neg, np.float64) - lp_ref_neg))
     return np.logaddexp(0.0, -d)
+
+
+def select_pair(rewards):
+    """Indices (y+, y-) of the highest and the lowest rewarded of a prompt's K completions (Section 2.1: two samples
+    ranked by the reward model; Section 4.2: of K samples only the highest and the lowest are trained on).  The
+    paper does not say what happens on ties: here y+ is the first of the highest and y- the last of the lowest, so
+    the two differ whenever K >= 2."""
+    r = [float(x) for x in rewards]
+    pos, neg = 0, 0
+    for j in range(len(r)):
+        if r[j] > r[pos]:
+            pos = j
+        if r[j] <= r[neg]:
+            neg = j
+    return pos, neg
 
 
 def sequence_logprob(token_logprobs, score_from, length):

@@ -295,6 +295,18 @@ __global__ void sequence_logprob_kernel(const float* tlp, const int* from, const
   acc = wave_sum(acc);
   if (lane == 0) out[n] = acc;
 }
+__global__ void select_pairs_kernel(const float* rewards, int B, int k, int* idx_pos, int* idx_neg) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  const float* r = rewards + (size_t)b * k;
+  int pos = 0, neg = 0;
+  for (int j = 1; j < k; ++j) {
+    if (r[j] > r[pos]) pos = j;        // first of the highest
+    if (r[j] <= r[neg]) neg = j;       // last of the lowest
+  }
+  idx_pos[b] = pos;
+  idx_neg[b] = neg;
+}
 __global__ void dpo_loss_kernel(const float* pp, const float* rp, const float* pn, const float* rn, int P, float beta, float* loss) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= P) return;
@@ -386,6 +398,11 @@ hipError_t rl_kv_prefill(const RopeArgs& a, hipStream_t s) {
 hipError_t rl_sequence_logprob(const float* tlp, const int* from, const int* lens, int N, int stride, float* out, hipStream_t s) {
   if (N <= 0) return hipSuccess;
   hipLaunchKernelGGL(sequence_logprob_kernel, dim3((N + 3) / 4), dim3(256), 0, s, tlp, from, lens, N, stride, out);
+  return hipGetLastError();
+}
+hipError_t rl_select_pairs(const float* rewards, int B, int k, int* idx_pos, int* idx_neg, hipStream_t s) {
+  if (B <= 0) return hipSuccess;
+  hipLaunchKernelGGL(select_pairs_kernel, dim3(blocks_for(B)), dim3(TPB), 0, s, rewards, B, k, idx_pos, idx_neg);
   return hipGetLastError();
 }
 hipError_t rl_dpo_loss(const float* pp, const float* rp, const float* pn, const float* rn, int P, float beta, float* loss, hipStream_t s) {

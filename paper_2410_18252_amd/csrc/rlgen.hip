@@ -935,6 +935,13 @@ int rlgen_dpo_loss(const float* pol_pos, const float* ref_pos, const float* pol_
   return RLGEN_OK;
 }
 
+int rlgen_select_pairs(const float* rewards, int32_t B, int32_t k, int32_t* idx_pos, int32_t* idx_neg, void* hip_stream) {
+  if (!rewards || !idx_pos || !idx_neg) return RLGEN_ERR_NULL;
+  if (B < 1 || k < 1) return RLGEN_ERR_BAD_ARG;
+  HIPCHK(rl_select_pairs(rewards, B, k, idx_pos, idx_neg, (hipStream_t)hip_stream));
+  return RLGEN_OK;
+}
+
 int rlgen_get_timings(rlgen_ctx* c, float* prefill_ms, float* decode_ms, float* decode_attn_ms, int32_t* decode_attn_launches) {
   if (!c) return RLGEN_ERR_NULL;
   HIPCHK(hipEventSynchronize(c->ev_end));

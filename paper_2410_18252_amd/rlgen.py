@@ -25,7 +25,7 @@ ARCH_NEOX, ARCH_LLAMA = 0, 1
 DTYPE_F32, DTYPE_BF16 = 0, 1
 
 EXPORTS = ["rlgen_workspace_bytes", "rlgen_create", "rlgen_update_weights", "rlgen_generate", "rlgen_score",
-           "rlgen_debug_logits", "rlgen_debug_sample", "rlgen_sequence_logprob", "rlgen_dpo_loss",
+           "rlgen_debug_logits", "rlgen_debug_sample", "rlgen_sequence_logprob", "rlgen_dpo_loss", "rlgen_select_pairs",
            "rlgen_get_timings", "rlgen_set_profiling", "rlgen_set_decode_split", "rlgen_status", "rlgen_strerror", "rlgen_destroy"]
 
 
@@ -67,6 +67,8 @@ lib.rlgen_debug_sample.restype = C.c_int
 lib.rlgen_debug_sample.argtypes = [_vp, _vp, _i32, _f32, _vp, _vp, _vp, _vp, _vp]
 lib.rlgen_sequence_logprob.restype = C.c_int
 lib.rlgen_sequence_logprob.argtypes = [_vp, _vp, _vp, _i32, _i32, _vp, _vp]
+lib.rlgen_select_pairs.restype = C.c_int
+lib.rlgen_select_pairs.argtypes = [_vp, _i32, _i32, _vp, _vp, _vp]
 lib.rlgen_dpo_loss.restype = C.c_int
 lib.rlgen_dpo_loss.argtypes = [_vp, _vp, _vp, _vp, _i32, _f32, _vp, _vp]
 lib.rlgen_get_timings.restype = C.c_int
@@ -182,6 +184,10 @@ class Policy:
         torch.cuda.current_stream().synchronize()
 
 
+def rlgen_update_weights(p: Policy, dev_weights: Dict[str, torch.Tensor]):
+    p.update_weights(dev_weights)
+
+
 def rlgen_generate(p: Policy, prompts: torch.Tensor, prompt_lens, k: int, max_new: int, temperature: float,
                    uniforms: torch.Tensor, forced: Optional[torch.Tensor] = None, out=None):
     """prompts int32 [B, stride] (device), prompt_lens host ints [B], uniforms fp32 [B, k, max_new] (device).
@@ -253,6 +259,16 @@ def rlgen_dpo_loss(pol_pos, ref_pos, pol_neg, ref_neg, beta: float):
     _check(lib.rlgen_dpo_loss(_ptr(pol_pos), _ptr(ref_pos), _ptr(pol_neg), _ptr(ref_neg), P, beta, _ptr(out), _stream()),
            "rlgen_dpo_loss")
     return out
+
+
+def rlgen_select_pairs(rewards):
+    """rewards [B, k] fp32 on the device -> (idx_pos, idx_neg), each [B] int32."""
+    assert rewards.dtype == torch.float32 and rewards.is_contiguous() and rewards.dim() == 2
+    B, k = rewards.shape
+    pos = torch.empty(B, dtype=torch.int32, device=rewards.device)
+    neg = torch.empty(B, dtype=torch.int32, device=rewards.device)
+    _check(lib.rlgen_select_pairs(_ptr(rewards), B, k, _ptr(pos), _ptr(neg), _stream()), "rlgen_select_pairs")
+    return pos, neg
 
 
 def rlgen_get_timings(p: Policy):

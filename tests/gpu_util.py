@@ -77,7 +77,7 @@ def padded(seqs, pad=-1):
     return arr, lens
 
 
-def oracle_generate_batch(dec, prompts, lens, k, max_new, T, uniforms, forced=None, with_buckets=False):
+def oracle_generate_batch(dec, prompts, lens, k, max_new, T, uniforms, forced=None, with_buckets=False, eos=-1):
     B = len(lens)
     toks = np.zeros((B, k, max_new), np.int32)
     lps = np.zeros((B, k, max_new), np.float32)
@@ -85,9 +85,10 @@ def oracle_generate_batch(dec, prompts, lens, k, max_new, T, uniforms, forced=No
     buckets = np.zeros((B, k, max_new, 2)) if with_buckets else None
     zfin = []
     for b in range(B):
-        t, l, m, z = O.generate(dec, prompts[b, :lens[b]], k, max_new, T, uniforms[b],
-                                None if forced is None else forced[b], return_final_logits=True,
-                                buckets=None if buckets is None else buckets[b])
-        toks[b], lps[b], margins[b] = t, l, m
-        zfin.append(z)
-    return toks, lps, margins, np.stack(zfin), buckets
+        res = O.generate(dec, prompts[b, :lens[b]], k, max_new, T, uniforms[b],
+                         None if forced is None else forced[b], return_final_logits=eos < 0,
+                         buckets=None if buckets is None else buckets[b], eos=eos)
+        toks[b], lps[b], margins[b] = res[:3]
+        if eos < 0:
+            zfin.append(res[3])
+    return toks, lps, margins, (np.stack(zfin) if zfin else None), buckets

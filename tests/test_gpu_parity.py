@@ -287,6 +287,44 @@ def test_dpo_loss_and_sequence_logprob_match_oracle():
         assert np.abs(got - ref).max() < 1e-5 * max(1.0, np.abs(ref).max())
 
 
+def test_select_pairs_matches_oracle():
+    rng = np.random.default_rng(39)
+    r = R()
+    for B, k in ((1, 1), (513, 2), (300, 4), (65, 7)):
+        rew = rng.integers(-2, 3, size=(B, k)).astype(np.float32)         # few distinct values: many ties
+        rew[::3] += rng.standard_normal((len(rew[::3]), k)).astype(np.float32)
+        pos, neg = r.rlgen_select_pairs(dev_f32(rew))
+        ref = np.array([O.select_pair(row) for row in rew], np.int32)
+        np.testing.assert_array_equal(pos.cpu().numpy(), ref[:, 0])
+        np.testing.assert_array_equal(neg.cpu().numpy(), ref[:, 1])
+
+
+def test_update_weights_replaces_the_policy():
+    """The parameter hand-off of the asynchronous loop (Appendix D, Algorithm 1): after the update the context
+    generates exactly what a context created with the new weights generates."""
+    m = GPU_SHAPES["neox-h80"]
+    r = R()
+    W1, W2 = scaled_bf16_weights(m, seed=21), scaled_bf16_weights(m, seed=22)
+    rng = np.random.default_rng(41)
+    prompts = rand_seqs(rng, m.vocab, [17, 40, 5])
+    arr, lens = padded(prompts)
+    u = rng.random((3, 2, 6), dtype=np.float32)
+    pol = make_policy(W1, max_seqs=6, max_seq_len=64)
+    ref2 = make_policy(W2, max_seqs=6, max_seq_len=64)
+    try:
+        a1 = r.rlgen_generate(pol, dev_i32(arr), lens, 2, 6, 0.7, dev_f32(u))
+        b2 = r.rlgen_generate(ref2, dev_i32(arr), lens, 2, 6, 0.7, dev_f32(u))
+        assert not torch.equal(a1[1], b2[1])
+        r.rlgen_update_weights(pol, r.upload_weights(W2.tensors))
+        a2 = r.rlgen_generate(pol, dev_i32(arr), lens, 2, 6, 0.7, dev_f32(u))
+        assert torch.equal(a2[0], b2[0]) and torch.equal(a2[1], b2[1])
+        farr, flens = padded([np.concatenate([prompts[b], a2[0][b, j].cpu().numpy()]) for b in range(3) for j in range(2)])
+        assert torch.equal(r.rlgen_score(pol, dev_i32(farr), flens, 0.7), r.rlgen_score(ref2, dev_i32(farr), flens, 0.7))
+    finally:
+        pol.close()
+        ref2.close()
+
+
 # ---------------------------------------------------------------- prompt cache shared by the k samples of a prompt
 @pytest.fixture(scope="module", params=list(GPU_SHAPES))
 def shared(request):

@@ -283,3 +283,50 @@ def test_whole_model_against_transformers_black_box(name):
     # and the fp32 oracle against the same reference
     dec32 = O.Decoder(W, m)
     np.testing.assert_allclose(dec32.logits(dec32.forward(seq, O.KVCache(m.n_layers))), ref, atol=1e-4)
+
+
+def test_greedy_is_the_zero_temperature_limit_and_argmax_of_recomputed_logits():
+    """Pins for temperature 0: the tokens are the argmax of logits recomputed without a cache; sampling at a very
+    low temperature gives the same tokens for any uniforms; the log-prob is log softmax(z)[token] (scipy)."""
+    from scipy.special import log_softmax
+    m = tiny_neox()
+    W = make_weights(m, 5, bf16=False)
+    for k_ in W.tensors:
+        if not k_.endswith("_g"):
+            W.tensors[k_] = W.tensors[k_] * np.float32(6.0)
+    dec = O.Decoder(W, m)
+    rng = np.random.default_rng(1)
+    prompt = rng.integers(0, m.vocab, size=7)
+    u = rng.random((2, 6))
+    toks, lps, margins = O.generate(dec, prompt, 2, 6, 0.0, u)
+    assert (toks[0] == toks[1]).all()
+    seq = list(prompt)
+    for t in range(6):
+        z = O.last_logits(dec, seq)
+        assert toks[0, t] == int(np.argmax(z))
+        assert abs(lps[0, t] - log_softmax(z.astype(np.float64))[toks[0, t]]) < 1e-5
+        top2 = np.sort(z.astype(np.float64))[-2:]
+        assert abs(margins[0, t] - (top2[1] - top2[0])) < 1e-4
+        seq.append(int(toks[0, t]))
+    assert margins.min() > 1e-3
+    cold, _, _ = O.generate(dec, prompt, 2, 6, margins.min() / 200.0, u)
+    np.testing.assert_array_equal(cold, toks)
+
+
+def test_eos_ends_a_completion():
+    m = tiny_llama()
+    W = make_weights(m, 6, bf16=False)
+    dec = O.Decoder(W, m)
+    rng = np.random.default_rng(2)
+    prompt = rng.integers(0, m.vocab, size=5)
+    u = rng.random((3, 8))
+    toks, lps, _ = O.generate(dec, prompt, 3, 8, 0.7, u)
+    eos = int(toks[1, 3])                                    # a token the second sample emits mid-way
+    te, le, me = O.generate(dec, prompt, 3, 8, 0.7, u, eos=eos)
+    for j in range(3):
+        hits = np.nonzero(toks[j] == eos)[0]
+        end = hits[0] + 1 if len(hits) else 8
+        np.testing.assert_array_equal(te[j, :end], toks[j, :end])
+        np.testing.assert_array_equal(le[j, :end], lps[j, :end])
+        assert (te[j, end:] == eos).all() and (le[j, end:] == 0).all() and np.isinf(me[j, end:]).all()
+    assert (te[1, 4:] == eos).all()

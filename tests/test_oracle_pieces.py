@@ -174,3 +174,21 @@ def test_dpo_pair_loss_closed_forms():
     # swapping the pair flips the sign of the argument: loss(+) - loss(-) = -beta*delta
     a, b = O.dpo_pair_loss(-1.0, -2.0, -4.0, -3.0, 0.03), O.dpo_pair_loss(-4.0, -3.0, -1.0, -2.0, 0.03)
     assert a - b == pytest.approx(-0.03 * 2.0, abs=1e-14)
+
+
+def test_select_pair_is_the_extremes_of_a_stable_ranking():
+    """Pins: the K = 2 cases written out; against a ranking by stable sort on random rewards with many ties."""
+    assert O.select_pair([1.0, 2.0]) == (1, 0)
+    assert O.select_pair([2.0, 1.0]) == (0, 1)
+    assert O.select_pair([1.0, 1.0]) == (0, 1)
+    assert O.select_pair([0.5]) == (0, 0)
+    assert O.select_pair([0.0, 3.0, -1.0, 3.0]) == (1, 2)
+    rng = np.random.default_rng(5)
+    for K in (2, 3, 4, 7):
+        for _ in range(200):
+            r = rng.integers(0, 3, size=K).astype(np.float64)        # few distinct values: ties are common
+            pos, neg = O.select_pair(r)
+            best_first = np.argsort(-r, kind="stable")                # descending, earlier index first among equals
+            assert pos == best_first[0]
+            assert neg == K - 1 - np.argsort(r[::-1], kind="stable")[0]   # last of the lowest
+            assert r[pos] == r.max() and r[neg] == r.min() and pos != neg
