@@ -132,8 +132,15 @@ int rlgen_update_weights(rlgen_ctx *ctx, const rlgen_weights *weights, void *hip
  *  token_logprobs out [B, k, max_new] fp32 = log softmax(z / temperature)[token]
  *
  * The k samples of one prompt share one prompt pass.  Errors: NULL, BAD_ARG (B, k, max_new < 1,
- * prompt_len < 1, prompt_stride < max prompt_len, temperature not finite or <= 0, or with
- * share_prompt_kv k * (n_q_heads / n_kv_heads) > 16), CAPACITY, DEVICE. */
+ * prompt_len < 1, prompt_stride < max prompt_len, temperature not finite or < 0, or with
+ * share_prompt_kv k * (n_q_heads / n_kv_heads) > 16), CAPACITY, DEVICE.
+ *
+ * temperature == 0 decodes greedily (the evaluation protocol of Section 5.2): every token is the
+ * first index of the largest logit, uniforms are not read (but must be non-null), and
+ * token_logprobs = log softmax(z)[token].
+ * With an EOS token set (rlgen_set_eos) a completion ends at its first EOS: the entries after it
+ * hold the EOS id at log-prob 0 (forced entries after it are ignored).  The sequence stays in the
+ * batch; its later positions cost the same as live ones. */
 int rlgen_generate(rlgen_ctx *ctx, const int32_t *prompts, const int32_t *prompt_lens, int32_t B,
                    int32_t prompt_stride, int32_t k, int32_t max_new, float temperature,
                    const float *uniforms, const int32_t *forced, int32_t *tokens,
@@ -186,6 +193,11 @@ int rlgen_select_pairs(const float *rewards, int32_t B, int32_t k, int32_t *idx_
 int rlgen_get_timings(rlgen_ctx *ctx, float *prefill_ms, float *decode_ms, float *decode_attn_ms,
                       int32_t *decode_attn_launches);
 int rlgen_set_profiling(rlgen_ctx *ctx, int32_t on);
+
+/* The token id that ends a completion in later rlgen_generate calls on this context (the paper's
+ * completions end in an EOS token or are penalised for lacking one: hyper-parameter tables of
+ * Appendix A.1 and A.2); -1 (the default) = none.  Errors: NULL, BAD_ARG (id outside [-1, vocab)). */
+int rlgen_set_eos(rlgen_ctx *ctx, int32_t eos_token);
 
 /* rlgen_generate decodes a batch of 256 or more sequences as two halves on two internal streams
  * (forked from and joined to the call's stream), so that one half's cache-streaming attention runs

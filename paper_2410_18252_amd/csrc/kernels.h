@@ -169,6 +169,9 @@ struct SampleArgs {
   int io_stride, io_add;
   int* tokens; float* logprobs;         // written at the same index
   int* next_token;                      // nullable [R]: copy of the emitted token for the next decode step
+  int greedy;                           // 1: the token is the first index of the largest logit (uniforms unused)
+  int eos; int* finished;               // eos >= 0 and finished [R] non-null: a row that has emitted eos keeps emitting
+                                        // it at log-prob 0 (forced entries ignored)
   int R;
   unsigned* status;
 };

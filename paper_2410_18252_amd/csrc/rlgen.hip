@@ -66,6 +66,8 @@ struct rlgen_ctx {
   int *d_kv_off, *d_kv_cap, *d_ctx_base, *d_iota, *d_lastrow, *d_order;
   bool use_order;
   bool fused_qkv;         // rotary_dim % 4 == 0: rotary embedding and cache writes run in the QKV GEMM's epilogue
+  int eos_token;          // -1: completions never end early (rlgen_set_eos)
+  int* d_finished;        // [max_seqs] 1 once a sequence of the running call has emitted eos_token
   int share_k;            // samples per prompt of the running generate call when prompts share their cache, else 0
   int *d_tok_index, *d_pos, *d_dst_seq, *d_lm_row, *d_target, *d_out_index, *d_next_token;
   AttnJob* d_jobs;
@@ -179,6 +181,7 @@ size_t carve(rlgen_ctx* c, char* base) {
   c->d_ctx_base = k.take<int>(base, S); c->d_iota = k.take<int>(base, S);
   c->d_lastrow = k.take<int>(base, S); c->d_next_token = k.take<int>(base, S);
   c->d_order = k.take<int>(base, S);
+  c->d_finished = k.take<int>(base, S + 4);
   c->d_tok_index = k.take<int>(base, R); c->d_pos = k.take<int>(base, R); c->d_dst_seq = k.take<int>(base, R);
   c->d_lm_row = k.take<int>(base, R); c->d_target = k.take<int>(base, R); c->d_out_index = k.take<int>(base, R);
   c->d_jobs = k.take<AttnJob>(base, R / 16 + S + 1);
@@ -430,8 +433,11 @@ int lm_head_stats(rlgen_ctx* c, const uint16_t* hfin, int rows, float temperatur
   return RLGEN_OK;
 }
 
+// temperature 0 selects greedy decoding: arg max of the logits, log-prob under softmax(z)
 int sample_rows(rlgen_ctx* c, int rows, float temperature, const float* uniforms, const int* forced, int io_stride,
-                int io_add, int* tokens, float* logprobs, int* next_token, hipStream_t st) {
+                int io_add, int* tokens, float* logprobs, int* next_token, hipStream_t st, int* finished = nullptr) {
+  const bool greedy = temperature == 0.f;
+  if (greedy) temperature = 1.f;
   int rc = lm_head_stats(c, c->hfin, rows, temperature, nullptr, st);
   if (rc) return rc;
   SampleArgs s{};
@@ -439,6 +445,7 @@ int sample_rows(rlgen_ctx* c, int rows, float temperature, const float* uniforms
   s.lm_head = c->lm_head; s.vocab = c->cfg.vocab; s.temperature = temperature;
   s.uniforms = uniforms; s.forced = forced; s.io_index = nullptr; s.io_stride = io_stride; s.io_add = io_add;
   s.tokens = tokens; s.logprobs = logprobs; s.next_token = next_token; s.R = rows; s.status = c->status;
+  s.greedy = greedy ? 1 : 0; s.eos = c->eos_token; s.finished = c->eos_token >= 0 ? finished : nullptr;
   HIPCHK(rl_sample(s, st));
   return RLGEN_OK;
 }
@@ -718,6 +725,7 @@ int rlgen_create(const rlgen_model_cfg* cfg, const rlgen_weights* weights, void*
       hipEventCreate(&c->ev_end) != hipSuccess)
     return fail(RLGEN_ERR_DEVICE);
   c->timed = true;
+  c->eos_token = -1;
   // two internal streams (default priority) for the halves of a large decode batch
   if (!getenv("RLGEN_NO_DECODE_SPLIT")) {
     if (hipStreamCreateWithFlags(&c->gstream[0], hipStreamNonBlocking) != hipSuccess ||
@@ -756,7 +764,7 @@ int rlgen_generate(rlgen_ctx* c, const int32_t* prompts, const int32_t* prompt_l
   if (!c || !prompts || !prompt_lens || !uniforms || !tokens || !token_logprobs) return RLGEN_ERR_NULL;
   const rlgen_model_cfg& m = c->cfg;
   if (B < 1 || k < 1 || max_new < 1 || prompt_stride < 1) return RLGEN_ERR_BAD_ARG;
-  if (!(temperature > 0.f) || !std::isfinite(temperature)) return RLGEN_ERR_BAD_ARG;
+  if (!(temperature >= 0.f) || !std::isfinite(temperature)) return RLGEN_ERR_BAD_ARG;      // 0 = greedy
   if ((long long)B * k > m.max_seqs) return RLGEN_ERR_CAPACITY;
   // shared prompt cache: one stream per prompt plus one short stream of new tokens per sequence; the k samples
   // of a prompt and the query heads of a kv head share the 16 columns of the attention MFMA
@@ -853,7 +861,8 @@ int rlgen_generate(rlgen_ctx* c, const int32_t* prompts, const int32_t* prompt_l
     if (rc) return rc;
   }
   if (c->timed) HIPCHK(hipEventRecord(c->ev_mid, st));
-  rc = sample_rows(c, S, temperature, uniforms, forced, max_new, 0, tokens, token_logprobs, c->d_next_token, st);
+  if (c->eos_token >= 0) HIPCHK(rl_fill_zero(c->d_finished, align_up((size_t)S * 4, 16), st));
+  rc = sample_rows(c, S, temperature, uniforms, forced, max_new, 0, tokens, token_logprobs, c->d_next_token, st, c->d_finished);
   if (rc) return rc;
   // one decode step of sequences g0 .. g0 + n - 1 on stream gs, with the activation set in use
   auto decode_step = [&](int t, DecView dv, int n, hipStream_t gs) -> int {
@@ -864,7 +873,7 @@ int rlgen_generate(rlgen_ctx* c, const int32_t* prompts, const int32_t* prompt_l
     if (r2) return r2;
     const size_t o = (size_t)dv.g0 * max_new;
     return sample_rows(c, n, temperature, uniforms + o, forced ? forced + o : nullptr, max_new, t, tokens + o, token_logprobs + o,
-                       c->d_next_token + dv.g0, gs);
+                       c->d_next_token + dv.g0, gs, c->d_finished + dv.g0);
   };
   if (ngroups == 2 && max_new > 1) {
     HIPCHK(hipEventRecord(c->ev_fork, st));
@@ -965,6 +974,13 @@ int rlgen_set_profiling(rlgen_ctx* c, int32_t on) {
   if (!c) return RLGEN_ERR_NULL;
   c->profiling = on > 0 ? on : 0;
   if (!on) c->prof_used = 0;
+  return RLGEN_OK;
+}
+
+int rlgen_set_eos(rlgen_ctx* c, int32_t eos_token) {
+  if (!c) return RLGEN_ERR_NULL;
+  if (eos_token < -1 || eos_token >= c->cfg.vocab) return RLGEN_ERR_BAD_ARG;
+  c->eos_token = eos_token;
   return RLGEN_OK;
 }
 

@@ -33,7 +33,15 @@ __global__ __launch_bounds__(256) void sample_kernel(SampleArgs a) {
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= a.R) return;
   const size_t idx = (size_t)(a.io_index ? a.io_index[row] : row) * a.io_stride + a.io_add;
-  float u = a.uniforms[idx];
+  if (a.finished && a.finished[row]) {            // the completion ended at an earlier step
+    if (lane == 0) {
+      a.tokens[idx] = a.eos;
+      a.logprobs[idx] = 0.f;
+      if (a.next_token) a.next_token[row] = a.eos;
+    }
+    return;
+  }
+  float u = a.greedy ? 0.f : a.uniforms[idx];
   if (!(u >= 0.f && u < 1.f)) {
     if (lane == 0) atomicOr(a.status, RLGEN_FAULT_UNIFORM);
     u = (u >= 1.f) ? 0.99999994f : 0.f;
@@ -79,6 +87,15 @@ __global__ __launch_bounds__(256) void sample_kernel(SampleArgs a) {
   if (gmin == 0x7fffffff) gmin = a.ngroups - 1;                 // cannot happen for u < 1; stay in bounds
   const int owner = min(gmin / per, 63);
   base = __shfl(gsel == gmin ? base : run, owner, WAVE);
+  if (a.greedy) {
+    // the first group that holds the largest logit: M is the largest group maximum
+    int gbest = 0x7fffffff;
+    for (int g = g0; g < g1; ++g)
+      if (p[g].x == M) { gbest = g; break; }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) gbest = min(gbest, __shfl_xor(gbest, o, WAVE));
+    gmin = gbest == 0x7fffffff ? 0 : gbest;
+  }
   if (forced >= 0) gmin = forced >> 6;
 
   // recompute the 64 tempered logits of group gmin: lane j <-> column 64 gmin + j
@@ -100,6 +117,10 @@ __global__ __launch_bounds__(256) void sample_kernel(SampleArgs a) {
   int tok;
   if (forced >= 0) {
     tok = forced;
+  } else if (a.greedy) {
+    const float best = wave_max(logit);
+    const unsigned long long at = __ballot(logit == best);
+    tok = min(gmin * 64 + (at ? __ffsll((long long)at) - 1 : 0), a.vocab - 1);
   } else {
     const double e = (logit == -INFINITY) ? 0.0 : (double)__expf(logit - M);
     const double cum = base + wave_incl_scan(e, lane);
@@ -116,6 +137,7 @@ __global__ __launch_bounds__(256) void sample_kernel(SampleArgs a) {
     a.tokens[idx] = tok;
     a.logprobs[idx] = (float)((double)ltok - logZ);
     if (a.next_token) a.next_token[row] = tok;
+    if (a.finished && tok == a.eos) a.finished[row] = 1;
   }
 }
 

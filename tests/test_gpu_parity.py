@@ -234,7 +234,7 @@ def test_argument_and_capacity_errors(small):
 
     assert code(lambda: r.rlgen_generate(pol, d, [3, 0], 2, 4, 0.7, u)) == r.ERR_BAD_ARG
     assert code(lambda: r.rlgen_generate(pol, d, [3, 4], 2, 4, 0.7, u)) == r.ERR_BAD_ARG          # longer than stride
-    assert code(lambda: r.rlgen_generate(pol, d, lens, 2, 4, 0.0, u)) == r.ERR_BAD_ARG
+    assert code(lambda: r.rlgen_generate(pol, d, lens, 2, 4, -0.5, u)) == r.ERR_BAD_ARG
     assert code(lambda: r.rlgen_generate(pol, d, lens, 2, 4, float("nan"), u)) == r.ERR_BAD_ARG
     assert code(lambda: r.rlgen_generate(pol, d, lens, 2, 4, -1.0, u)) == r.ERR_BAD_ARG
     big_u = dev_f32(np.zeros((2, 2, 78), np.float32))
@@ -437,3 +437,73 @@ def test_split_decode_matches_oracle_and_unsplit(name, share, monkeypatch):
         assert r.rlgen_status(pol) == 0
     finally:
         pol.close()
+
+
+# ---------------------------------------------------------------- greedy decoding and completions that end at EOS
+GREEDY_MARGIN = 2 * TOL_LOGITS        # the oracle's arg max is unambiguous when its lead exceeds both sides' logit error
+
+
+@pytest.mark.parametrize("share", [0, 1])
+def test_greedy_matches_oracle(small, share):
+    m, W, dec, pol0 = small
+    pol = pol0 if not share else make_policy(W, max_seqs=12, max_seq_len=80, max_batch_tokens=80, share_prompt_kv=1)
+    try:
+        rng = np.random.default_rng(51)
+        B, k, T = 4, 2, 8
+        prompts = rand_seqs(rng, m.vocab, [9, 33, 1, 64])
+        arr, lens = padded(prompts)
+        u = np.full((B, k, T), 0.123, np.float32)
+        r = R()
+        t_o, l_o, margins, _, _ = oracle_generate_batch(dec, arr, lens, k, T, 0.0, u)
+        forced = np.where(margins > GREEDY_MARGIN, -1, t_o).astype(np.int32)
+        t_g, l_g = r.rlgen_generate(pol, dev_i32(arr), lens, k, T, 0.0, dev_f32(u), dev_i32(forced))
+        t_g, l_g = t_g.cpu().numpy(), l_g.cpu().numpy()
+        report("greedy", err=np.abs(l_g - l_o).max(), free=(forced < 0).mean(), h=m.head_dim)
+        np.testing.assert_array_equal(t_g, t_o)
+        assert np.abs(l_g - l_o).max() < TOL_LOGPROB
+        assert (forced < 0).mean() > 0.3
+        np.testing.assert_array_equal(t_g[:, 0], t_g[:, 1])          # both samples of a prompt are the same completion
+        # unforced: along the GPU's own path every token's logit is within the logit tolerance of the oracle's maximum
+        t_f, _ = r.rlgen_generate(pol, dev_i32(arr), lens, k, T, 0.0, dev_f32(u))
+        t_f = t_f.cpu().numpy()
+        for b in range(B):
+            seq = list(prompts[b])
+            for t in range(T):
+                z = O.last_logits(dec, seq)
+                assert z[t_f[b, 0, t]] >= z.max() - GREEDY_MARGIN
+                seq.append(int(t_f[b, 0, t]))
+        assert r.rlgen_status(pol) == 0
+    finally:
+        if share:
+            pol.close()
+
+
+@pytest.mark.parametrize("temp", [0.7, 0.0])
+def test_eos_ends_completions(small, temp):
+    m, W, dec, pol = small
+    rng = np.random.default_rng(52)
+    B, k, T = 5, 2, 9
+    prompts = rand_seqs(rng, m.vocab, [12, 40, 3, 64, 21])
+    arr, lens = padded(prompts)
+    u = rng.random((B, k, T), dtype=np.float32)
+    r = R()
+    t0, _, _, _, _ = oracle_generate_batch(dec, arr, lens, k, T, temp, u)
+    eos = int(np.bincount(t0[:, :, 2:6].ravel()).argmax())            # a token several completions emit mid-way
+    t_o, l_o, margins, _, _ = oracle_generate_batch(dec, arr, lens, k, T, temp, u, eos=eos)
+    ended = (t_o == eos).any(axis=2)
+    assert ended.any() and (t_o[:, :, -1] == eos).any()
+    forced = np.where(margins > (MARGIN if temp > 0 else GREEDY_MARGIN), -1, t_o).astype(np.int32)
+    try:
+        r.rlgen_set_eos(pol, eos)
+        t_g, l_g = r.rlgen_generate(pol, dev_i32(arr), lens, k, T, temp, dev_f32(u), dev_i32(forced))
+        t_g, l_g = t_g.cpu().numpy(), l_g.cpu().numpy()
+        np.testing.assert_array_equal(t_g, t_o)
+        assert np.abs(l_g - l_o).max() < TOL_LOGPROB
+        after = np.cumsum(np.cumsum(t_o == eos, axis=2), axis=2) > 1      # strictly after the first EOS
+        assert (l_g[after] == 0).all() and (t_g[after] == eos).all()
+        with pytest.raises(r.RlgenError):
+            r.rlgen_set_eos(pol, m.vocab)
+    finally:
+        r.rlgen_set_eos(pol, -1)
+    t_n, _ = r.rlgen_generate(pol, dev_i32(arr), lens, k, T, temp, dev_f32(u), dev_i32(np.where(forced >= 0, t0, -1).astype(np.int32)))
+    assert r.rlgen_status(pol) == 0
