@@ -426,9 +426,9 @@ hipError_t launch_k(const GemmArgs& g, hipStream_t s) {
 
 // Whole K tiles take the direct-load pipeline with two LDS stages (more stages measured slower: the extra LDS
 // costs a resident block); a ragged K falls back to register staging, which can zero-fill the tail.
-template <int BM, int BN, int WM, int WN, int EPI>
+template <int BM, int BN, int WM, int WN, int EPI, int NS = 2>
 hipError_t launch(const GemmArgs& g, hipStream_t s) {
-  return g.K % BK == 0 ? launch_k<BM, BN, WM, WN, EPI, false, 2>(g, s) : launch_k<BM, BN, WM, WN, EPI, true, 0>(g, s);
+  return g.K % BK == 0 ? launch_k<BM, BN, WM, WN, EPI, false, NS>(g, s) : launch_k<BM, BN, WM, WN, EPI, true, 0>(g, s);
 }
 
 template <int EPI>
@@ -445,6 +445,9 @@ hipError_t launch_variant(const GemmArgs& g, int variant, hipStream_t s) {
       else return hipErrorInvalidValue;
     case 7:
       if constexpr (EPI != EPI_SWIGLU_F16 && EPI != EPI_LMHEAD) return launch<64, 128, 1, 4, EPI>(g, s);
+      else return hipErrorInvalidValue;
+    case 8:      // the smallest tile with four LDS stages: loads three K steps ahead, for launches with few blocks per CU
+      if constexpr (EPI != EPI_SWIGLU_F16 && EPI != EPI_LMHEAD) return launch<64, 128, 1, 4, EPI, 4>(g, s);
       else return hipErrorInvalidValue;
   }
   return hipErrorInvalidValue;
