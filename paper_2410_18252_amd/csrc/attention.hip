@@ -60,6 +60,11 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a) {
       // the K samples of prompt u sit in the MFMA columns (next to the G query heads of the kv head): the
       // prompt's keys and values are read once for all of them, then each sample's own new tokens
       const int j = (c / G) % a.share_k;
+      if (a.finished) {           // nothing to do once every sample of the prompt has ended
+        bool live = false;
+        for (int jj = 0; jj < a.share_k; ++jj) live |= a.finished[u * a.share_k + jj] == 0;
+        if (!live) return;
+      }
       qrow = u * a.share_k + j;
       seq0 = u;
       len0 = a.ctx_base[u * a.share_k];
@@ -68,6 +73,7 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a) {
       nseg = 1 + a.share_k;
       store_col = c < G * a.share_k;
     } else {
+      if (a.finished && a.finished[u]) return;      // an ended completion's output is never used: do not stream its cache
       qrow = u;
       seq0 = u;
       len0 = a.ctx_base[u] + a.ctx_add;
@@ -110,6 +116,7 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a) {
   float m = -INFINITY, lsum = 0.f;
 
   for (int seg = 0; seg < nseg; ++seg) {
+    if (seg > 0 && a.finished && a.finished[qrow - (c / G) % a.share_k + seg - 1]) continue;     // ended sample: skip its stream
     const int cache_seq = seg == 0 ? seq0 : sfx_seq0 + seg - 1;
     const int nkeys = seg == 0 ? len0 : sfx_len;
     const bool mine = seg == 0 || (c / G) % a.share_k == seg - 1;     // does column c attend to this segment

@@ -383,6 +383,7 @@ int run_layers(rlgen_ctx* c, int rows, bool decode, int t, int ncopy, bool use_c
       a.kv_off = c->d_kv_off + u0; a.kv_cap = c->d_kv_cap + u0;
       a.ctx_base = c->d_ctx_base + dv.g0; a.ctx_add = t; a.S = rows; a.order = c->use_order ? c->d_order + u0 : nullptr;
       a.share_k = c->share_k; a.sfx_first = c->share_k ? dv.B + dv.g0 - dv.b0 : 0;
+      a.finished = c->eos_token >= 0 ? c->d_finished + dv.g0 : nullptr;
       hipEvent_t e0 = nullptr, e1 = nullptr;
       if (c->profiling > 0 && (l + t) % c->profiling == 0) {
         while (c->prof_events.size() < c->prof_used + 2) {

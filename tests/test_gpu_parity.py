@@ -478,9 +478,23 @@ def test_greedy_matches_oracle(small, share):
             pol.close()
 
 
+@pytest.mark.parametrize("share", [0, 1])
 @pytest.mark.parametrize("temp", [0.7, 0.0])
-def test_eos_ends_completions(small, temp):
-    m, W, dec, pol = small
+def test_eos_ends_completions(small, temp, share):
+    """Ended completions report EOS at log-prob 0 from then on, and decode attention stops reading their cache
+    (with a shared prompt cache: the prompt's stream is skipped once all its samples have ended)."""
+    m, W, dec, pol0 = small
+    if share:
+        pol = make_policy(W, max_seqs=12, max_seq_len=80, max_batch_tokens=80, share_prompt_kv=1)
+        try:
+            _check_eos(m, dec, pol, temp)
+        finally:
+            pol.close()
+    else:
+        _check_eos(m, dec, pol0, temp)
+
+
+def _check_eos(m, dec, pol, temp):
     rng = np.random.default_rng(52)
     B, k, T = 5, 2, 9
     prompts = rand_seqs(rng, m.vocab, [12, 40, 3, 64, 21])
