@@ -521,3 +521,33 @@ def _check_eos(m, dec, pol, temp):
         r.rlgen_set_eos(pol, -1)
     t_n, _ = r.rlgen_generate(pol, dev_i32(arr), lens, k, T, temp, dev_f32(u), dev_i32(np.where(forced >= 0, t0, -1).astype(np.int32)))
     assert r.rlgen_status(pol) == 0
+
+
+# ---------------------------------------------------------------- degenerate sizes
+@pytest.mark.parametrize("share", [0, 1])
+def test_degenerate_sizes(small, share, monkeypatch):
+    """One prompt of one token, one sample, one new token (no decode step at all); then the context filled to its
+    exact capacity in sequences, sequence length and cache tokens; with the two-stream decode forced on."""
+    m, W, dec, _ = small
+    monkeypatch.setenv("RLGEN_DECODE_SPLIT_MIN", "2")
+    r = R()
+    S, L = 6, 40
+    need = S * 64 if not share else 3 * 32 + S * 32            # 3 prompts x 2 samples: prompts of 8 + 32 new tokens
+    pol = make_policy(W, max_seqs=S, max_seq_len=L, max_kv_tokens=need, max_batch_tokens=L, share_prompt_kv=share)
+    try:
+        rng = np.random.default_rng(61)
+        for B, k, P, T in ((1, 1, 1, 1), (1, 1, L - 1, 1), (3, 2, 8, 32), (2, 3, 8, 1)):
+            prompts = rand_seqs(rng, m.vocab, [P] * B)
+            arr, lens = padded(prompts)
+            u = rng.random((B, k, T), dtype=np.float32)
+            t_o, l_o, margins, _, _ = oracle_generate_batch(dec, arr, lens, k, T, 0.7, u)
+            forced = np.where(margins > MARGIN, -1, t_o).astype(np.int32)
+            t_g, l_g = r.rlgen_generate(pol, dev_i32(arr), lens, k, T, 0.7, dev_f32(u), dev_i32(forced))
+            np.testing.assert_array_equal(t_g.cpu().numpy(), t_o)
+            assert np.abs(l_g.cpu().numpy() - l_o).max() < TOL_LOGPROB, (B, k, P, T)
+        with pytest.raises(r.RlgenError) as e:                   # one more new token than the cache holds
+            r.rlgen_generate(pol, dev_i32(arr), lens, 3, 33 if share else 57, 0.7, dev_f32(np.zeros((2, 3, 33 if share else 57), np.float32)))
+        assert e.value.code == r.ERR_CAPACITY
+        assert r.rlgen_status(pol) == 0
+    finally:
+        pol.close()
