@@ -196,7 +196,13 @@ int rlgen_set_profiling(rlgen_ctx *ctx, int32_t on);
 
 /* The token id that ends a completion in later rlgen_generate calls on this context (the paper's
  * completions end in an EOS token or are penalised for lacking one: hyper-parameter tables of
- * Appendix A.1 and A.2); -1 (the default) = none.  Errors: NULL, BAD_ARG (id outside [-1, vocab)). */
+ * Appendix A.1 and A.2); -1 (the default) = none.  With an EOS id set and one cache per sequence
+ * (share_prompt_kv = 0), rlgen_generate drops ended sequences from the batch: every 8 decode steps
+ * it WAITS for the stream, reads which sequences have ended, fills the rest of their outputs and
+ * continues with the others (and returns early once none is left), so the call is no longer purely
+ * asynchronous.  With share_prompt_kv = 1 ended sequences stay in the batch and only stop reading
+ * their cache.  The outputs are the same either way.
+ * Errors: NULL, BAD_ARG (id outside [-1, vocab)). */
 int rlgen_set_eos(rlgen_ctx *ctx, int32_t eos_token);
 
 /* rlgen_generate decodes a batch of 256 or more sequences as two halves on two internal streams

@@ -75,7 +75,7 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a) {
     } else {
       if (a.finished && a.finished[u]) return;      // an ended completion's output is never used: do not stream its cache
       qrow = u;
-      seq0 = u;
+      seq0 = a.cache_seq_of ? a.cache_seq_of[u] : u;       // rows of a compacted batch name their cache sequence
       len0 = a.ctx_base[u] + a.ctx_add;
       nseg = 1;
       store_col = c < G;

@@ -100,6 +100,7 @@ struct AttnArgs {
   // shared prompt cache: 0 = off.  K = samples per prompt: sequence s = prompt * K + j; cache sequence `prompt`
   // holds the prompt's keys (ctx_base[prompt * K] of them), cache sequence sfx_first + s the ctx_add new tokens of s
   int share_k, sfx_first;
+  const int* cache_seq_of;            // nullable [S] (not with share_k): cache sequence of row i, default i (kv_off / kv_cap index)
   const int* finished;                // nullable [S]: sequences whose completion has ended are skipped (their output rows keep
                                       // whatever they held; nothing downstream of an ended sequence is used)
   // prefill

@@ -68,6 +68,9 @@ struct rlgen_ctx {
   bool fused_qkv;         // rotary_dim % 4 == 0: rotary embedding and cache writes run in the QKV GEMM's epilogue
   int eos_token;          // -1: completions never end early (rlgen_set_eos)
   int* d_finished;        // [max_seqs] 1 once a sequence of the running call has emitted eos_token
+  int eos_every;          // ended sequences are dropped from the batch every this many decode steps (0: never)
+  int *d_cmp, *d_lists;   // compacted per-row arrays (2 sides x 4 x max_seqs) and uploaded index lists (3 x max_seqs)
+  int *h_fin, *h_lists;   // pinned: downloaded flags [max_seqs], index lists [3 max_seqs]
   int share_k;            // samples per prompt of the running generate call when prompts share their cache, else 0
   int *d_tok_index, *d_pos, *d_dst_seq, *d_lm_row, *d_target, *d_out_index, *d_next_token;
   AttnJob* d_jobs;
@@ -182,6 +185,7 @@ size_t carve(rlgen_ctx* c, char* base) {
   c->d_lastrow = k.take<int>(base, S); c->d_next_token = k.take<int>(base, S);
   c->d_order = k.take<int>(base, S);
   c->d_finished = k.take<int>(base, S + 4);
+  c->d_cmp = k.take<int>(base, 8 * S); c->d_lists = k.take<int>(base, 3 * S);
   c->d_tok_index = k.take<int>(base, R); c->d_pos = k.take<int>(base, R); c->d_dst_seq = k.take<int>(base, R);
   c->d_lm_row = k.take<int>(base, R); c->d_target = k.take<int>(base, R); c->d_out_index = k.take<int>(base, R);
   c->d_jobs = k.take<AttnJob>(base, R / 16 + S + 1);
@@ -289,6 +293,19 @@ __global__ void tune_rows_kernel(int* pos, int* dst_seq, int* kv_off, int* kv_ca
     kv_cap[i] = 32;
   }
 }
+// Rows keep[0 .. n) of a decode batch become rows 0 .. n of the compacted one (none of them has ended).
+__global__ void compact_rows_kernel(const int* keep, int n, const int* seq, const int* ctx, const int* next, int* seq2, int* ctx2,
+                                    int* next2, int* fin2) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const int r = keep[i];
+  seq2[i] = seq[r]; ctx2[i] = ctx[r]; next2[i] = next[r]; fin2[i] = 0;
+}
+// Outputs of steps t .. T - 1 of sequences that ended before step t: the EOS id at log-prob 0.  One block per sequence.
+__global__ void fill_tail_kernel(const int* seqs, int t, int T, int eos, int* tokens, float* logprobs) {
+  const size_t o = (size_t)seqs[blockIdx.x] * T;
+  for (int i = t + threadIdx.x; i < T; i += blockDim.x) { tokens[o + i] = eos; logprobs[o + i] = 0.f; }
+}
 __global__ void fill_f32_kernel(float* p, size_t n, float v) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -335,7 +352,12 @@ QkvEpi qkv_epilogue(const RopeArgs& r, uint16_t* kvstage) {
 //          ctx_base + t - 1); otherwise rows follow d_pos / d_dst_seq / d_jobs of the current chunk.
 // A decode step covers sequences g0 .. g0 + rows - 1 (all of the call's, or one half); with a shared prompt cache
 // these are the samples of prompts b0 .. of the call's B prompts.
-struct DecView { int g0, b0, B; };
+struct DecView {
+  int g0, b0, B;
+  // compacted batch (after ended sequences were dropped): per-row arrays instead of the per-sequence ones at g0
+  const int* row_seq = nullptr; const int* row_ctx = nullptr; int* row_next = nullptr; int* row_fin = nullptr;
+  const int* row_order = nullptr;
+};
 // Below this many sequences a decode step is too short to gain from running as two concurrent halves.
 constexpr int DECODE_SPLIT_MIN_SEQS = 256;     // RLGEN_DECODE_SPLIT_MIN overrides it at context creation
 
@@ -357,7 +379,8 @@ int run_layers(rlgen_ctx* c, int rows, bool decode, int t, int ncopy, bool use_c
     r.qkv = c->qkv; r.rows = rows; r.Hq = m.n_q_heads; r.Hkv = m.n_kv_heads; r.h = h; r.r = m.rotary_dim;
     r.table = c->rope; r.q = c->q; r.kv = kvl; r.lay = c->lay; r.kv_off = c->d_kv_off; r.kv_cap = c->d_kv_cap;
     if (decode) {
-      r.pos = c->d_ctx_base + dv.g0; r.pos_add = t - 1; r.dst_seq = c->d_iota + dv.g0; r.ncopy = 1;
+      r.pos = dv.row_seq ? dv.row_ctx : c->d_ctx_base + dv.g0; r.pos_add = t - 1;
+      r.dst_seq = dv.row_seq ? dv.row_seq : c->d_iota + dv.g0; r.ncopy = 1;
       r.slot_sub = c->share_k ? c->d_ctx_base + dv.g0 : nullptr;     // new tokens start at slot 0 of their own stream
     }
     else { r.pos = c->d_pos; r.pos_add = 0; r.dst_seq = c->d_dst_seq; r.ncopy = ncopy; r.v_by_blocks = 1; r.jobs = c->d_jobs; r.njobs = njobs; }
@@ -384,6 +407,10 @@ int run_layers(rlgen_ctx* c, int rows, bool decode, int t, int ncopy, bool use_c
       a.ctx_base = c->d_ctx_base + dv.g0; a.ctx_add = t; a.S = rows; a.order = c->use_order ? c->d_order + u0 : nullptr;
       a.share_k = c->share_k; a.sfx_first = c->share_k ? dv.B + dv.g0 - dv.b0 : 0;
       a.finished = c->eos_token >= 0 ? c->d_finished + dv.g0 : nullptr;
+      if (dv.row_seq) {
+        a.kv_off = c->d_kv_off; a.kv_cap = c->d_kv_cap; a.cache_seq_of = dv.row_seq; a.ctx_base = dv.row_ctx;
+        a.order = dv.row_order; a.finished = dv.row_fin;
+      }
       hipEvent_t e0 = nullptr, e1 = nullptr;
       if (c->profiling > 0 && (l + t) % c->profiling == 0) {
         while (c->prof_events.size() < c->prof_used + 2) {
@@ -436,7 +463,8 @@ int lm_head_stats(rlgen_ctx* c, const uint16_t* hfin, int rows, float temperatur
 
 // temperature 0 selects greedy decoding: arg max of the logits, log-prob under softmax(z)
 int sample_rows(rlgen_ctx* c, int rows, float temperature, const float* uniforms, const int* forced, int io_stride,
-                int io_add, int* tokens, float* logprobs, int* next_token, hipStream_t st, int* finished = nullptr) {
+                int io_add, int* tokens, float* logprobs, int* next_token, hipStream_t st, int* finished = nullptr,
+                const int* io_index = nullptr) {
   const bool greedy = temperature == 0.f;
   if (greedy) temperature = 1.f;
   int rc = lm_head_stats(c, c->hfin, rows, temperature, nullptr, st);
@@ -444,7 +472,7 @@ int sample_rows(rlgen_ctx* c, int rows, float temperature, const float* uniforms
   SampleArgs s{};
   s.partial = c->partial; s.ngroups = c->ngroups; s.hfin = c->hfin; s.d = c->cfg.d_model;
   s.lm_head = c->lm_head; s.vocab = c->cfg.vocab; s.temperature = temperature;
-  s.uniforms = uniforms; s.forced = forced; s.io_index = nullptr; s.io_stride = io_stride; s.io_add = io_add;
+  s.uniforms = uniforms; s.forced = forced; s.io_index = io_index; s.io_stride = io_stride; s.io_add = io_add;
   s.tokens = tokens; s.logprobs = logprobs; s.next_token = next_token; s.R = rows; s.status = c->status;
   s.greedy = greedy ? 1 : 0; s.eos = c->eos_token; s.finished = c->eos_token >= 0 ? finished : nullptr;
   HIPCHK(rl_sample(s, st));
@@ -728,6 +756,13 @@ int rlgen_create(const rlgen_model_cfg* cfg, const rlgen_weights* weights, void*
     return fail(RLGEN_ERR_DEVICE);
   c->timed = true;
   c->eos_token = -1;
+  {
+    const char* e = getenv("RLGEN_EOS_COMPACT_EVERY");
+    c->eos_every = e ? atoi(e) : 8;
+    if (c->eos_every < 0) c->eos_every = 0;
+  }
+  if (hipHostMalloc((void**)&c->h_fin, (size_t)4 * S * sizeof(int), hipHostMallocDefault) != hipSuccess) return fail(RLGEN_ERR_DEVICE);
+  c->h_lists = c->h_fin + S;
   // two internal streams (default priority) for the halves of a large decode batch
   if (!getenv("RLGEN_NO_DECODE_SPLIT")) {
     if (hipStreamCreateWithFlags(&c->gstream[0], hipStreamNonBlocking) != hipSuccess ||
@@ -834,6 +869,9 @@ int rlgen_generate(rlgen_ctx* c, const int32_t* prompts, const int32_t* prompt_l
     const double kv_bytes = 4.0 * kvd * ctx * m.n_layers;
     split = kv_bytes >= 4.0 * weight_bytes;
   }
+  // with EOS set and one cache per sequence, ended sequences leave the batch (single stream; see the decode loop)
+  const bool compacting = c->eos_token >= 0 && !share && c->eos_every > 0 && max_new > 1;
+  if (compacting) split = false;
   const int ngroups = split ? 2 : 1;
   const int Bh = ngroups == 2 ? (B + 1) / 2 : B;       // (B + 1) / 2 * k <= (max_seqs + 1) / 2 rows for k >= 1, B * k <= max_seqs
   {
@@ -868,11 +906,13 @@ int rlgen_generate(rlgen_ctx* c, const int32_t* prompts, const int32_t* prompt_l
   if (rc) return rc;
   // one decode step of sequences g0 .. g0 + n - 1 on stream gs, with the activation set in use
   auto decode_step = [&](int t, DecView dv, int n, hipStream_t gs) -> int {
-    HIPCHK(rl_embed(c->x, c->embed, c->d_next_token + dv.g0, nullptr, n, m.d_model, m.vocab, c->status, gs));
+    HIPCHK(rl_embed(c->x, c->embed, dv.row_seq ? dv.row_next : c->d_next_token + dv.g0, nullptr, n, m.d_model, m.vocab, c->status, gs));
     int r2 = run_layers(c, n, true, t, 1, true, 0, gs, dv);
     if (r2) return r2;
     r2 = final_norm(c, nullptr, n, n, 0, gs);
     if (r2) return r2;
+    if (dv.row_seq)       // row i reads and writes the entries of sequence row_seq[i]
+      return sample_rows(c, n, temperature, uniforms, forced, max_new, t, tokens, token_logprobs, dv.row_next, gs, dv.row_fin, dv.row_seq);
     const size_t o = (size_t)dv.g0 * max_new;
     return sample_rows(c, n, temperature, uniforms + o, forced ? forced + o : nullptr, max_new, t, tokens + o, token_logprobs + o,
                        c->d_next_token + dv.g0, gs, c->d_finished + dv.g0);
@@ -895,6 +935,55 @@ int rlgen_generate(rlgen_ctx* c, const int32_t* prompts, const int32_t* prompt_l
       HIPCHK(hipStreamWaitEvent(st, c->ev_join[gi], 0));
     }
     if (rc) return rc;
+  } else if (compacting) {
+    // Completions end at EOS: every eos_every steps the host reads which sequences have ended (this waits for the
+    // stream), fills the rest of their outputs and drops them from the batch; the rows that remain are gathered
+    // into fresh per-row arrays.  The cache is addressed by sequence, so nothing in it moves.
+    std::vector<int> row_seq(S);
+    for (int q = 0; q < S; ++q) row_seq[q] = q;
+    DecView dv{0, 0, B};
+    dv.row_seq = c->d_iota; dv.row_ctx = c->d_ctx_base; dv.row_next = c->d_next_token; dv.row_fin = c->d_finished;
+    dv.row_order = c->use_order ? c->d_order : nullptr;
+    int rows = S, side = 0;
+    for (int t = 1; t < max_new && rows > 0; ++t) {
+      if (t % c->eos_every == 0) {
+        HIPCHK(hipMemcpyAsync(c->h_fin, dv.row_fin, (size_t)rows * 4, hipMemcpyDeviceToHost, st));
+        HIPCHK(hipStreamSynchronize(st));
+        int kept = 0, gone = 0;
+        int* keep = c->h_lists;             // [0, kept): rows that stay; then the sequence ids that leave; then the new order
+        std::vector<int> left;
+        for (int i = 0; i < rows; ++i)
+          if (c->h_fin[i]) left.push_back(row_seq[i]);
+          else { keep[kept] = i; row_seq[kept] = row_seq[i]; ++kept; }
+        gone = (int)left.size();
+        if (gone > 0) {
+          int* h_left = keep + kept;
+          int* h_order = h_left + gone;
+          for (int i = 0; i < gone; ++i) h_left[i] = left[i];
+          for (int i = 0; i < kept; ++i) h_order[i] = i;
+          std::stable_sort(h_order, h_order + kept, [&](int x, int y) { return prompt_lens[row_seq[x] / k] > prompt_lens[row_seq[y] / k]; });
+          HIPCHK(hipMemcpyAsync(c->d_lists, keep, (size_t)(2 * kept + gone) * 4, hipMemcpyHostToDevice, st));
+          int* d_keep = c->d_lists;
+          int* d_left = d_keep + kept;
+          int* d_ord = d_left + gone;
+          hipLaunchKernelGGL(fill_tail_kernel, dim3(gone), dim3(64), 0, st, d_left, t, max_new, c->eos_token, tokens, token_logprobs);
+          HIPCHK(hipGetLastError());
+          if (kept > 0) {
+            int* base = c->d_cmp + (size_t)side * 4 * S;
+            hipLaunchKernelGGL(compact_rows_kernel, dim3((kept + 255) / 256), dim3(256), 0, st, d_keep, kept, dv.row_seq, dv.row_ctx,
+                               dv.row_next, base, base + S, base + 2 * S, base + 3 * S);
+            HIPCHK(hipGetLastError());
+            dv.row_seq = base; dv.row_ctx = base + S; dv.row_next = base + 2 * S; dv.row_fin = base + 3 * S;
+            dv.row_order = (long long)kept * m.n_kv_heads <= 8192 ? d_ord : nullptr;
+            side ^= 1;
+          }
+          rows = kept;
+          if (rows == 0) break;
+        }
+      }
+      rc = decode_step(t, dv, rows, st);
+      if (rc) return rc;
+    }
   } else {
     for (int t = 1; t < max_new; ++t) {
       rc = decode_step(t, DecView{0, 0, B}, S, st);
@@ -1033,6 +1122,7 @@ void rlgen_destroy(rlgen_ctx* c) {
     }
   }
   if (c->h_stage) (void)hipHostFree(c->h_stage);
+  if (c->h_fin) (void)hipHostFree(c->h_fin);
   delete c;
 }
 

@@ -551,3 +551,47 @@ def test_degenerate_sizes(small, share, monkeypatch):
         assert r.rlgen_status(pol) == 0
     finally:
         pol.close()
+
+
+@pytest.mark.parametrize("every", [1, 2, 5])
+@pytest.mark.parametrize("name", ["neox-h80", "llama-gqa4-h16"])
+def test_ended_sequences_leave_the_batch(name, every, monkeypatch):
+    """EOS is forced at chosen steps of chosen sequences (a forced token counts as emitted on both sides), so the
+    batch shrinks several times, down to nothing before the last step in one case; outputs must match the oracle
+    and, bit for bit, a context that keeps ended sequences in the batch."""
+    m = GPU_SHAPES[name]
+    W = scaled_bf16_weights(m)
+    dec = O.Decoder(W, m)
+    rng = np.random.default_rng(71)
+    B, k, T, temp = 4, 2, 14, 0.7
+    prompts = rand_seqs(rng, m.vocab, [30, 5, 64, 17])
+    arr, lens = padded(prompts)
+    u = rng.random((B, k, T), dtype=np.float32)
+    eos = 3
+    r = R()
+    for schedule in ({0: 0, 1: 1, 2: 2, 5: 3, 7: 9}, {q: q % 3 for q in range(8)}):      # sequence -> step of its EOS
+        plan = np.full((B * k, T), -1, np.int32)
+        for q, t in schedule.items():
+            plan[q, t] = eos
+        plan = plan.reshape(B, k, T)
+        t_o, l_o, margins, _, _ = oracle_generate_batch(dec, arr, lens, k, T, temp, u, forced=plan, eos=eos)
+        forced = np.where(plan >= 0, plan, np.where(margins > MARGIN, -1, t_o)).astype(np.int32)
+        outs = []
+        for ev in (every, 0):
+            monkeypatch.setenv("RLGEN_EOS_COMPACT_EVERY", str(ev))
+            pol = make_policy(W, max_seqs=8, max_seq_len=80, max_batch_tokens=80)
+            try:
+                r.rlgen_set_eos(pol, eos)
+                t_g, l_g = r.rlgen_generate(pol, dev_i32(arr), lens, k, T, temp, dev_f32(u), dev_i32(forced))
+                assert r.rlgen_status(pol) == 0
+                outs.append((t_g.cpu().numpy(), l_g.cpu().numpy()))
+            finally:
+                pol.close()
+        np.testing.assert_array_equal(outs[0][0], t_o)
+        assert np.abs(outs[0][1] - l_o).max() < TOL_LOGPROB
+        np.testing.assert_array_equal(outs[0][0], outs[1][0])
+        np.testing.assert_array_equal(outs[0][1], outs[1][1])
+        ended_at = {q: t for q, t in schedule.items()}
+        flat_t, flat_l = outs[0][0].reshape(B * k, T), outs[0][1].reshape(B * k, T)
+        for q, t in ended_at.items():
+            assert (flat_t[q, t:] == eos).all() and (flat_l[q, t + 1:] == 0).all()
