@@ -50,6 +50,9 @@ def main():
                     help="skip the extra pass that times the attention kernel with nothing beside it")
     ap.add_argument("--no-decode-split", action="store_true",
                     help="decode the whole batch on one stream (every kernel runs alone; slower)")
+    ap.add_argument("--eos-mix", action="store_true",
+                    help="completions end at an EOS token forced at a step drawn uniformly from [1, max_new] (seeded): ended "
+                         "sequences leave the batch; tokens/s then counts the tokens up to and including each EOS")
     ap.add_argument("--k", type=int, default=0, help="override the workload's samples per prompt")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -90,8 +93,18 @@ def main():
     out = (torch.empty((B, k, T), dtype=torch.int32, device="cuda"),
            torch.empty((B, k, T), dtype=torch.float32, device="cuda"))
 
+    d_forced, real_tokens = None, S * T
+    if args.eos_mix:
+        eos = 0
+        ends = np.random.default_rng(4000 + args.config).integers(1, T + 1, size=(B, k))     # completion lengths
+        forced = np.full((B, k, T), -1, np.int32)
+        np.put_along_axis(forced, (ends - 1)[..., None], eos, axis=2)
+        d_forced = torch.from_numpy(forced).cuda()
+        real_tokens = int(ends.sum())
+        R.rlgen_set_eos(pol, eos)
+
     def step():
-        R.rlgen_generate(pol, d_arr, lens, k, T, w.temperature, d_u, None, out)
+        R.rlgen_generate(pol, d_arr, lens, k, T, w.temperature, d_u, d_forced, out)
 
     if args.copy_probe:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
@@ -120,7 +133,7 @@ def main():
     assert ((toks >= 0) & (toks < m.vocab)).all()
 
     ms_per_step = 1e3 * elapsed / args.steps
-    tokens_per_s = S * T / (elapsed / args.steps)
+    tokens_per_s = real_tokens / (elapsed / args.steps)
 
     # ---- roofline of the dominant kernel: decode attention.  Algorithmic bytes of one launch (one layer, one
     # decode step t): every sequence reads its K and V streams of ctx = prompt_len + t keys (bf16), plus q in
@@ -130,10 +143,16 @@ def main():
     qo = 2 * 2 * S * m.n_q_heads * m.head_dim
     # with a shared prompt cache a launch reads each prompt's keys once, and t new keys per sequence
     keys = (lambda t: int(lens.astype(np.int64).sum()) + S * t) if share else (lambda t: int((seq_len + t).sum()))
+    if args.eos_mix:        # a sequence whose completion ended before step t is skipped by the attention launch of step t
+        live = lambda t: (ends.reshape(-1) > t)
+        if share:
+            keys = lambda t: int((lens.astype(np.int64) * (ends > t).any(axis=1)).sum()) + int(live(t).sum()) * t
+        else:
+            keys = lambda t: int(((seq_len + t) * live(t)).sum())
     bytes_per_launch = np.mean([per_key * keys(t) + qo for t in range(1, T)]) if T > 1 else 0.0
     # A batch of >= 256 sequences decodes as two halves on two streams: every layer and step then has two attention
     # launches, each over half of the bytes, running beside the other half's linear layers.
-    halves = max(1, round(attn_launches * EVENT_EVERY / max(1, args.steps * m.n_layers * (T - 1))))
+    halves = max(1, round(attn_launches * EVENT_EVERY / max(1, args.steps * m.n_layers * (T - 1)))) if not args.eos_mix else 1
     bytes_per_launch /= halves
 
     def roofline_of(ms, launches, extra):
@@ -159,7 +178,7 @@ def main():
         "ms_per_step": round(ms_per_step, 2), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": w.name, "prompts": B, "k": k, "max_new": T, "prompt_len": [w.prompt_len_lo, w.prompt_len_hi],
-                   "temperature": w.temperature, "generated_tokens_per_step": S * T,
+                   "temperature": w.temperature, "generated_tokens_per_step": real_tokens,
                    "kv_layout": "prompt cache shared by the k samples" if share else "one contiguous cache per sequence",
                    "storage": "bf16 weights (held as fp16, exact) and bf16 KV cache; fp16 MFMA inputs, fp32 accumulation"},
         "prefill_ms": round(float(np.mean(prefill_ms)), 2), "decode_ms": round(float(np.mean(decode_ms)), 2),
