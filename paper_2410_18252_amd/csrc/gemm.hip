@@ -1,11 +1,12 @@
 // fp16 x fp16 -> fp32 GEMM on the gfx950 matrix cores, C[M,N] = A[M,K] . W[N,K]^T, with the
 // epilogues the decoder needs fused in.  (Weights are the caller's bf16 values held in fp16, which
 // represents them exactly; activations are fp16, whose 11 significant bits keep the logits within
-// the parity bound where bf16 activations do not.)  Both operands are K-block major (see kblk_off), so a block's
-// tile is one contiguous run in memory and every MFMA operand fragment is one 16-byte LDS read.  256 threads = 4 waves in a 2x2 arrangement; each wave owns a
-// (BM/2)x(BN/2) sub-tile built from 32x32x16 MFMAs; A and W tiles of depth 64 are staged through
-// LDS (16-byte chunks, XOR-swizzled by row so that fragment reads spread over all banks) with
-// register prefetch of the next tile and one barrier per K step.
+// the parity bound where bf16 activations do not.)  Both operands are K-block major (see kblk_off), so a
+// block's tile is one contiguous run in memory and every MFMA operand fragment is one 16-byte LDS read.
+// A block of WM x WN waves owns a BM x BN tile; each wave a (BM/WM) x (BN/WN) sub-tile built from 32x32x16
+// MFMAs.  A and W tiles of depth 64 go from global memory straight into LDS (16-byte chunks, XOR-swizzled by
+// row so that fragment reads spread over all banks), two or four stages deep, with one barrier per K step;
+// a K that is not a multiple of 64 takes the older path through registers, which can zero-fill the tail.
 #include "kernels.h"
 #include <algorithm>
 

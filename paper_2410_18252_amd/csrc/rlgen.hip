@@ -1,7 +1,7 @@
 // Host side of librlgen.so: configuration checks, workspace carving, weight packing and the
 // scheduler that turns rlgen_generate / rlgen_score into kernel launches on the caller's stream.
-// No device memory is allocated here; the only host allocations are the context and one pinned
-// staging buffer for per-call sequence metadata.
+// No device memory is allocated here; the host allocations are the context, two pinned buffers (per-call
+// sequence metadata; the flags and index lists of EOS compaction), two internal streams and a few events.
 #include "../../include/rlgen.h"
 #include "kernels.h"
 
