@@ -24,6 +24,9 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per decode-attention launch over its algorithmic bytes on workload 4, measured with rocprofv3
 # FETCH_SIZE + WRITE_SIZE, each scaled by its reading for a plain 1 GiB copy (profiles/attention_decode_c4_hbm_traffic.txt).
 TRAFFIC_OVER_ALGORITHMIC = 1.039
+# The same for every kernel of the decode phase together, two-stream decode (profiles/decode_phase_c4_hbm_traffic.txt):
+# weights are read once per half batch, whole super-blocks are loaded, activations and partial sums pass through HBM.
+DECODE_TRAFFIC_OVER_ALGORITHMIC = 1.192
 
 
 # every EVENT_EVERY-th decode-attention launch of the timed region is bracketed with HIP events (each bracket costs
@@ -183,6 +186,9 @@ def main():
                    "storage": "bf16 weights (held as fp16, exact) and bf16 KV cache; fp16 MFMA inputs, fp32 accumulation"},
         "prefill_ms": round(float(np.mean(prefill_ms)), 2), "decode_ms": round(float(np.mean(decode_ms)), 2),
         "decode_algorithmic_GBps": round(decode_gbs, 1), "decode_frac_of_hbm_peak": round(decode_gbs / HBM_PEAK_GBS, 4),
+        # HBM bytes actually moved over the decode time, from the counter-measured ratio above (headline layout only)
+        "decode_hbm_GBps": round(decode_gbs * DECODE_TRAFFIC_OVER_ALGORITHMIC, 1)
+        if args.config == 4 and halves > 1 and not share and not args.k and not args.eos_mix else None,
         "setup_s": round(setup_s, 1),
         "roofline": roofline,
     }
