@@ -56,6 +56,8 @@ def main():
     ap.add_argument("--eos-mix", action="store_true",
                     help="completions end at an EOS token forced at a step drawn uniformly from [1, max_new] (seeded): ended "
                          "sequences leave the batch; tokens/s then counts the tokens up to and including each EOS")
+    ap.add_argument("--no-score", action="store_true",
+                    help="workload 4 ends with rlgen_score over the generated sequences; this leaves it out of the step")
     ap.add_argument("--k", type=int, default=0, help="override the workload's samples per prompt")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -106,8 +108,30 @@ def main():
         real_tokens = int(ends.sum())
         R.rlgen_set_eos(pol, eos)
 
-    def step():
+    # Workload 4 is "generate, then rlgen_score on the resulting sequences": the sequences (prompt + completion) are
+    # assembled on the device by one scatter of the generated tokens into a buffer that already holds the prompts.
+    with_score = args.config == 4 and not args.no_score and not args.eos_mix
+    if with_score:
+        seq_lens = np.repeat(lens, k).astype(np.int32) + T
+        stride = int(lens.max()) + T
+        h_full = np.full((S, stride), -1, np.int32)
+        for b in range(B):
+            h_full[b * k:(b + 1) * k, :lens[b]] = arr[b, :lens[b]]
+        d_full = torch.from_numpy(h_full).cuda()
+        d_pos = (torch.from_numpy(np.repeat(lens, k).astype(np.int64)).cuda()[:, None] + torch.arange(T, device="cuda")[None, :])
+        score_from = np.repeat(lens, k).astype(np.int32)
+        d_score = torch.empty((S, stride), dtype=torch.float32, device="cuda")
+    score_ms = []
+
+    def step(timed=False):
         R.rlgen_generate(pol, d_arr, lens, k, T, w.temperature, d_u, d_forced, out)
+        tm = R.rlgen_get_timings(pol) if timed else None          # waits for the generation's events only
+        if with_score:
+            d_full.scatter_(1, d_pos, out[0].view(S, T))
+            R.rlgen_score(pol, d_full, seq_lens, w.temperature, score_from, d_score)
+            if timed:
+                score_ms.append(R.rlgen_get_timings(pol)["prefill_ms"])
+        return tm
 
     if args.copy_probe:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
@@ -124,8 +148,7 @@ def main():
     prefill_ms, decode_ms, attn_ms, attn_launches = [], [], 0.0, 0
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
-        tm = R.rlgen_get_timings(pol)        # waits for this step's events only
+        tm = step(timed=True)
         prefill_ms.append(tm["prefill_ms"]); decode_ms.append(tm["decode_ms"])
         attn_ms += tm["decode_attn_ms"]; attn_launches += tm["decode_attn_launches"]
     torch.cuda.synchronize()
@@ -182,9 +205,12 @@ def main():
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": w.name, "prompts": B, "k": k, "max_new": T, "prompt_len": [w.prompt_len_lo, w.prompt_len_hi],
                    "temperature": w.temperature, "generated_tokens_per_step": real_tokens,
+                   "step": "rlgen_generate, then rlgen_score over the generated sequences" if with_score else "rlgen_generate",
                    "kv_layout": "prompt cache shared by the k samples" if share else "one contiguous cache per sequence",
                    "storage": "bf16 weights (held as fp16, exact) and bf16 KV cache; fp16 MFMA inputs, fp32 accumulation"},
         "prefill_ms": round(float(np.mean(prefill_ms)), 2), "decode_ms": round(float(np.mean(decode_ms)), 2),
+        "score_ms": round(float(np.mean(score_ms)), 2) if score_ms else None,
+        "generate_only_tokens_per_s": round(real_tokens / (1e-3 * float(np.mean(prefill_ms) + np.mean(decode_ms))), 1),
         "decode_algorithmic_GBps": round(decode_gbs, 1), "decode_frac_of_hbm_peak": round(decode_gbs / HBM_PEAK_GBS, 4),
         # HBM bytes actually moved over the decode time, from the counter-measured ratio above (headline layout only)
         "decode_hbm_GBps": round(decode_gbs * DECODE_TRAFFIC_OVER_ALGORITHMIC, 1)
@@ -197,7 +223,7 @@ def main():
         # switched off, so that a launch covers the whole batch and runs alone
         R.rlgen_set_decode_split(pol, False)
         R.rlgen_set_profiling(pol, EVENT_EVERY)
-        step()
+        R.rlgen_generate(pol, d_arr, lens, k, T, w.temperature, d_u, d_forced, out)
         tm = R.rlgen_get_timings(pol)
         R.rlgen_set_profiling(pol, 0)
         R.rlgen_set_decode_split(pol, True)
