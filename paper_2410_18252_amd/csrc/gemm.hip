@@ -212,6 +212,55 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f16_kernel(GemmArgs g) {
         __builtin_amdgcn_global_load_lds((gptr_t)(qb[i] + kt * kw), (lptr_t)(la + (BM + i * RPP) * BK), 16, 0, 0);
     };
     constexpr int L = PA + PB;                      // loads per wave and stage
+    if constexpr (NS == 2) {
+      // Skewed by a quarter of a K step: the wait for the next stage and the barrier sit before the last of the four
+      // MFMA groups of a stage, whose fragments are in registers by then.  Behind the barrier nobody reads this
+      // stage's LDS any more, so its buffer is refilled at once, and the first fragments of the next stage are
+      // fetched while the last MFMA group runs: the matrix pipe does not drain at the stage boundary.
+      f16x8 fa[2][TM], fb[2][TN];
+      auto frags = [&](int buf, int kk, int slot) {
+        const uint16_t* la = lds + buf * STAGE + (wm * (BM / WM)) * BK;
+        const uint16_t* lb = lds + buf * STAGE + BM * BK + (wn * (BN / WN)) * BK;
+        const int chunk = kk * 2 + fhalf;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+          int r = i * 32 + frow;
+          fa[slot][i] = *(const f16x8*)(la + r * BK + ((chunk ^ swz(r)) * 8));
+        }
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          int r = j * 32 + frow;
+          fb[slot][j] = *(const f16x8*)(lb + r * BK + ((chunk ^ swz(r)) * 8));
+        }
+      };
+      auto mma = [&](int slot) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[slot][j], fa[slot][i], acc[i][j], 0, 0, 0);
+      };
+      issue(kt0, 0);
+      wait_loads_then_barrier<0>();
+      if (kt0 + 1 < nk) issue(kt0 + 1, 1);
+      frags(0, 0, 0);
+      for (int kt = kt0; kt < nk; ++kt) {
+        const int buf = (kt - kt0) & 1;
+        frags(buf, 1, 1);
+        mma(0);
+        frags(buf, 2, 0);
+        mma(1);
+        frags(buf, 3, 1);
+        mma(0);
+        if (kt + 1 < nk) {
+          // stage kt + 1 has landed, and every wave holds its last fragments of stage kt in registers
+          asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+          if (kt + 2 < nk) issue(kt + 2, buf);
+          frags(buf ^ 1, 0, 0);
+        }
+        mma(1);
+      }
+    } else {
 #pragma unroll
     for (int s = 0; s < NS - 1; ++s)
       if (kt0 + s < nk) issue(kt0 + s, s);
@@ -224,6 +273,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f16_kernel(GemmArgs g) {
       // every wave has left stage kt - 1: its buffer takes stage kt + NS - 1
       if (kt + NS - 1 < nk) issue(kt + NS - 1, (kt - kt0 + NS - 1) % NS);
       k_step((kt - kt0) % NS, [] {});
+    }
     }
   }
 

@@ -545,7 +545,7 @@ int tune_gemms(rlgen_ctx* c, hipStream_t st) {
       std::vector<Cand> cands = {{0, 1}, {3, 1}, {5, 1}};
       if (!wide_only) {
         cands.push_back({7, 1});
-        if (g.K % 64 == 0 && g.K >= 2048) cands.push_back({8, 1});     // deeper load pipeline: pays on a long K with few tiles
+        if (g.K % 64 == 0 && g.K >= 2048 && g.M <= 2048) cands.push_back({8, 1});     // deeper load pipeline: pays on a long K with few tiles
         const long long t7 = (long long)((g.M + 63) / 64) * ((g.N + 127) / 128);
         if (g.ws && t7 <= 1024 && epi != EPI_QKV)
           for (int sp : {2, 3, 4, 6, 8})
