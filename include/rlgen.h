@@ -48,6 +48,13 @@ extern "C" {
 #define RLGEN_DTYPE_F32   0  /* tensors supplied as fp32; rounded to bf16 (nearest even) on load */
 #define RLGEN_DTYPE_BF16  1  /* tensors supplied as bf16                                          */
 
+/* Threads: calls on one context must not overlap; different contexts may be used from different
+ * threads.  Environment variables read at rlgen_create (testing and measurement knobs, not needed
+ * in normal use): RLGEN_DEBUG_TUNE=1 prints the GEMM tile-shape timings; RLGEN_NO_DECODE_SPLIT=1
+ * keeps every decode on the caller's stream; RLGEN_DECODE_SPLIT_MIN=n replaces the 256-sequence
+ * threshold of the two-stream decode (and its cache-traffic criterion); RLGEN_EOS_COMPACT_EVERY=n
+ * replaces the 8-step interval at which ended sequences leave the batch (0: never);
+ * RLGEN_UNFUSED_QKV=1 selects the separate rotary kernel instead of the fused QKV epilogue. */
 typedef struct rlgen_ctx rlgen_ctx; /* opaque */
 
 typedef struct {

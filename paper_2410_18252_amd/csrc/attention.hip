@@ -34,8 +34,11 @@
 
 namespace {
 
-template <int HD, bool DECODE>
+// QB = query blocks of 16 columns a wave carries through one pass over the keys (prompt pass only: two blocks halve
+// the key / value traffic per query; a.jobs then counts blocks of 16 QB tokens).
+template <int HD, bool DECODE, int QB = 1>
 __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a) {
+  static_assert(!DECODE || QB == 1, "decode has one query block");
   constexpr int NCH = HD / 8;            // 16-byte chunks per key row
   constexpr int KSTEPS = (HD + 31) / 32; // MFMA steps over head_dim for the scores
   constexpr int VT = HD / 16;            // 16-row tiles of V^T / O^T
@@ -46,10 +49,10 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a) {
 
   // A job streams one or more segments.  Segment i is the stream of cache sequence seg_seq(i) with seg_len(i)
   // keys; column c takes part in it if seg_col(i) < 0 or seg_col(i) == c / G (its sample).
-  int kvh, qrow, qhead, qpos, nseg;
+  int kvh, qrow[QB], qhead, qpos[QB], nseg;
   int seq0, len0;           // first segment
   int sfx_seq0 = 0, sfx_len = 0;   // shared-prompt decode: segments 1.. are the samples' own suffix streams
-  bool store_col;
+  bool store_col[QB];
   if constexpr (DECODE) {
     const int units = a.share_k ? a.S / a.share_k : a.S;       // prompts or sequences
     if (job >= units * Hkv) return;
@@ -65,65 +68,78 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a) {
         for (int jj = 0; jj < a.share_k; ++jj) live |= a.finished[u * a.share_k + jj] == 0;
         if (!live) return;
       }
-      qrow = u * a.share_k + j;
+      qrow[0] = u * a.share_k + j;
       seq0 = u;
       len0 = a.ctx_base[u * a.share_k];
       sfx_seq0 = a.sfx_first + u * a.share_k;
       sfx_len = a.ctx_add;
       nseg = 1 + a.share_k;
-      store_col = c < G * a.share_k;
+      store_col[0] = c < G * a.share_k;
     } else {
       if (a.finished && a.finished[u]) return;      // an ended completion's output is never used: do not stream its cache
-      qrow = u;
+      qrow[0] = u;
       seq0 = a.cache_seq_of ? a.cache_seq_of[u] : u;       // rows of a compacted batch name their cache sequence
       len0 = a.ctx_base[u] + a.ctx_add;
       nseg = 1;
-      store_col = c < G;
+      store_col[0] = c < G;
     }
     qhead = kvh * G + (c % G);
-    qpos = 0x7fffffff;      // a decode query sees every key of its segments
+    qpos[0] = 0x7fffffff;      // a decode query sees every key of its segments
   } else {
-    if (job >= a.njobs * a.Hq) return;
-    const AttnJob jb = a.jobs[job / a.Hq];
+    // a.jobs lists blocks of 16 tokens, QB consecutive ones (of one sequence, the first a multiple of QB) per wave
+    if (job >= a.njobs / QB * a.Hq) return;
+    AttnJob jb = a.jobs[job / a.Hq * QB];
+    jb.qblock /= QB;
     qhead = job % a.Hq;
     kvh = qhead / G;
     seq0 = jb.cache_seq;
-    const int tok = jb.qblock * 16 + c;
-    store_col = tok < jb.len;
-    qpos = min(tok, jb.len - 1);
-    qrow = jb.row0 + qpos;
-    len0 = min(jb.qblock * 16 + 16, jb.len);
+#pragma unroll
+    for (int b = 0; b < QB; ++b) {
+      const int tok = (jb.qblock * QB + b) * 16 + c;
+      store_col[b] = tok < jb.len;
+      qpos[b] = min(tok, jb.len - 1);
+      qrow[b] = jb.row0 + qpos[b];
+    }
+    len0 = min((jb.qblock + 1) * 16 * QB, jb.len);      // keys the last query of the job sees
     nseg = 1;
   }
 
   // query fragments (B operand): lane (c, g) holds q[col c][32 i + 8 g .. + 7]
-  f16x8 qf[KSTEPS];
-  {
-    const uint16_t* qp = a.q + (size_t)qrow * a.q_ld + qhead * HD;
+  f16x8 qf[QB][KSTEPS];
+#pragma unroll
+  for (int b = 0; b < QB; ++b) {
+    const uint16_t* qp = a.q + (size_t)qrow[b] * a.q_ld + qhead * HD;
 #pragma unroll
     for (int i = 0; i < KSTEPS; ++i) {
       const int d0 = 32 * i + 8 * g;
-      if (d0 < HD) qf[i] = *(const f16x8*)(qp + d0);
+      if (d0 < HD) qf[b][i] = *(const f16x8*)(qp + d0);
       else
 #pragma unroll
-        for (int e = 0; e < 8; ++e) qf[i][e] = (f16_t)0.f;
+        for (int e = 0; e < 8; ++e) qf[b][i][e] = (f16_t)0.f;
     }
   }
 
-  f32x4 o[VT];
+  f32x4 o[QB][VT];
+  float m[QB], lsum[QB];
 #pragma unroll
-  for (int t = 0; t < VT; ++t) o[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-  float m = -INFINITY, lsum = 0.f;
+  for (int b = 0; b < QB; ++b) {
+#pragma unroll
+    for (int t = 0; t < VT; ++t) o[b][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    m[b] = -INFINITY;
+    lsum[b] = 0.f;
+  }
 
   for (int seg = 0; seg < nseg; ++seg) {
-    if (seg > 0 && a.finished && a.finished[qrow - (c / G) % a.share_k + seg - 1]) continue;     // ended sample: skip its stream
+    if (seg > 0 && a.finished && a.finished[qrow[0] - (c / G) % a.share_k + seg - 1]) continue;     // ended sample: skip its stream
     const int cache_seq = seg == 0 ? seq0 : sfx_seq0 + seg - 1;
     const int nkeys = seg == 0 ? len0 : sfx_len;
     const bool mine = seg == 0 || (c / G) % a.share_k == seg - 1;     // does column c attend to this segment
     const int cap = a.kv_cap[cache_seq];
     const long long off = a.kv_off[cache_seq];
     const uint16_t* __restrict__ st = a.kv + a.lay.stream(off, cap, kvh);
-    const int klimit = mine ? min(nkeys - 1, qpos) : -1;               // last visible key index for this column
+    int klimit[QB];                                                     // last visible key index for this column
+#pragma unroll
+    for (int b = 0; b < QB; ++b) klimit[b] = mine ? min(nkeys - 1, qpos[b]) : -1;
 
   const int nsb = (nkeys + 31) >> 5;
   // the whole next super-block (32 keys, 32 values) is requested before the current one is consumed
@@ -152,46 +168,58 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a) {
     load_sb(sb, kraw, vraw);
 #endif
 
-    f32x4 sc[2];
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      sc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int i = 0; i < KSTEPS; ++i)
-        sc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(bf16x8_to_f16x8(kraw[t][i]), qf[i], sc[t], 0, 0, 0);
-    }
-    // lane (c, g) now holds the scores of keys 32 sb + 8 g + 4 t + j against column c
-    float p[8];
-    float bmax = -INFINITY;
+    // the super-block's operands are widened once and serve every query block
+    f16x8 kf[2][KSTEPS], vf[VT];
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int key = sb * 32 + 8 * g + 4 * t + j;
-        const float v = key <= klimit ? sc[t][j] * a.scale : -INFINITY;
-        p[4 * t + j] = v;
-        bmax = fmaxf(bmax, v);
+      for (int i = 0; i < KSTEPS; ++i) kf[t][i] = bf16x8_to_f16x8(kraw[t][i]);
+#pragma unroll
+    for (int t = 0; t < VT; ++t) vf[t] = bf16x8_to_f16x8(vraw[t]);
+#pragma unroll
+    for (int b = 0; b < QB; ++b) {
+      if (QB > 1 && __all(sb * 32 > klimit[b])) continue;    // wholly behind this block's causal limit
+      f32x4 sc[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        sc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < KSTEPS; ++i)
+          sc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[t][i], qf[b][i], sc[t], 0, 0, 0);
       }
-    bmax = fmaxf(bmax, __shfl_xor(bmax, 16, WAVE));
-    bmax = fmaxf(bmax, __shfl_xor(bmax, 32, WAVE));
-    const float mnew = fmaxf(m, bmax);
-    // a column that has seen no key yet (m and mnew both -inf) keeps alpha = 1 and p = 0
-    const float alpha = mnew == -INFINITY ? 1.f : __expf(m - mnew);
-    m = mnew;
-    float psum = 0.f;
+      // lane (c, g) now holds the scores of keys 32 sb + 8 g + 4 t + j against column c
+      float p[8];
+      float bmax = -INFINITY;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      p[e] = mnew == -INFINITY ? 0.f : __expf(p[e] - mnew);
-      psum += p[e];
-    }
-    lsum = lsum * alpha + psum;
-    f16x8 pf;
+      for (int t = 0; t < 2; ++t)
 #pragma unroll
-    for (int e = 0; e < 8; ++e) pf[e] = (f16_t)p[e];
+        for (int j = 0; j < 4; ++j) {
+          const int key = sb * 32 + 8 * g + 4 * t + j;
+          const float v = key <= klimit[b] ? sc[t][j] * a.scale : -INFINITY;
+          p[4 * t + j] = v;
+          bmax = fmaxf(bmax, v);
+        }
+      bmax = fmaxf(bmax, __shfl_xor(bmax, 16, WAVE));
+      bmax = fmaxf(bmax, __shfl_xor(bmax, 32, WAVE));
+      const float mnew = fmaxf(m[b], bmax);
+      // a column that has seen no key yet (m and mnew both -inf) keeps alpha = 1 and p = 0
+      const float alpha = mnew == -INFINITY ? 1.f : __expf(m[b] - mnew);
+      m[b] = mnew;
+      float psum = 0.f;
 #pragma unroll
-    for (int t = 0; t < VT; ++t) {
-      o[t] *= alpha;
-      o[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(bf16x8_to_f16x8(vraw[t]), pf, o[t], 0, 0, 0);
+      for (int e = 0; e < 8; ++e) {
+        p[e] = mnew == -INFINITY ? 0.f : __expf(p[e] - mnew);
+        psum += p[e];
+      }
+      lsum[b] = lsum[b] * alpha + psum;
+      f16x8 pf;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) pf[e] = (f16_t)p[e];
+#pragma unroll
+      for (int t = 0; t < VT; ++t) {
+        o[b][t] *= alpha;
+        o[b][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vf[t], pf, o[b][t], 0, 0, 0);
+      }
     }
 #if ATTN_PREFETCH
 #pragma unroll
@@ -203,26 +231,30 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a) {
 #endif
   }
   }   // segments
-  lsum += __shfl_xor(lsum, 16, WAVE);
-  lsum += __shfl_xor(lsum, 32, WAVE);
-  const float inv = 1.0f / lsum;
-  if (store_col) {
 #pragma unroll
-    for (int t = 0; t < VT; ++t) {
-      u32x2 w;
-      w[0] = pack_f16x2(o[t][0] * inv, o[t][1] * inv);
-      w[1] = pack_f16x2(o[t][2] * inv, o[t][3] * inv);
-      *(u32x2*)(a.out + kblk_off(qrow, qhead * HD + 16 * t + 4 * g, a.out_rows)) = w;
+  for (int b = 0; b < QB; ++b) {
+    float ls = lsum[b];
+    ls += __shfl_xor(ls, 16, WAVE);
+    ls += __shfl_xor(ls, 32, WAVE);
+    const float inv = 1.0f / ls;
+    if (store_col[b]) {
+#pragma unroll
+      for (int t = 0; t < VT; ++t) {
+        u32x2 w;
+        w[0] = pack_f16x2(o[b][t][0] * inv, o[b][t][1] * inv);
+        w[1] = pack_f16x2(o[b][t][2] * inv, o[b][t][3] * inv);
+        *(u32x2*)(a.out + kblk_off(qrow[b], qhead * HD + 16 * t + 4 * g, a.out_rows)) = w;
+      }
     }
   }
 }
 
-template <bool DECODE>
+template <bool DECODE, int QB>
 hipError_t dispatch(const AttnArgs& a, int jobs, hipStream_t s) {
   if (jobs <= 0) return hipSuccess;
   dim3 grid((jobs + 3) / 4), block(256);
   switch (a.lay.h) {
-#define CASE(H) case H: hipLaunchKernelGGL((attention_kernel<H, DECODE>), grid, block, 0, s, a); break;
+#define CASE(H) case H: hipLaunchKernelGGL((attention_kernel<H, DECODE, (QB > 1 && H > 80) ? 1 : QB>), grid, block, 0, s, a); break;
     CASE(16) CASE(32) CASE(48) CASE(64) CASE(80) CASE(96) CASE(112) CASE(128) CASE(256)
 #undef CASE
     default: return hipErrorInvalidValue;
@@ -234,6 +266,13 @@ hipError_t dispatch(const AttnArgs& a, int jobs, hipStream_t s) {
 
 hipError_t rl_attention_decode(const AttnArgs& a, hipStream_t s) {
   if (a.share_k && (a.S % a.share_k != 0 || a.share_k * (a.Hq / a.lay.Hkv) > 16)) return hipErrorInvalidValue;
-  return dispatch<true>(a, (a.share_k ? a.S / a.share_k : a.S) * a.lay.Hkv, s);
+  return dispatch<true, 1>(a, (a.share_k ? a.S / a.share_k : a.S) * a.lay.Hkv, s);
 }
-hipError_t rl_attention_prefill(const AttnArgs& a, hipStream_t s) { return dispatch<false>(a, a.njobs * a.Hq, s); }
+// a.jobs: 16-token blocks; every sequence must contribute a multiple of rl_attention_prefill_qb(h) of them (blocks
+// past its end are allowed), since a wave takes that many consecutive blocks
+int rl_attention_prefill_qb(int h) { return h <= 80 ? 2 : 1; }
+hipError_t rl_attention_prefill(const AttnArgs& a, hipStream_t s) {
+  const int qb = rl_attention_prefill_qb(a.lay.h);
+  if (a.njobs % qb != 0) return hipErrorInvalidValue;
+  return dispatch<false, 2>(a, a.njobs / qb * a.Hq, s);
+}

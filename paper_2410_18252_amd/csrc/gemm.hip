@@ -461,7 +461,11 @@ template <int BM, int BN, int WM, int WN, int EPI, bool KTAIL, int NS = 0>
 hipError_t launch_k(const GemmArgs& g, hipStream_t s) {
   constexpr size_t lds_bytes = (NS ? NS : 2) * (size_t)(BM + BN) * BK * sizeof(uint16_t);
   static_assert(lds_bytes <= 160 * 1024, "LDS of one CU");
-  static bool configured = false;
+  // once per device and instantiation (a repeated call is harmless, so no lock)
+  static bool configured_on[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  bool& configured = configured_on[dev];
   if (!configured) {
     if (lds_bytes > 65536) {
       hipError_t e = hipFuncSetAttribute((const void*)gemm_f16_kernel<BM, BN, WM, WN, EPI, KTAIL, NS>,

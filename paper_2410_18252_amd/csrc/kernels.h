@@ -108,6 +108,8 @@ struct AttnArgs {
 };
 hipError_t rl_attention_decode(const AttnArgs& a, hipStream_t s);
 hipError_t rl_attention_prefill(const AttnArgs& a, hipStream_t s);
+// 16-token blocks a prompt-pass attention wave takes at once for head size h; a.jobs must list a multiple of it per sequence
+int rl_attention_prefill_qb(int h);
 
 // ------------------------------------------------------------------ element-wise and small kernels
 // dst bf16 <- src (fp32 rounded to nearest even, or bf16 copied); n elements

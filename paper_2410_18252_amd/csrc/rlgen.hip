@@ -188,7 +188,7 @@ size_t carve(rlgen_ctx* c, char* base) {
   c->d_cmp = k.take<int>(base, 8 * S); c->d_lists = k.take<int>(base, 3 * S);
   c->d_tok_index = k.take<int>(base, R); c->d_pos = k.take<int>(base, R); c->d_dst_seq = k.take<int>(base, R);
   c->d_lm_row = k.take<int>(base, R); c->d_target = k.take<int>(base, R); c->d_out_index = k.take<int>(base, R);
-  c->d_jobs = k.take<AttnJob>(base, R / 16 + S + 1);
+  c->d_jobs = k.take<AttnJob>(base, R / 16 + 2 * S + 2);
   c->Sg = (2 * m.max_seqs + 2) / 3 + 1;        // the larger half: ceil(B / 2) prompts of B >= 2, k samples each
   for (int i = 0; i < 3; ++i) {
     const size_t rows = i == 0 ? R : (size_t)c->Sg, lm = i == 0 ? LM : (size_t)c->Sg;
@@ -262,14 +262,15 @@ int pack_weights(rlgen_ctx* c, const rlgen_weights* w, hipStream_t st) {
 
 // Expands per-sequence metadata into the per-row arrays the kernels index.  One block per sequence.
 __global__ void expand_kernel(const SeqMeta* meta, int first, const int* tokens, int* tok_index, int* pos, int* dst_seq,
-                              AttnJob* jobs, int* lm_row, int* target, int* out_index, int scoring) {
+                              AttnJob* jobs, int* lm_row, int* target, int* out_index, int scoring, int job_mult) {
   const SeqMeta m = meta[first + blockIdx.x];
   for (int p = threadIdx.x; p < m.len; p += blockDim.x) {
     tok_index[m.row0 + p] = m.src_off + p;
     pos[m.row0 + p] = p;
     dst_seq[m.row0 + p] = m.cache_seq;
   }
-  const int nj = (m.len + 15) >> 4;
+  // 16-token blocks, their count rounded up to a multiple of job_mult (the blocks past the end do nothing)
+  const int nj = (m.len + 16 * job_mult - 1) / (16 * job_mult) * job_mult;
   for (int j = threadIdx.x; j < nj; j += blockDim.x) jobs[m.job0 + j] = AttnJob{m.cache_seq, m.row0, m.len, j};
   if (scoring) {
     for (int t = m.score_from + threadIdx.x; t < m.len; t += blockDim.x) {
@@ -322,6 +323,11 @@ __global__ void clamp_targets_kernel(int* target, int n, int vocab, unsigned* st
 }
 
 struct Chunk { int first, count, rows, jobs, lm_rows; };
+// 16-token blocks of a sequence of `len` tokens in the job list: rounded up to what one attention wave takes
+int jobs_of(const rlgen_ctx* c, int len) {
+  const int per = 16 * rl_attention_prefill_qb(c->cfg.head_dim);
+  return (len + per - 1) / per * (per / 16);
+}
 
 enum { G_QKV = 0, G_O = 1, G_UP = 2, G_DOWN = 3, G_LMHEAD = 4 };
 
@@ -631,7 +637,8 @@ int stage_upload(rlgen_ctx* c, const Staged& s, int nmeta, int nseq, int nstream
 
 int expand(rlgen_ctx* c, const Chunk& ch, const int* tokens, bool scoring, hipStream_t st) {
   hipLaunchKernelGGL(expand_kernel, dim3(ch.count), dim3(256), 0, st, c->d_meta, ch.first, tokens, c->d_tok_index, c->d_pos,
-                     c->d_dst_seq, c->d_jobs, c->d_lm_row, c->d_target, c->d_out_index, scoring ? 1 : 0);
+                     c->d_dst_seq, c->d_jobs, c->d_lm_row, c->d_target, c->d_out_index, scoring ? 1 : 0,
+                     rl_attention_prefill_qb(c->cfg.head_dim));
   HIPCHK(hipGetLastError());
   return RLGEN_OK;
 }
@@ -669,7 +676,7 @@ int score_impl(rlgen_ctx* c, const int32_t* seqs, const int32_t* seq_lens, const
     s.kv_off[n] = (int)kvtok; s.kv_cap[n] = round32(len);
     s.ctx_base[n] = len; s.iota[n] = n; s.lastrow[n] = cur.rows + len - 1; s.order[n] = n;
     kvtok += round32(len);
-    cur.count++; cur.rows += len; cur.jobs += (len + 15) / 16; cur.lm_rows += nlm;
+    cur.count++; cur.rows += len; cur.jobs += jobs_of(c, len); cur.lm_rows += nlm;
   }
   chunks.push_back(cur);
   rc = stage_upload(c, s, N, N, N, st);
@@ -846,7 +853,7 @@ int rlgen_generate(rlgen_ctx* c, const int32_t* prompts, const int32_t* prompt_l
         off += round32(len + max_new);
       }
     }
-    cur.count++; cur.rows += len; cur.jobs += (len + 15) / 16;
+    cur.count++; cur.rows += len; cur.jobs += jobs_of(c, len);
   }
   chunks.push_back(cur);
   if (share)
