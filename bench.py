@@ -58,6 +58,8 @@ def main():
                          "sequences leave the batch; tokens/s then counts the tokens up to and including each EOS")
     ap.add_argument("--no-score", action="store_true",
                     help="workload 4 ends with rlgen_score over the generated sequences; this leaves it out of the step")
+    ap.add_argument("--score-plain", action="store_true",
+                    help="score every generated sequence on its own instead of a prompt once with its k completions")
     ap.add_argument("--k", type=int, default=0, help="override the workload's samples per prompt")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -121,6 +123,9 @@ def main():
         d_pos = (torch.from_numpy(np.repeat(lens, k).astype(np.int64)).cuda()[:, None] + torch.arange(T, device="cuda")[None, :])
         score_from = np.repeat(lens, k).astype(np.int32)
         d_score = torch.empty((S, stride), dtype=torch.float32, device="cuda")
+        if not args.score_plain:
+            # the sequences are a prompt with its k completions each: the library runs the prompt once per group
+            R.rlgen_set_score_groups(pol, k)
     score_ms = []
 
     def step(timed=False):
@@ -205,7 +210,8 @@ def main():
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": w.name, "prompts": B, "k": k, "max_new": T, "prompt_len": [w.prompt_len_lo, w.prompt_len_hi],
                    "temperature": w.temperature, "generated_tokens_per_step": real_tokens,
-                   "step": "rlgen_generate, then rlgen_score over the generated sequences" if with_score else "rlgen_generate",
+                   "step": ("rlgen_generate, then rlgen_score over the generated sequences"
+                            + ("" if args.score_plain else f" (groups of {k} sharing their prompt)")) if with_score else "rlgen_generate",
                    "kv_layout": "prompt cache shared by the k samples" if share else "one contiguous cache per sequence",
                    "storage": "bf16 weights (held as fp16, exact) and bf16 KV cache; fp16 MFMA inputs, fp32 accumulation"},
         "prefill_ms": round(float(np.mean(prefill_ms)), 2), "decode_ms": round(float(np.mean(decode_ms)), 2),

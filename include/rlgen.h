@@ -212,6 +212,19 @@ int rlgen_set_profiling(rlgen_ctx *ctx, int32_t on);
  * Errors: NULL, BAD_ARG (id outside [-1, vocab)). */
 int rlgen_set_eos(rlgen_ctx *ctx, int32_t eos_token);
 
+/* The sequences a learner scores come in groups: a prompt x and its k completions (the pair y+, y-
+ * of the DPO objective, Section 2.1; K = 4 in Section 4.2).  After rlgen_set_score_groups(ctx, k),
+ * k > 1, rlgen_score requires N to be a multiple of k, score_from non-null and equal within every
+ * group of k consecutive sequences (1 <= score_from <= seq_len), and takes the caller's word that
+ * the group's sequences agree in their first score_from tokens: that shared part then goes through
+ * the model once per group instead of once per sequence.  Outputs are the same as without grouping
+ * up to rounding order.  The agreement is checked on the device; a group that breaks it sets the
+ * sticky status (rlgen_status returns DEVICE) and its log-probs are meaningless.  k = 1 (the
+ * default) scores every sequence on its own.  A call falls back to scoring every sequence on its
+ * own when a group does not fit one chunk of max_batch_tokens rows, or when rotary_dim is not a
+ * multiple of 4.  Errors: NULL, BAD_ARG (k < 1). */
+int rlgen_set_score_groups(rlgen_ctx *ctx, int32_t k);
+
 /* rlgen_generate decodes a batch of 256 or more sequences as two halves on two internal streams
  * (forked from and joined to the call's stream), so that one half's cache-streaming attention runs
  * beside the other half's linear layers.  on = 0 turns that off for later calls on this context

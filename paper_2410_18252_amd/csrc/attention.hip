@@ -101,7 +101,9 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a) {
       qrow[b] = jb.row0 + qpos[b];
     }
     len0 = min((jb.qblock + 1) * 16 * QB, jb.len);      // keys the last query of the job sees
-    nseg = 1;
+    nseg = jb.pre_len > 0 ? 2 : 1;                      // a shared prefix is walked first
+    sfx_seq0 = jb.pre_seq;
+    sfx_len = jb.pre_len;
   }
 
   // query fragments (B operand): lane (c, g) holds q[col c][32 i + 8 g .. + 7]
@@ -131,15 +133,17 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a) {
 
   for (int seg = 0; seg < nseg; ++seg) {
     if (seg > 0 && a.finished && a.finished[qrow[0] - (c / G) % a.share_k + seg - 1]) continue;     // ended sample: skip its stream
-    const int cache_seq = seg == 0 ? seq0 : sfx_seq0 + seg - 1;
-    const int nkeys = seg == 0 ? len0 : sfx_len;
-    const bool mine = seg == 0 || (c / G) % a.share_k == seg - 1;     // does column c attend to this segment
+    // prompt pass with a shared prefix: segment 0 is the prefix (every key visible), segment 1 the sequence itself
+    const bool prefix_seg = !DECODE && nseg == 2 && seg == 0;
+    const int cache_seq = DECODE ? (seg == 0 ? seq0 : sfx_seq0 + seg - 1) : (prefix_seg ? sfx_seq0 : seq0);
+    const int nkeys = DECODE ? (seg == 0 ? len0 : sfx_len) : (prefix_seg ? sfx_len : len0);
+    const bool mine = !DECODE || seg == 0 || (c / G) % a.share_k == seg - 1;     // does column c attend to this segment
     const int cap = a.kv_cap[cache_seq];
     const long long off = a.kv_off[cache_seq];
     const uint16_t* __restrict__ st = a.kv + a.lay.stream(off, cap, kvh);
     int klimit[QB];                                                     // last visible key index for this column
 #pragma unroll
-    for (int b = 0; b < QB; ++b) klimit[b] = mine ? min(nkeys - 1, qpos[b]) : -1;
+    for (int b = 0; b < QB; ++b) klimit[b] = !mine ? -1 : prefix_seg ? nkeys - 1 : min(nkeys - 1, qpos[b]);
 
   const int nsb = (nkeys + 31) >> 5;
   // the whole next super-block (32 keys, 32 values) is requested before the current one is consumed

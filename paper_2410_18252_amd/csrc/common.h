@@ -76,3 +76,4 @@ __device__ __forceinline__ float wave_max(float v) {
 // Sticky device-detected input faults (bit flags in ctx->status word).
 #define RLGEN_FAULT_TOKEN   1u
 #define RLGEN_FAULT_UNIFORM 2u
+#define RLGEN_FAULT_GROUP   4u      // sequences declared to share a prefix (rlgen_set_score_groups) do not

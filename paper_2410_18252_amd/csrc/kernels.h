@@ -85,7 +85,9 @@ hipError_t rl_gemm_variant(const GemmArgs& g, int epi, int variant, hipStream_t 
 hipError_t rl_gemm_splitk(const GemmArgs& g, int epi, int variant, hipStream_t s);   // needs g.ws, g.splits >= 2
 
 // ------------------------------------------------------------------ attention
-struct AttnJob { int cache_seq, row0, len, qblock; };   // prefill: 16 queries [16 qblock, 16 qblock + 16) of one sequence
+// prefill: 16 queries [16 qblock, 16 qblock + 16) of one sequence.  pre_len > 0: the sequence continues a prefix held
+// by cache sequence pre_seq (pre_len keys, all visible to every query) -- the shared prompt of grouped scoring
+struct AttnJob { int cache_seq, row0, len, qblock, pre_seq, pre_len; };
 struct AttnArgs {
   const uint16_t* q; int q_ld;        // fp16 [rows, Hq * h], rotated
   uint16_t* out; int out_rows;        // fp16 [out_rows, Hq * h], K-block major (input of the O projection)

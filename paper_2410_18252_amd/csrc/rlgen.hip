@@ -28,6 +28,12 @@ struct SeqMeta {       // one per sequence of a call, consumed by expand_kernel
   int lm0;             // first LM-head row of the sequence within its chunk (scoring)
   int score_from;      // first scored position
   int out_off;         // offset of the sequence's row in the output array (scoring)
+  // grouped scoring: the sequence is the tail of a caller's sequence whose first pos0 tokens are processed once
+  // for the whole group, as the sequence in cache stream pre_seq
+  int pos0;            // position of the sequence's first token (0 unless it continues a shared prefix)
+  int prev_row;        // row holding the last token of the shared prefix (-1: none): it predicts this sequence's first token
+  int pre_seq;         // cache stream of the shared prefix
+  int ref_off;         // offset, in the caller's token array, of the group's first sequence (prefixes are compared against it)
 };
 
 struct LayerW {
@@ -66,6 +72,7 @@ struct rlgen_ctx {
   int *d_kv_off, *d_kv_cap, *d_ctx_base, *d_iota, *d_lastrow, *d_order;
   bool use_order;
   bool fused_qkv;         // rotary_dim % 4 == 0: rotary embedding and cache writes run in the QKV GEMM's epilogue
+  int score_groups;       // k > 1: rlgen_score treats every k consecutive sequences as one prompt with k completions
   int eos_token;          // -1: completions never end early (rlgen_set_eos)
   int* d_finished;        // [max_seqs] 1 once a sequence of the running call has emitted eos_token
   int eos_every;          // ended sequences are dropped from the batch every this many decode steps (0: never)
@@ -179,7 +186,7 @@ size_t carve(rlgen_ctx* c, char* base) {
   c->lay.h = m.head_dim;
   c->lay.layer_stride = 2LL * m.max_kv_tokens * m.n_kv_heads * m.head_dim;
   c->kv = k.take<uint16_t>(base, (size_t)c->lay.layer_stride * m.n_layers);
-  c->d_meta = k.take<SeqMeta>(base, S);
+  c->d_meta = k.take<SeqMeta>(base, 2 * S);       // grouped scoring adds one shared prefix per group
   c->d_kv_off = k.take<int>(base, 2 * S); c->d_kv_cap = k.take<int>(base, 2 * S);   // prompt + per-sequence streams
   c->d_ctx_base = k.take<int>(base, S); c->d_iota = k.take<int>(base, S);
   c->d_lastrow = k.take<int>(base, S); c->d_next_token = k.take<int>(base, S);
@@ -188,7 +195,7 @@ size_t carve(rlgen_ctx* c, char* base) {
   c->d_cmp = k.take<int>(base, 8 * S); c->d_lists = k.take<int>(base, 3 * S);
   c->d_tok_index = k.take<int>(base, R); c->d_pos = k.take<int>(base, R); c->d_dst_seq = k.take<int>(base, R);
   c->d_lm_row = k.take<int>(base, R); c->d_target = k.take<int>(base, R); c->d_out_index = k.take<int>(base, R);
-  c->d_jobs = k.take<AttnJob>(base, R / 16 + 2 * S + 2);
+  c->d_jobs = k.take<AttnJob>(base, R / 16 + 4 * S + 2);
   c->Sg = (2 * m.max_seqs + 2) / 3 + 1;        // the larger half: ceil(B / 2) prompts of B >= 2, k samples each
   for (int i = 0; i < 3; ++i) {
     const size_t rows = i == 0 ? R : (size_t)c->Sg, lm = i == 0 ? LM : (size_t)c->Sg;
@@ -262,17 +269,30 @@ int pack_weights(rlgen_ctx* c, const rlgen_weights* w, hipStream_t st) {
 
 // Expands per-sequence metadata into the per-row arrays the kernels index.  One block per sequence.
 __global__ void expand_kernel(const SeqMeta* meta, int first, const int* tokens, int* tok_index, int* pos, int* dst_seq,
-                              AttnJob* jobs, int* lm_row, int* target, int* out_index, int scoring, int job_mult) {
+                              AttnJob* jobs, int* lm_row, int* target, int* out_index, int scoring, int job_mult,
+                              unsigned* status) {
   const SeqMeta m = meta[first + blockIdx.x];
   for (int p = threadIdx.x; p < m.len; p += blockDim.x) {
     tok_index[m.row0 + p] = m.src_off + p;
-    pos[m.row0 + p] = p;
+    pos[m.row0 + p] = m.pos0 + p;
     dst_seq[m.row0 + p] = m.cache_seq;
   }
   // 16-token blocks, their count rounded up to a multiple of job_mult (the blocks past the end do nothing)
   const int nj = (m.len + 16 * job_mult - 1) / (16 * job_mult) * job_mult;
-  for (int j = threadIdx.x; j < nj; j += blockDim.x) jobs[m.job0 + j] = AttnJob{m.cache_seq, m.row0, m.len, j};
-  if (scoring) {
+  for (int j = threadIdx.x; j < nj; j += blockDim.x)
+    jobs[m.job0 + j] = AttnJob{m.cache_seq, m.row0, m.len, j, m.pre_seq, m.prev_row >= 0 ? m.pos0 : 0};
+  if (scoring && m.prev_row >= 0) {
+    // every token of the tail is scored; the first one from the shared prefix's last row
+    for (int t = threadIdx.x; t < m.len; t += blockDim.x) {
+      lm_row[m.lm0 + t] = t == 0 ? m.prev_row : m.row0 + t - 1;
+      target[m.lm0 + t] = tokens[m.src_off + t];
+      out_index[m.lm0 + t] = m.out_off + t;
+    }
+    // the caller declared the first pos0 tokens equal to those of the group's first sequence
+    bool same = true;
+    for (int p = threadIdx.x; p < m.pos0; p += blockDim.x) same &= tokens[m.src_off - m.pos0 + p] == tokens[m.ref_off + p];
+    if (!same) atomicOr(status, RLGEN_FAULT_GROUP);
+  } else if (scoring) {
     for (int t = m.score_from + threadIdx.x; t < m.len; t += blockDim.x) {
       const int i = m.lm0 + (t - m.score_from);
       lm_row[i] = m.row0 + t - 1;
@@ -613,7 +633,7 @@ Staged stage_views(rlgen_ctx* c) {
   const size_t S = c->cfg.max_seqs;
   char* p = c->h_stage;
   Staged s;
-  s.meta = (SeqMeta*)p; p += align_up(S * sizeof(SeqMeta));
+  s.meta = (SeqMeta*)p; p += align_up(2 * S * sizeof(SeqMeta));
   s.kv_off = (int*)p; p += align_up(2 * S * 4);
   s.kv_cap = (int*)p; p += align_up(2 * S * 4);
   s.ctx_base = (int*)p; p += align_up(S * 4);
@@ -638,7 +658,7 @@ int stage_upload(rlgen_ctx* c, const Staged& s, int nmeta, int nseq, int nstream
 int expand(rlgen_ctx* c, const Chunk& ch, const int* tokens, bool scoring, hipStream_t st) {
   hipLaunchKernelGGL(expand_kernel, dim3(ch.count), dim3(256), 0, st, c->d_meta, ch.first, tokens, c->d_tok_index, c->d_pos,
                      c->d_dst_seq, c->d_jobs, c->d_lm_row, c->d_target, c->d_out_index, scoring ? 1 : 0,
-                     rl_attention_prefill_qb(c->cfg.head_dim));
+                     rl_attention_prefill_qb(c->cfg.head_dim), c->status);
   HIPCHK(hipGetLastError());
   return RLGEN_OK;
 }
@@ -655,31 +675,95 @@ int score_impl(rlgen_ctx* c, const int32_t* seqs, const int32_t* seq_lens, const
     if (seq_lens[n] < 1 || seq_lens[n] > stride) return RLGEN_ERR_BAD_ARG;
     if (seq_lens[n] > m.max_seq_len) return RLGEN_ERR_CAPACITY;
   }
+  // Grouped scoring (rlgen_set_score_groups): the k sequences of a group share their first score_from tokens, which
+  // are processed once, as a sequence of their own whose keys and values every member's tail attends to.
+  const int gk = (!logits && c->score_groups > 1) ? c->score_groups : 1;
+  if (gk > 1) {
+    if (N % gk != 0 || !score_from) return RLGEN_ERR_BAD_ARG;
+    for (int n0 = 0; n0 < N; n0 += gk)
+      for (int j = 0; j < gk; ++j)
+        if (score_from[n0 + j] != score_from[n0] || score_from[n0] < 1 || score_from[n0] > seq_lens[n0 + j]) return RLGEN_ERR_BAD_ARG;
+  }
   int rc = stage_begin(c);
   if (rc) return rc;
   Staged s = stage_views(c);
   std::vector<Chunk> chunks;
-  Chunk cur{0, 0, 0, 0, 0};
-  long long kvtok = 0;
-  for (int n = 0; n < N; ++n) {
-    const int len = seq_lens[n];
-    const int from = logits ? len : std::max(1, score_from ? score_from[n] : 1);
-    const int nlm = logits ? 1 : std::max(0, len - from);
-    if (cur.count && (cur.rows + len > c->R || kvtok + round32(len) > m.max_kv_tokens)) {
-      chunks.push_back(cur);
-      cur = Chunk{n, 0, 0, 0, 0};
-      kvtok = 0;
+  int nmeta = 0;
+  // (the separate rotary kernel of the unfused path places keys by position, not by position within the tail: there
+  // the call scores plainly)
+  bool grouped = gk > 1 && c->fused_qkv;
+  if (grouped) {
+    Chunk cur{0, 0, 0, 0, 0};
+    long long kvtok = 0;
+    int vs = 0;                               // virtual sequences: one shared prefix per group, one tail per member
+    for (int n0 = 0; n0 < N && grouped; n0 += gk) {
+      const int P = score_from[n0];
+      long long rows_g = P, kv_g = round32(P);
+      for (int j = 0; j < gk; ++j)
+        if (seq_lens[n0 + j] > P) { rows_g += seq_lens[n0 + j] - P; kv_g += round32(seq_lens[n0 + j] - P); }
+      if (rows_g > c->R || kv_g > m.max_kv_tokens) { grouped = false; break; }     // a group must fit one chunk: score plainly
+      if (cur.count && (cur.rows + rows_g > c->R || kvtok + kv_g > m.max_kv_tokens)) {
+        chunks.push_back(cur);
+        cur = Chunk{vs, 0, 0, 0, 0};
+        kvtok = 0;
+      }
+      auto add = [&](int len, int src_off, int out_off) -> SeqMeta& {
+        SeqMeta& e = s.meta[vs];
+        e = SeqMeta{};
+        e.prev_row = -1;
+        e.row0 = cur.rows; e.len = len; e.src_off = src_off; e.cache_seq = vs; e.job0 = cur.jobs; e.lm0 = cur.lm_rows;
+        e.score_from = len; e.out_off = out_off;
+        s.kv_off[vs] = (int)kvtok; s.kv_cap[vs] = round32(len);
+        kvtok += round32(len);
+        ++vs;
+        cur.count++; cur.rows += len; cur.jobs += jobs_of(c, len);
+        return e;
+      };
+      const int pre_vs = vs;
+      add(P, n0 * stride, n0 * stride);
+      const int last_prefix_row = cur.rows - 1;
+      for (int j = 0; j < gk; ++j) {
+        const int n = n0 + j, L = seq_lens[n] - P;
+        if (L <= 0) continue;
+        const int lm0 = cur.lm_rows;
+        SeqMeta& e = add(L, n * stride + P, n * stride + P);
+        e.lm0 = lm0; e.pos0 = P; e.prev_row = last_prefix_row; e.pre_seq = pre_vs; e.ref_off = n0 * stride;
+        cur.lm_rows += L;
+      }
     }
-    SeqMeta& e = s.meta[n];
-    e.row0 = cur.rows; e.len = len; e.src_off = n * stride; e.cache_seq = n; e.job0 = cur.jobs;
-    e.lm0 = cur.lm_rows; e.score_from = from; e.out_off = n * stride;
-    s.kv_off[n] = (int)kvtok; s.kv_cap[n] = round32(len);
-    s.ctx_base[n] = len; s.iota[n] = n; s.lastrow[n] = cur.rows + len - 1; s.order[n] = n;
-    kvtok += round32(len);
-    cur.count++; cur.rows += len; cur.jobs += jobs_of(c, len); cur.lm_rows += nlm;
+    if (grouped) {
+      chunks.push_back(cur);
+      nmeta = vs;
+    } else {
+      chunks.clear();
+    }
   }
-  chunks.push_back(cur);
-  rc = stage_upload(c, s, N, N, N, st);
+  if (!grouped) {
+    Chunk cur{0, 0, 0, 0, 0};
+    long long kvtok = 0;
+    for (int n = 0; n < N; ++n) {
+      const int len = seq_lens[n];
+      const int from = logits ? len : std::max(1, score_from ? score_from[n] : 1);
+      const int nlm = logits ? 1 : std::max(0, len - from);
+      if (cur.count && (cur.rows + len > c->R || kvtok + round32(len) > m.max_kv_tokens)) {
+        chunks.push_back(cur);
+        cur = Chunk{n, 0, 0, 0, 0};
+        kvtok = 0;
+      }
+      SeqMeta& e = s.meta[n];
+      e = SeqMeta{};
+      e.prev_row = -1;
+      e.row0 = cur.rows; e.len = len; e.src_off = n * stride; e.cache_seq = n; e.job0 = cur.jobs;
+      e.lm0 = cur.lm_rows; e.score_from = from; e.out_off = n * stride;
+      s.kv_off[n] = (int)kvtok; s.kv_cap[n] = round32(len);
+      s.ctx_base[n] = len; s.iota[n] = n; s.lastrow[n] = cur.rows + len - 1; s.order[n] = n;
+      kvtok += round32(len);
+      cur.count++; cur.rows += len; cur.jobs += jobs_of(c, len); cur.lm_rows += nlm;
+    }
+    chunks.push_back(cur);
+    nmeta = N;
+  }
+  rc = stage_upload(c, s, nmeta, grouped ? 0 : N, nmeta, st);
   if (rc) return rc;
   if (c->timed) HIPCHK(hipEventRecord(c->ev_start, st));
   if (!logits) {
@@ -751,7 +835,7 @@ int rlgen_create(const rlgen_model_cfg* cfg, const rlgen_weights* weights, void*
   carve(c, c->ws);
   hipStream_t st = (hipStream_t)hip_stream;
   const size_t S = cfg->max_seqs;
-  c->stage_bytes = align_up(S * sizeof(SeqMeta)) + 4 * align_up(S * 4) + 2 * align_up(2 * S * 4);
+  c->stage_bytes = align_up(2 * S * sizeof(SeqMeta)) + 4 * align_up(S * 4) + 2 * align_up(2 * S * 4);
   auto fail = [&](int code) {
     rlgen_destroy(c);
     return code;
@@ -836,6 +920,8 @@ int rlgen_generate(rlgen_ctx* c, const int32_t* prompts, const int32_t* prompt_l
       cur = Chunk{b, 0, 0, 0, 0};
     }
     SeqMeta& e = s.meta[b];
+    e = SeqMeta{};
+    e.prev_row = -1;
     e.row0 = cur.rows; e.len = len; e.src_off = b * prompt_stride; e.cache_seq = share ? b : b * k; e.job0 = cur.jobs;
     e.lm0 = 0; e.score_from = len; e.out_off = 0;
     if (share) {
@@ -1079,6 +1165,13 @@ int rlgen_set_eos(rlgen_ctx* c, int32_t eos_token) {
   if (!c) return RLGEN_ERR_NULL;
   if (eos_token < -1 || eos_token >= c->cfg.vocab) return RLGEN_ERR_BAD_ARG;
   c->eos_token = eos_token;
+  return RLGEN_OK;
+}
+
+int rlgen_set_score_groups(rlgen_ctx* c, int32_t k) {
+  if (!c) return RLGEN_ERR_NULL;
+  if (k < 1) return RLGEN_ERR_BAD_ARG;
+  c->score_groups = k;
   return RLGEN_OK;
 }
 

@@ -26,7 +26,7 @@ DTYPE_F32, DTYPE_BF16 = 0, 1
 
 EXPORTS = ["rlgen_workspace_bytes", "rlgen_create", "rlgen_update_weights", "rlgen_generate", "rlgen_score",
            "rlgen_debug_logits", "rlgen_debug_sample", "rlgen_sequence_logprob", "rlgen_dpo_loss", "rlgen_select_pairs",
-           "rlgen_get_timings", "rlgen_set_profiling", "rlgen_set_decode_split", "rlgen_set_eos", "rlgen_status", "rlgen_strerror", "rlgen_destroy"]
+           "rlgen_get_timings", "rlgen_set_profiling", "rlgen_set_decode_split", "rlgen_set_eos", "rlgen_set_score_groups", "rlgen_status", "rlgen_strerror", "rlgen_destroy"]
 
 
 class ModelCfg(C.Structure):
@@ -73,6 +73,8 @@ lib.rlgen_dpo_loss.restype = C.c_int
 lib.rlgen_dpo_loss.argtypes = [_vp, _vp, _vp, _vp, _i32, _f32, _vp, _vp]
 lib.rlgen_get_timings.restype = C.c_int
 lib.rlgen_get_timings.argtypes = [_vp, C.POINTER(_f32), C.POINTER(_f32), C.POINTER(_f32), C.POINTER(_i32)]
+lib.rlgen_set_score_groups.restype = C.c_int
+lib.rlgen_set_score_groups.argtypes = [_vp, _i32]
 lib.rlgen_set_eos.restype = C.c_int
 lib.rlgen_set_eos.argtypes = [_vp, _i32]
 lib.rlgen_set_decode_split.restype = C.c_int
@@ -277,6 +279,10 @@ def rlgen_get_timings(p: Policy):
     a, b, c, n = _f32(), _f32(), _f32(), _i32()
     _check(lib.rlgen_get_timings(p.ctx, C.byref(a), C.byref(b), C.byref(c), C.byref(n)), "rlgen_get_timings")
     return {"prefill_ms": a.value, "decode_ms": b.value, "decode_attn_ms": c.value, "decode_attn_launches": n.value}
+
+
+def rlgen_set_score_groups(p: Policy, k: int):
+    _check(lib.rlgen_set_score_groups(p.ctx, int(k)), "rlgen_set_score_groups")
 
 
 def rlgen_set_eos(p: Policy, eos_token: int):

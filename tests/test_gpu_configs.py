@@ -117,6 +117,17 @@ def test_full_size_workload(ci):
             assert (sc[i, :P] == 0).all() and (sc[i, P + T:] == 0).all()
         report(f"config{ci}-score-vs-generate", err=worst)
         assert worst < TOL_LOGPROB
+        # the same with each prompt run once for its k completions
+        r.rlgen_set_score_groups(pol, k)
+        sg = r.rlgen_score(pol, dev_i32(full), flens, w.temperature, np.repeat(lens, k))
+        torch.cuda.synchronize()
+        log(f"grouped score done in {r.rlgen_get_timings(pol)['prefill_ms']:.1f} ms")
+        r.rlgen_set_score_groups(pol, 1)
+        assert r.rlgen_status(pol) == 0
+        sg = sg.cpu().numpy()
+        report(f"config{ci}-grouped-score", vs_plain=np.abs(sg - sc).max())
+        assert np.abs(sg - sc).max() < TOL_LOGPROB
+        assert ((sg == 0) == (sc == 0)).all()
         # and against the oracle on the subset's 8-token sequences
         sc8 = r.rlgen_score(pol, dev_i32(sarr), slens, w.temperature, slens - n8).cpu().numpy()
         for i in range(len(seqs8)):

@@ -595,3 +595,57 @@ def test_ended_sequences_leave_the_batch(name, every, monkeypatch):
         flat_t, flat_l = outs[0][0].reshape(B * k, T), outs[0][1].reshape(B * k, T)
         for q, t in ended_at.items():
             assert (flat_t[q, t:] == eos).all() and (flat_l[q, t + 1:] == 0).all()
+
+
+# ---------------------------------------------------------------- scoring a prompt's k completions with the prompt shared
+@pytest.mark.parametrize("k", [2, 3])
+def test_grouped_score_matches_oracle_and_plain(small, k):
+    m, W, dec, pol = small
+    rng = np.random.default_rng(81 + k)
+    r = R()
+    #            prompt length, completion lengths (0: a member that is the bare prompt)
+    groups = [(30, [9, 1, 0][:k] + [5] * (k - 3)), (1, [20] * k), (33, [17, 16, 15][:k]), (16, [1] * k), (40, [30, 10, 20][:k])]
+    if k == 3:
+        groups = groups[:3] + groups[4:]          # 12 sequences: the context's capacity
+    seqs, from_ = [], []
+    for P, tails in groups:
+        prompt = rng.integers(0, m.vocab, size=P)
+        for L in tails:
+            seqs.append(np.concatenate([prompt, rng.integers(0, m.vocab, size=L)]))
+            from_.append(P)
+    arr, lens = padded(seqs, pad=-3)
+    from_ = np.array(from_, np.int32)
+    plain = r.rlgen_score(pol, dev_i32(arr), lens, 0.7, from_).cpu().numpy()
+    try:
+        r.rlgen_set_score_groups(pol, k)
+        got = r.rlgen_score(pol, dev_i32(arr), lens, 0.7, from_).cpu().numpy()
+        assert r.rlgen_status(pol) == 0
+        # the last group (40 + tails) does not fit a chunk of 80 rows when k = 3: the call then scores plainly
+        for i, sq in enumerate(seqs):
+            ref = O.score(dec, sq, 0.7, from_[i])
+            assert np.abs(got[i, :len(sq)] - ref).max() < TOL_LOGPROB, i
+            assert (got[i, len(sq):] == 0).all() and (got[i, :from_[i]] == 0).all()
+        report("score-grouped", vs_plain=np.abs(got - plain).max(), k=k, h=m.head_dim)
+        assert np.abs(got - plain).max() < TOL_LOGPROB
+        # argument checks: N not a multiple of k, unequal score_from in a group, score_from beyond a member
+        with pytest.raises(r.RlgenError):
+            r.rlgen_score(pol, dev_i32(arr[:k + 1]), lens[:k + 1], 0.7, from_[:k + 1])
+        bad = from_.copy(); bad[1] += 1
+        with pytest.raises(r.RlgenError):
+            r.rlgen_score(pol, dev_i32(arr), lens, 0.7, bad)
+        with pytest.raises(r.RlgenError):
+            r.rlgen_score(pol, dev_i32(arr), lens, 0.7, None)
+    finally:
+        r.rlgen_set_score_groups(pol, 1)
+    # a member whose "shared" part differs is detected on the device (the flag is sticky: a context of its own)
+    pol2 = make_policy(W, max_seqs=len(seqs), max_seq_len=80)
+    try:
+        r.rlgen_set_score_groups(pol2, k)
+        r.rlgen_score(pol2, dev_i32(arr), lens, 0.7, from_)
+        assert r.rlgen_status(pol2) == 0
+        arr2 = arr.copy(); arr2[2 * k + 1, 5] = (arr2[2 * k + 1, 5] + 1) % m.vocab
+        r.rlgen_score(pol2, dev_i32(arr2), lens, 0.7, from_)
+        # (a model whose rotary width is not a multiple of 4 takes the separate rotary kernel, where grouping is off)
+        assert r.rlgen_status(pol2) == (r.ERR_DEVICE if m.rotary_dim % 4 == 0 else 0)
+    finally:
+        pol2.close()
