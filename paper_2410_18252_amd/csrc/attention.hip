@@ -194,20 +194,29 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a) {
       // lane (c, g) now holds the scores of keys 32 sb + 8 g + 4 t + j against column c
       float p[8];
       float bmax = -INFINITY;
+      if (__all(sb * 32 + 31 <= klimit[b])) {      // every key of the super-block is visible to every column: no masking
 #pragma unroll
-      for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int key = sb * 32 + 8 * g + 4 * t + j;
-          const float v = key <= klimit[b] ? sc[t][j] * a.scale : -INFINITY;
-          p[4 * t + j] = v;
-          bmax = fmaxf(bmax, v);
+        for (int e = 0; e < 8; ++e) {
+          p[e] = sc[e >> 2][e & 3] * a.scale;
+          bmax = fmaxf(bmax, p[e]);
         }
+      } else {
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const int key = sb * 32 + 8 * g + 4 * t + j;
+            const float v = key <= klimit[b] ? sc[t][j] * a.scale : -INFINITY;
+            p[4 * t + j] = v;
+            bmax = fmaxf(bmax, v);
+          }
+      }
       bmax = fmaxf(bmax, __shfl_xor(bmax, 16, WAVE));
       bmax = fmaxf(bmax, __shfl_xor(bmax, 32, WAVE));
       const float mnew = fmaxf(m[b], bmax);
+      const bool rescale = !__all(mnew == m[b]);    // the running maximum moved in some column
       // a column that has seen no key yet (m and mnew both -inf) keeps alpha = 1 and p = 0
-      const float alpha = mnew == -INFINITY ? 1.f : __expf(m[b] - mnew);
+      const float alpha = (!rescale || mnew == -INFINITY) ? 1.f : __expf(m[b] - mnew);
       m[b] = mnew;
       float psum = 0.f;
 #pragma unroll
@@ -215,15 +224,18 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a) {
         p[e] = mnew == -INFINITY ? 0.f : __expf(p[e] - mnew);
         psum += p[e];
       }
-      lsum[b] = lsum[b] * alpha + psum;
       f16x8 pf;
 #pragma unroll
       for (int e = 0; e < 8; ++e) pf[e] = (f16_t)p[e];
+      if (rescale) {
+        lsum[b] = lsum[b] * alpha + psum;
 #pragma unroll
-      for (int t = 0; t < VT; ++t) {
-        o[b][t] *= alpha;
-        o[b][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vf[t], pf, o[b][t], 0, 0, 0);
+        for (int t = 0; t < VT; ++t) o[b][t] *= alpha;
+      } else {
+        lsum[b] += psum;
       }
+#pragma unroll
+      for (int t = 0; t < VT; ++t) o[b][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vf[t], pf, o[b][t], 0, 0, 0);
     }
 #if ATTN_PREFETCH
 #pragma unroll
