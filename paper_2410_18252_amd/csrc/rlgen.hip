@@ -505,6 +505,14 @@ int sample_rows(rlgen_ctx* c, int rows, float temperature, const float* uniforms
   return RLGEN_OK;
 }
 
+// bytes of the weights a decode step reads (fp16 matrices: every layer's and the LM head)
+double weight_bytes_of(const rlgen_model_cfg& m) {
+  const double qd = (double)m.n_q_heads * m.head_dim, kvd = (double)m.n_kv_heads * m.head_dim;
+  const double per_layer = (qd + 2 * kvd) * m.d_model + qd * m.d_model +
+                           (m.arch == RLGEN_ARCH_LLAMA ? 3.0 : 2.0) * m.d_ffn * (double)m.d_model;
+  return 2.0 * (per_layer * m.n_layers + (double)m.vocab * m.d_model);
+}
+
 // Times every tile shape (and K split) on each linear layer of this model at the row counts it will see --
 // max_seqs rows for a decode step, a full chunk for the prompt pass -- and keeps the fastest.  Inputs are the
 // activation scratch buffers filled with pseudo-random fp16; outputs land in scratch.
@@ -529,7 +537,11 @@ int tune_gemms(rlgen_ctx* c, hipStream_t st) {
   HIPCHK(hipEventCreate(&e1));
   const LayerW& L = c->layers[0];
   int rc = RLGEN_OK;
-  const bool tune_half = c->have_streams && m.max_seqs >= c->split_min_seqs;
+  // the half-batch decode is worth tuning when a full cache would outweigh the weights four times (the run-time
+  // criterion of rlgen_generate, applied to the context's capacity)
+  bool tune_half = c->have_streams && m.max_seqs >= c->split_min_seqs;
+  if (tune_half && c->split_min_seqs == DECODE_SPLIT_MIN_SEQS)
+    tune_half = 4.0 * m.n_kv_heads * m.head_dim * (double)m.max_kv_tokens * m.n_layers >= 4.0 * weight_bytes_of(m);
   for (int which = 0; which < 5; ++which) c->tuned[2][which] = {-1, 1};
   // The half-batch decode is tuned first; the whole-batch decode may then pick another tile shape but keeps the
   // K split, so that a sequence's arithmetic (the order of its sums) does not depend on how the batch was cut.
@@ -573,7 +585,9 @@ int tune_gemms(rlgen_ctx* c, hipStream_t st) {
         cands.push_back({7, 1});
         if (g.K % 64 == 0 && g.K >= 2048 && g.M <= 2048) cands.push_back({8, 1});     // deeper load pipeline: pays on a long K with few tiles
         const long long t7 = (long long)((g.M + 63) / 64) * ((g.N + 127) / 128);
-        if (g.ws && t7 <= 1024 && epi != EPI_QKV)
+        // a decode that runs as two concurrent halves hides its GEMMs behind the other half's attention: what they
+        // cost then is HBM traffic, and split-K adds its partial sums to it (measured: decode 3 % slower with it)
+        if (g.ws && t7 <= 1024 && epi != EPI_QKV && !(mode != 1 && tune_half))
           for (int sp : {2, 3, 4, 6, 8})
             // what the half batch picks the whole batch must be able to run too (same K split)
             if (nk / sp >= 4 && (size_t)sp * (mode == 2 ? m.max_seqs : g.M) * g.N <= g.ws_elems) cands.push_back({7, sp});
@@ -953,10 +967,8 @@ int rlgen_generate(rlgen_ctx* c, const int32_t* prompts, const int32_t* prompt_l
   // Splitting reads the weights twice per step, so it pays only when the cache traffic of a step dwarfs them.
   bool split = c->have_streams && !c->split_off && B >= 2 && S >= c->split_min_seqs;
   if (split && c->split_min_seqs == DECODE_SPLIT_MIN_SEQS) {
-    const double qd = (double)m.n_q_heads * m.head_dim, kvd = (double)m.n_kv_heads * m.head_dim;
-    const double per_layer = (qd + 2 * kvd) * m.d_model + qd * m.d_model +
-                             (m.arch == RLGEN_ARCH_LLAMA ? 3.0 : 2.0) * m.d_ffn * (double)m.d_model;
-    const double weight_bytes = 2.0 * (per_layer * m.n_layers + (double)m.vocab * m.d_model);
+    const double kvd = (double)m.n_kv_heads * m.head_dim;
+    const double weight_bytes = weight_bytes_of(m);
     double ctx = 0;
     for (int b = 0; b < B; ++b) ctx += (share ? 1.0 : (double)k) * prompt_lens[b] + (double)k * max_new * 0.5;
     const double kv_bytes = 4.0 * kvd * ctx * m.n_layers;
@@ -966,7 +978,7 @@ int rlgen_generate(rlgen_ctx* c, const int32_t* prompts, const int32_t* prompt_l
   const bool compacting = c->eos_token >= 0 && !share && c->eos_every > 0 && max_new > 1;
   if (compacting) split = false;
   const int ngroups = split ? 2 : 1;
-  const int Bh = ngroups == 2 ? (B + 1) / 2 : B;       // (B + 1) / 2 * k <= (max_seqs + 1) / 2 rows for k >= 1, B * k <= max_seqs
+  const int Bh = ngroups == 2 ? (B + 1) / 2 : B;       // the larger half: at most 2/3 of B * k <= max_seqs rows (B >= 2)
   {
     const int unit_k = share ? 1 : k;                 // order entries per prompt
     for (int gi = 0; gi < ngroups; ++gi) {
