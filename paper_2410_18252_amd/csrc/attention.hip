@@ -180,62 +180,56 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a) {
       for (int i = 0; i < KSTEPS; ++i) kf[t][i] = bf16x8_to_f16x8(kraw[t][i]);
 #pragma unroll
     for (int t = 0; t < VT; ++t) vf[t] = bf16x8_to_f16x8(vraw[t]);
+    // straight-line code over the query blocks: their chains (MFMA -> softmax -> MFMA) are independent, and the
+    // scheduler interleaves them only if no branch separates them
+    f32x4 sc[QB][2];
 #pragma unroll
-    for (int b = 0; b < QB; ++b) {
-      if (QB > 1 && __all(sb * 32 > klimit[b])) continue;    // wholly behind this block's causal limit
-      f32x4 sc[2];
+    for (int b = 0; b < QB; ++b)
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
-        sc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+        sc[b][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int i = 0; i < KSTEPS; ++i)
-          sc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[t][i], qf[b][i], sc[t], 0, 0, 0);
+          sc[b][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[t][i], qf[b][i], sc[b][t], 0, 0, 0);
       }
-      // lane (c, g) now holds the scores of keys 32 sb + 8 g + 4 t + j against column c
-      float p[8];
+    // lane (c, g) now holds the scores of keys 32 sb + 8 g + 4 t + j against column c
+    float p[QB][8], alpha[QB];
+#pragma unroll
+    for (int b = 0; b < QB; ++b) {
       float bmax = -INFINITY;
-      if (__all(sb * 32 + 31 <= klimit[b])) {      // every key of the super-block is visible to every column: no masking
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          p[e] = sc[e >> 2][e & 3] * a.scale;
-          bmax = fmaxf(bmax, p[e]);
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int key = sb * 32 + 8 * g + 4 * t + j;
+          const float v = key <= klimit[b] ? sc[b][t][j] * a.scale : -INFINITY;
+          p[b][4 * t + j] = v;
+          bmax = fmaxf(bmax, v);
         }
-      } else {
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const int key = sb * 32 + 8 * g + 4 * t + j;
-            const float v = key <= klimit[b] ? sc[t][j] * a.scale : -INFINITY;
-            p[4 * t + j] = v;
-            bmax = fmaxf(bmax, v);
-          }
-      }
       bmax = fmaxf(bmax, __shfl_xor(bmax, 16, WAVE));
       bmax = fmaxf(bmax, __shfl_xor(bmax, 32, WAVE));
       const float mnew = fmaxf(m[b], bmax);
-      const bool rescale = !__all(mnew == m[b]);    // the running maximum moved in some column
       // a column that has seen no key yet (m and mnew both -inf) keeps alpha = 1 and p = 0
-      const float alpha = (!rescale || mnew == -INFINITY) ? 1.f : __expf(m[b] - mnew);
+      alpha[b] = mnew == -INFINITY ? 1.f : __expf(m[b] - mnew);
       m[b] = mnew;
       float psum = 0.f;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        p[e] = mnew == -INFINITY ? 0.f : __expf(p[e] - mnew);
-        psum += p[e];
+        p[b][e] = mnew == -INFINITY ? 0.f : __expf(p[b][e] - mnew);
+        psum += p[b][e];
       }
+      lsum[b] = lsum[b] * alpha[b] + psum;
+    }
+#pragma unroll
+    for (int b = 0; b < QB; ++b) {
       f16x8 pf;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) pf[e] = (f16_t)p[e];
-      if (rescale) {
-        lsum[b] = lsum[b] * alpha + psum;
+      for (int e = 0; e < 8; ++e) pf[e] = (f16_t)p[b][e];
 #pragma unroll
-        for (int t = 0; t < VT; ++t) o[b][t] *= alpha;
-      } else {
-        lsum[b] += psum;
+      for (int t = 0; t < VT; ++t) {
+        o[b][t] *= alpha[b];
+        o[b][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vf[t], pf, o[b][t], 0, 0, 0);
       }
-#pragma unroll
-      for (int t = 0; t < VT; ++t) o[b][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vf[t], pf, o[b][t], 0, 0, 0);
     }
 #if ATTN_PREFETCH
 #pragma unroll
