@@ -23,6 +23,9 @@
 #ifndef ATTN_PREFETCH
 #define ATTN_PREFETCH 1
 #endif
+#ifndef ATTN_PREFETCH2
+#define ATTN_PREFETCH2 1
+#endif
 #ifndef ATTN_NT
 #define ATTN_NT 1
 #endif
@@ -165,8 +168,19 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a) {
   u32x4 knext[2][KSTEPS], vnext[VT];
   if (nsb > 0) load_sb(0, kraw, vraw);
 #endif
+#if ATTN_PREFETCH2
+  // decode: a second super-block in flight (the kernel is bound by bytes in flight, and registers allow it)
+  u32x4 knext2[2][KSTEPS], vnext2[VT];
+  // measured: head size 128 gains 4 % from it, head sizes 64 and 80 lose (fewer waves fit), 256 would spill
+  constexpr bool P2 = DECODE && HD > 96 && HD <= 128;
+  if (P2 && nsb > 1) load_sb(1, knext, vnext);
+#endif
   for (int sb = 0; sb < nsb; ++sb) {
-#if ATTN_PREFETCH
+#if ATTN_PREFETCH2
+    if (P2) {
+      if (sb + 2 < nsb) load_sb(sb + 2, knext2, vnext2);
+    } else if (sb + 1 < nsb) load_sb(sb + 1, knext, vnext);
+#elif ATTN_PREFETCH
     if (sb + 1 < nsb) load_sb(sb + 1, knext, vnext);
 #else
     load_sb(sb, kraw, vraw);
@@ -238,6 +252,16 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnArgs a) {
       for (int i = 0; i < KSTEPS; ++i) kraw[t][i] = knext[t][i];
 #pragma unroll
     for (int t = 0; t < VT; ++t) vraw[t] = vnext[t];
+#endif
+#if ATTN_PREFETCH2
+    if (P2) {
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int i = 0; i < KSTEPS; ++i) knext[t][i] = knext2[t][i];
+#pragma unroll
+      for (int t = 0; t < VT; ++t) vnext[t] = vnext2[t];
+    }
 #endif
   }
   }   // segments
