@@ -585,9 +585,7 @@ int tune_gemms(rlgen_ctx* c, hipStream_t st) {
         cands.push_back({7, 1});
         if (g.K % 64 == 0 && g.K >= 2048 && g.M <= 2048) cands.push_back({8, 1});     // deeper load pipeline: pays on a long K with few tiles
         const long long t7 = (long long)((g.M + 63) / 64) * ((g.N + 127) / 128);
-        // a decode that runs as two concurrent halves hides its GEMMs behind the other half's attention: what they
-        // cost then is HBM traffic, and split-K adds its partial sums to it (measured: decode 3 % slower with it)
-        if (g.ws && t7 <= 1024 && epi != EPI_QKV && !(mode != 1 && tune_half))
+        if (g.ws && t7 <= 1024 && epi != EPI_QKV)
           for (int sp : {2, 3, 4, 6, 8})
             // what the half batch picks the whole batch must be able to run too (same K split)
             if (nk / sp >= 4 && (size_t)sp * (mode == 2 ? m.max_seqs : g.M) * g.N <= g.ws_elems) cands.push_back({7, sp});
