@@ -32,6 +32,7 @@ GPU_SHAPES = {
     "neox-h32-rot6": ModelShape(ARCH_NEOX, 2, 64, 2, 2, 32, 128, 150, rotary_dim=6),     # rotary_dim % 4 != 0: unfused rotary path
     "neox-h256": ModelShape(ARCH_NEOX, 1, 256, 1, 1, 256, 256, 130, rotary_dim=64),
     "llama-gqa4-h16": ModelShape(ARCH_LLAMA, 2, 128, 8, 2, 16, 96, 500, rotary_dim=16, rope_theta=500000.0),
+    "llama-gqa16-h16": ModelShape(ARCH_LLAMA, 1, 256, 16, 1, 16, 96, 150, rotary_dim=16, rope_theta=500000.0),   # widest group: 16 query heads on one kv head
     "llama-gqa2-h128": ModelShape(ARCH_LLAMA, 2, 256, 2, 1, 128, 64, 64, rotary_dim=128, rope_theta=500000.0),
 }
 
@@ -43,6 +44,8 @@ def scaled_bf16_weights(shape, seed=21, scale=None, lm_head_scale=1.0) -> Weight
     half the tolerances."""
     if scale is None:
         scale = 2.5 if shape.arch == ARCH_LLAMA else (3.0 if shape.head_dim == 256 else 4.0)
+        if shape.n_q_heads // shape.n_kv_heads == 16:
+            scale = 2.0           # one 16-dim kv head for d_model 256: the 16-bit rounding weighs more
     W = make_weights(shape, seed, bf16=False, lm_head_scale=lm_head_scale)
     for k in W.tensors:
         if not k.endswith("_g"):
