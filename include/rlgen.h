@@ -183,6 +183,16 @@ int rlgen_sequence_logprob(const float *token_logprobs, const int32_t *from, con
 int rlgen_dpo_loss(const float *pol_pos, const float *ref_pos, const float *pol_neg,
                    const float *ref_neg, int32_t P, float beta, float *loss, void *hip_stream);
 
+/* Proximal RLOO, the off-policy baseline the paper compares Online DPO with (Appendix B, Eq. 1): for each of
+ * a prompt's k >= 2 completions, objective = min(r A, clip(r, 1 - epsilon, 1 + epsilon) A) with
+ * r = exp(pol_logprob - old_logprob) (pi_theta over the generating policy pi_old, both sequence log-probs as
+ * rlgen_sequence_logprob returns them) and A = the completion's reward minus the mean reward of the prompt's
+ * other k - 1 completions (at k = 2, the other completion's reward, as the appendix writes it).
+ * pol_logprob, old_logprob, rewards, objective: DEVICE [B, k] fp32.
+ * Errors: NULL, BAD_ARG (B < 1, k < 2, epsilon negative or not finite), DEVICE. */
+int rlgen_proximal_rloo(const float *pol_logprob, const float *old_logprob, const float *rewards, int32_t B,
+                        int32_t k, float epsilon, float *objective, void *hip_stream);
+
 /* Which two of a prompt's k completions are trained on (Section 2.1: the two samples ranked by reward;
  * Section 4.2: of K = 4 samples the highest and the lowest rewarded).  rewards [B, k] fp32 (the caller's
  * reward model; no NaN), idx_pos / idx_neg [B] int32 out, all DEVICE: idx_pos[b] = first index of the

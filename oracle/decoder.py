@@ -350,6 +350,26 @@ def dpo_pair_loss(lp_pol_pos, lp_ref_pos, lp_pol_neg, lp_ref_neg, beta):
     return np.logaddexp(0.0, -d)
 
 
+def proximal_rloo_objective(lp_pol, lp_old, rewards, epsilon):
+    """Clipped importance-weighted RLOO objective of every one of a prompt's k >= 2 completions (Appendix B, Eq. 1):
+    min(r A, clip(r, 1 - eps, 1 + eps) A) with r = pi_theta(y|x) / pi_old(y|x) = exp(lp_pol - lp_old) and A the
+    completion's reward minus the baseline.  The appendix writes the baseline for k = 2 (the other completion's
+    reward); for k > 2 this takes RLOO's leave-one-out mean of the other k - 1 rewards, which is the same thing at
+    k = 2.  Arguments are [k] sequence log-probabilities and rewards; float64 throughout."""
+    lp_pol = np.asarray(lp_pol, np.float64)
+    lp_old = np.asarray(lp_old, np.float64)
+    rew = np.asarray(rewards, np.float64)
+    k = len(rew)
+    out = np.zeros(k, np.float64)
+    for i in range(k):
+        baseline = sum(rew[j] for j in range(k) if j != i) / (k - 1)
+        adv = rew[i] - baseline
+        ratio = np.exp(lp_pol[i] - lp_old[i])
+        clipped = min(max(ratio, 1.0 - epsilon), 1.0 + epsilon)
+        out[i] = min(ratio * adv, clipped * adv)
+    return out
+
+
 def select_pair(rewards):
     """Indices (y+, y-) of the highest and the lowest rewarded of a prompt's K completions (Section 2.1: two samples
     ranked by the reward model; Section 4.2: of K samples only the highest and the lowest are trained on).  The

@@ -315,6 +315,20 @@ __global__ void dpo_loss_kernel(const float* pp, const float* rp, const float* p
   loss[i] = fmaxf(-x, 0.f) + log1pf(expf(-fabsf(x)));
 }
 
+// One thread per completion; its baseline is the mean reward of the prompt's other k - 1 completions.
+__global__ void proximal_rloo_kernel(const float* lp_pol, const float* lp_old, const float* rewards, int B, int k, float eps,
+                                     float* objective) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= B * k) return;
+  const float* r = rewards + (size_t)(i / k) * k;
+  float others = 0.f;
+  for (int j = 0; j < k; ++j) others += (j == i % k) ? 0.f : r[j];
+  const float adv = rewards[i] - others / (float)(k - 1);
+  const float ratio = expf(lp_pol[i] - lp_old[i]);
+  const float clipped = fminf(fmaxf(ratio, 1.f - eps), 1.f + eps);
+  objective[i] = fminf(ratio * adv, clipped * adv);
+}
+
 }  // namespace
 
 hipError_t rl_to_bf16(uint16_t* dst, const void* src, int src_is_bf16, size_t n, hipStream_t s) {
@@ -408,5 +422,12 @@ hipError_t rl_select_pairs(const float* rewards, int B, int k, int* idx_pos, int
 hipError_t rl_dpo_loss(const float* pp, const float* rp, const float* pn, const float* rn, int P, float beta, float* loss, hipStream_t s) {
   if (P <= 0) return hipSuccess;
   hipLaunchKernelGGL(dpo_loss_kernel, dim3(blocks_for(P)), dim3(TPB), 0, s, pp, rp, pn, rn, P, beta, loss);
+  return hipGetLastError();
+}
+hipError_t rl_proximal_rloo(const float* lp_pol, const float* lp_old, const float* rewards, int B, int k, float eps, float* objective,
+                            hipStream_t s) {
+  if (B <= 0) return hipSuccess;
+  hipLaunchKernelGGL(proximal_rloo_kernel, dim3(blocks_for((size_t)B * k)), dim3(TPB), 0, s, lp_pol, lp_old, rewards, B, k, eps,
+                     objective);
   return hipGetLastError();
 }

@@ -190,3 +190,5 @@ hipError_t rl_score_finalize(const float2* partial, int ngroups, const float* ta
 hipError_t rl_sequence_logprob(const float* tlp, const int* from, const int* lens, int N, int stride, float* out, hipStream_t s);
 hipError_t rl_select_pairs(const float* rewards, int B, int k, int* idx_pos, int* idx_neg, hipStream_t s);
 hipError_t rl_dpo_loss(const float* pp, const float* rp, const float* pn, const float* rn, int P, float beta, float* loss, hipStream_t s);
+hipError_t rl_proximal_rloo(const float* lp_pol, const float* lp_old, const float* rewards, int B, int k, float eps, float* objective,
+                            hipStream_t s);

@@ -1138,6 +1138,14 @@ int rlgen_dpo_loss(const float* pol_pos, const float* ref_pos, const float* pol_
   return RLGEN_OK;
 }
 
+int rlgen_proximal_rloo(const float* pol_logprob, const float* old_logprob, const float* rewards, int32_t B, int32_t k,
+                        float epsilon, float* objective, void* hip_stream) {
+  if (!pol_logprob || !old_logprob || !rewards || !objective) return RLGEN_ERR_NULL;
+  if (B < 1 || k < 2 || (int64_t)B * k > INT32_MAX || !std::isfinite(epsilon) || epsilon < 0.f) return RLGEN_ERR_BAD_ARG;
+  HIPCHK(rl_proximal_rloo(pol_logprob, old_logprob, rewards, B, k, epsilon, objective, (hipStream_t)hip_stream));
+  return RLGEN_OK;
+}
+
 int rlgen_select_pairs(const float* rewards, int32_t B, int32_t k, int32_t* idx_pos, int32_t* idx_neg, void* hip_stream) {
   if (!rewards || !idx_pos || !idx_neg) return RLGEN_ERR_NULL;
   if (B < 1 || k < 1) return RLGEN_ERR_BAD_ARG;

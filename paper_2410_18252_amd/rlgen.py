@@ -25,7 +25,7 @@ ARCH_NEOX, ARCH_LLAMA = 0, 1
 DTYPE_F32, DTYPE_BF16 = 0, 1
 
 EXPORTS = ["rlgen_workspace_bytes", "rlgen_create", "rlgen_update_weights", "rlgen_generate", "rlgen_score",
-           "rlgen_debug_logits", "rlgen_debug_sample", "rlgen_sequence_logprob", "rlgen_dpo_loss", "rlgen_select_pairs",
+           "rlgen_debug_logits", "rlgen_debug_sample", "rlgen_sequence_logprob", "rlgen_dpo_loss", "rlgen_select_pairs", "rlgen_proximal_rloo",
            "rlgen_get_timings", "rlgen_set_profiling", "rlgen_set_decode_split", "rlgen_set_eos", "rlgen_set_score_groups", "rlgen_status", "rlgen_strerror", "rlgen_destroy"]
 
 
@@ -69,6 +69,8 @@ lib.rlgen_sequence_logprob.restype = C.c_int
 lib.rlgen_sequence_logprob.argtypes = [_vp, _vp, _vp, _i32, _i32, _vp, _vp]
 lib.rlgen_select_pairs.restype = C.c_int
 lib.rlgen_select_pairs.argtypes = [_vp, _i32, _i32, _vp, _vp, _vp]
+lib.rlgen_proximal_rloo.restype = C.c_int
+lib.rlgen_proximal_rloo.argtypes = [_vp, _vp, _vp, _i32, _i32, _f32, _vp, _vp]
 lib.rlgen_dpo_loss.restype = C.c_int
 lib.rlgen_dpo_loss.argtypes = [_vp, _vp, _vp, _vp, _i32, _f32, _vp, _vp]
 lib.rlgen_get_timings.restype = C.c_int
@@ -262,6 +264,18 @@ def rlgen_dpo_loss(pol_pos, ref_pos, pol_neg, ref_neg, beta: float):
     out = torch.empty(P, dtype=torch.float32, device=pol_pos.device)
     _check(lib.rlgen_dpo_loss(_ptr(pol_pos), _ptr(ref_pos), _ptr(pol_neg), _ptr(ref_neg), P, beta, _ptr(out), _stream()),
            "rlgen_dpo_loss")
+    return out
+
+
+def rlgen_proximal_rloo(pol_logprob, old_logprob, rewards, epsilon: float):
+    """[B, k] fp32 sequence log-probs under pi_theta and pi_old and rewards -> [B, k] clipped objective."""
+    assert rewards.dim() == 2
+    B, k = rewards.shape
+    for t in (pol_logprob, old_logprob, rewards):
+        assert t.dtype == torch.float32 and t.is_contiguous() and tuple(t.shape) == (B, k)
+    out = torch.empty(B, k, dtype=torch.float32, device=rewards.device)
+    _check(lib.rlgen_proximal_rloo(_ptr(pol_logprob), _ptr(old_logprob), _ptr(rewards), B, k, epsilon, _ptr(out), _stream()),
+           "rlgen_proximal_rloo")
     return out
 
 

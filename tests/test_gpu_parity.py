@@ -287,6 +287,23 @@ def test_dpo_loss_and_sequence_logprob_match_oracle():
         assert np.abs(got - ref).max() < 1e-5 * max(1.0, np.abs(ref).max())
 
 
+def test_proximal_rloo_matches_oracle():
+    rng = np.random.default_rng(40)
+    r = R()
+    for B, k, eps in ((1, 2, 0.2), (513, 2, 0.2), (300, 4, 0.1), (65, 7, 0.0)):
+        lp_old = (-rng.random((B, k)) * 100).astype(np.float32)
+        lp_pol = (lp_old + rng.standard_normal((B, k)).astype(np.float32) * 0.4).astype(np.float32)
+        rew = rng.standard_normal((B, k)).astype(np.float32)
+        got = r.rlgen_proximal_rloo(dev_f32(lp_pol), dev_f32(lp_old), dev_f32(rew), eps).cpu().numpy()
+        ref = np.stack([O.proximal_rloo_objective(lp_pol[b], lp_old[b], rew[b], np.float64(np.float32(eps))) for b in range(B)])
+        assert got.shape == (B, k)
+        assert np.abs(got - ref).max() < 1e-5 * max(1.0, np.abs(ref).max())
+    z = dev_f32(np.zeros((2, 1), np.float32))
+    with pytest.raises(r.RlgenError) as e:
+        r.rlgen_proximal_rloo(z, z, z, 0.2)                           # k = 1 has no baseline
+    assert e.value.code == r.ERR_BAD_ARG
+
+
 def test_select_pairs_matches_oracle():
     rng = np.random.default_rng(39)
     r = R()

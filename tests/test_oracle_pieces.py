@@ -192,3 +192,37 @@ def test_select_pair_is_the_extremes_of_a_stable_ranking():
             assert pos == best_first[0]
             assert neg == K - 1 - np.argsort(r[::-1], kind="stable")[0]   # last of the lowest
             assert r[pos] == r.max() and r[neg] == r.min() and pos != neg
+
+
+def test_proximal_rloo_objective_is_the_clipped_surrogate():
+    """Pins (Appendix B, Eq. 1): worked k = 2 values; on-policy (ratio 1) the objective is the advantage R1 - R2;
+    the four regimes of the clipped minimum written case by case (positive advantage caps the ratio from above,
+    negative advantage from below); advantages of a prompt's completions sum to zero at ratio 1; brute force of
+    the leave-one-out baseline for k > 2."""
+    # ratio = e^{0.5} > 1.2, A = +2 -> clipped at 1.2 * 2 ; second completion: ratio e^{-0.5} < 0.8, A = -2 -> 0.8 * -2
+    got = O.proximal_rloo_objective([-9.5, -10.5], [-10.0, -10.0], [3.0, 1.0], 0.2)
+    np.testing.assert_allclose(got, [2.4, -1.6], atol=1e-14)
+    # ratio above the band with a negative advantage is NOT clipped (the minimum keeps the more negative value)
+    got = O.proximal_rloo_objective([-9.5, -10.0], [-10.0, -10.0], [1.0, 3.0], 0.2)
+    np.testing.assert_allclose(got, [-2.0 * np.exp(0.5), 2.0], atol=1e-14)
+    # ratio below the band with a positive advantage is not clipped either
+    got = O.proximal_rloo_objective([-11.0, -10.0], [-10.0, -10.0], [3.0, 1.0], 0.2)
+    np.testing.assert_allclose(got, [2.0 * np.exp(-1.0), -2.0], atol=1e-14)
+    rng = np.random.default_rng(11)
+    for k in (2, 3, 4, 8):
+        for _ in range(100):
+            lp_old = -rng.random(k) * 50
+            lp_pol = lp_old + rng.standard_normal(k) * 0.3
+            rew = rng.standard_normal(k)
+            eps = float(rng.choice([0.0, 0.1, 0.2]))
+            got = O.proximal_rloo_objective(lp_pol, lp_old, rew, eps)
+            on_policy = O.proximal_rloo_objective(lp_old, lp_old, rew, eps)
+            adv = (rew - (rew.sum() - rew) / (k - 1))                 # leave-one-out mean, vectorised
+            np.testing.assert_allclose(on_policy, adv, atol=1e-12)
+            assert abs(on_policy.sum()) < 1e-12
+            if k == 2:
+                np.testing.assert_allclose(adv, [rew[0] - rew[1], rew[1] - rew[0]], atol=1e-12)
+            ratio = np.exp(lp_pol - lp_old)
+            by_case = np.where(adv >= 0, np.minimum(ratio, 1 + eps) * adv, np.maximum(ratio, 1 - eps) * adv)
+            np.testing.assert_allclose(got, by_case, atol=1e-12)
+            assert (got <= ratio * adv + 1e-12).all()                 # a lower bound of the unclipped surrogate
