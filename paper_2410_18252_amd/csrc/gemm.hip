@@ -55,6 +55,9 @@ __device__ __forceinline__ float erf_as(float x) {
 __device__ __forceinline__ float gelu_erf(float v) { return 0.5f * v * (1.0f + erf_as(v * 0.70710678118654752f)); }
 __device__ __forceinline__ float silu(float v) { return v / (1.0f + __expf(-v)); }
 
+// nothing may be scheduled across this point
+#define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+
 template <int N>
 __device__ __forceinline__ void wait_loads_then_barrier() {
   // all but the N most recent vector-memory loads of this wave have landed; then every wave of the block is here
@@ -233,12 +236,13 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f16_kernel(GemmArgs g) {
           fb[slot][j] = *(const f16x8*)(lb + r * BK + ((chunk ^ swz(r)) * 8));
         }
       };
-      auto mma = [&](int slot) {
+      constexpr int HEAD = TM * TN >= 8 ? 2 : 1;
+      auto mma = [&](int slot, int lo, int hi) {     // MFMAs lo .. hi - 1 of the group, row-major over the wave's tiles
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int j = 0; j < TN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[slot][j], fa[slot][i], acc[i][j], 0, 0, 0);
+        for (int t = 0; t < TM * TN; ++t)
+          if (t >= lo && t < hi)
+            acc[t / TN][t % TN] =
+                __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[slot][t % TN], fa[slot][t / TN], acc[t / TN][t % TN], 0, 0, 0);
       };
       issue(kt0, 0);
       wait_loads_then_barrier<0>();
@@ -246,19 +250,38 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f16_kernel(GemmArgs g) {
       frags(0, 0, 0);
       for (int kt = kt0; kt < nk; ++kt) {
         const int buf = (kt - kt0) & 1;
+        // Per MFMA group: the first MFMAs, then the LDS reads of the next group's fragments, then the rest, in exactly
+        // this order (the fences stop the compiler from sinking the reads behind the MFMAs, where the wait for them
+        // would sit directly in front of their first use).
+        mma(0, 0, HEAD);
+        SCHED_FENCE();
         frags(buf, 1, 1);
-        mma(0);
+        SCHED_FENCE();
+        mma(0, HEAD, TM * TN);
+        SCHED_FENCE();
+        mma(1, 0, HEAD);
+        SCHED_FENCE();
         frags(buf, 2, 0);
-        mma(1);
+        SCHED_FENCE();
+        mma(1, HEAD, TM * TN);
+        SCHED_FENCE();
+        mma(0, 0, HEAD);
+        SCHED_FENCE();
         frags(buf, 3, 1);
-        mma(0);
+        SCHED_FENCE();
+        mma(0, HEAD, TM * TN);
+        SCHED_FENCE();
+        mma(1, 0, HEAD);
+        SCHED_FENCE();
         if (kt + 1 < nk) {
           // stage kt + 1 has landed, and every wave holds its last fragments of stage kt in registers
           asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
           if (kt + 2 < nk) issue(kt + 2, buf);
           frags(buf ^ 1, 0, 0);
+          SCHED_FENCE();
         }
-        mma(1);
+        mma(1, HEAD, TM * TN);
+        SCHED_FENCE();
       }
     } else {
 #pragma unroll
