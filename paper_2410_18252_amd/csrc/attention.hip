@@ -40,7 +40,7 @@ namespace {
 // QB = query blocks of 16 columns a wave carries through one pass over the keys (prompt pass only: two blocks halve
 // the key / value traffic per query; a.jobs then counts blocks of 16 QB tokens).
 template <int HD, bool DECODE, int QB = 1>
-__global__ __launch_bounds__(256) void attention_kernel(AttnArgs a) {
+__global__ __launch_bounds__(256, (!DECODE && HD <= 128) ? 2 : 1) void attention_kernel(AttnArgs a) {
   static_assert(!DECODE || QB == 1, "decode has one query block");
   constexpr int NCH = HD / 8;            // 16-byte chunks per key row
   constexpr int KSTEPS = (HD + 31) / 32; // MFMA steps over head_dim for the scores
