@@ -26,6 +26,12 @@
 #ifndef ATTN_PREFETCH2
 #define ATTN_PREFETCH2 1
 #endif
+#ifndef ATTN_PROMPT_NOPF
+#define ATTN_PROMPT_NOPF 1
+#endif
+#ifndef ATTN_PROMPT_BLOCKS
+#define ATTN_PROMPT_BLOCKS 2
+#endif
 #ifndef ATTN_NT
 #define ATTN_NT 1
 #endif
@@ -40,11 +46,12 @@ namespace {
 // QB = query blocks of 16 columns a wave carries through one pass over the keys (prompt pass only: two blocks halve
 // the key / value traffic per query; a.jobs then counts blocks of 16 QB tokens).
 template <int HD, bool DECODE, int QB = 1>
-__global__ __launch_bounds__(256, (!DECODE && HD <= 128) ? 2 : 1) void attention_kernel(AttnArgs a) {
+__global__ __launch_bounds__(256, (!DECODE && HD <= 128) ? ATTN_PROMPT_BLOCKS : 1) void attention_kernel(AttnArgs a) {
   static_assert(!DECODE || QB == 1, "decode has one query block");
   constexpr int NCH = HD / 8;            // 16-byte chunks per key row
   constexpr int KSTEPS = (HD + 31) / 32; // MFMA steps over head_dim for the scores
   constexpr int VT = HD / 16;            // 16-row tiles of V^T / O^T
+  constexpr bool PF = DECODE || !ATTN_PROMPT_NOPF;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int c = lane & 15, g = lane >> 4;
   const int Hkv = a.lay.Hkv, G = a.Hq / Hkv;
@@ -166,7 +173,7 @@ __global__ __launch_bounds__(256, (!DECODE && HD <= 128) ? 2 : 1) void attention
   u32x4 kraw[2][KSTEPS], vraw[VT];
 #if ATTN_PREFETCH
   u32x4 knext[2][KSTEPS], vnext[VT];
-  if (nsb > 0) load_sb(0, kraw, vraw);
+  if (PF && nsb > 0) load_sb(0, kraw, vraw);
 #endif
 #if ATTN_PREFETCH2
   // decode: a second super-block in flight (the kernel is bound by bytes in flight, and registers allow it)
@@ -179,7 +186,8 @@ __global__ __launch_bounds__(256, (!DECODE && HD <= 128) ? 2 : 1) void attention
 #if ATTN_PREFETCH2
     if (P2) {
       if (sb + 2 < nsb) load_sb(sb + 2, knext2, vnext2);
-    } else if (sb + 1 < nsb) load_sb(sb + 1, knext, vnext);
+    } else if (PF) { if (sb + 1 < nsb) load_sb(sb + 1, knext, vnext); }
+    else load_sb(sb, kraw, vraw);
 #elif ATTN_PREFETCH
     if (sb + 1 < nsb) load_sb(sb + 1, knext, vnext);
 #else
@@ -246,12 +254,14 @@ __global__ __launch_bounds__(256, (!DECODE && HD <= 128) ? 2 : 1) void attention
       }
     }
 #if ATTN_PREFETCH
+    if (PF) {
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int i = 0; i < KSTEPS; ++i) kraw[t][i] = knext[t][i];
 #pragma unroll
     for (int t = 0; t < VT; ++t) vraw[t] = vnext[t];
+    }
 #endif
 #if ATTN_PREFETCH2
     if (P2) {
