@@ -543,6 +543,31 @@ int tune_gemms(rlgen_ctx* c, hipStream_t st) {
   if (tune_half && c->split_min_seqs == DECODE_SPLIT_MIN_SEQS)
     tune_half = 4.0 * m.n_kv_heads * m.head_dim * (double)m.max_kv_tokens * m.n_layers >= 4.0 * weight_bytes_of(m);
   for (int which = 0; which < 5; ++which) c->tuned[2][which] = {-1, 1};
+  // The neighbour of the half-batch timing runs: the decode attention of the other half, over half a full batch of
+  // sequences that each hold their share of the cache (all zeros), twice in a row.
+  AttnArgs nb{};
+  int* nb_meta = nullptr;
+  float nb_ms = 0.f;
+  if (tune_half) {
+    const int Sh = (m.max_seqs + 1) / 2;
+    const int cap = (int)std::min<long long>(m.max_kv_tokens / m.max_seqs, m.max_seq_len) / 32 * 32;
+    if (cap >= 32 && (long long)Sh * cap * 2 * m.n_kv_heads * m.head_dim <= c->lay.layer_stride) {
+      std::vector<int> meta(3 * (size_t)Sh);
+      for (int i = 0; i < Sh; ++i) { meta[i] = i * cap; meta[Sh + i] = cap; meta[2 * Sh + i] = cap - 1; }
+      bool ok = hipMalloc((void**)&nb_meta, meta.size() * sizeof(int)) == hipSuccess &&
+                hipMemcpy(nb_meta, meta.data(), meta.size() * sizeof(int), hipMemcpyHostToDevice) == hipSuccess &&
+                rl_fill_zero(c->kv, (size_t)Sh * cap * 2 * m.n_kv_heads * m.head_dim * 2, st) == hipSuccess;
+      nb.q = c->q; nb.q_ld = qd; nb.out = (uint16_t*)c->qkv; nb.out_rows = Sh; nb.kv = c->kv; nb.lay = c->lay;
+      nb.kv_off = nb_meta; nb.kv_cap = nb_meta + Sh; nb.ctx_base = nb_meta + 2 * Sh; nb.ctx_add = 1; nb.S = Sh;
+      nb.Hq = m.n_q_heads; nb.scale = 1.0f / sqrtf((float)m.head_dim);
+      for (int r = 0; ok && r < 2; ++r) {          // the second pair is the timed one
+        ok = hipEventRecord(e0, st) == hipSuccess && rl_attention_decode(nb, st) == hipSuccess &&
+             rl_attention_decode(nb, st) == hipSuccess && hipEventRecord(e1, st) == hipSuccess &&
+             hipEventSynchronize(e1) == hipSuccess && hipEventElapsedTime(&nb_ms, e0, e1) == hipSuccess;
+      }
+      if (!ok) rc = RLGEN_ERR_DEVICE;
+    }
+  }
   // The half-batch decode is tuned first; the whole-batch decode may then pick another tile shape but keeps the
   // K split, so that a sequence's arithmetic (the order of its sums) does not depend on how the batch was cut.
   const int modes[3] = {2, 0, 1};
@@ -585,17 +610,20 @@ int tune_gemms(rlgen_ctx* c, hipStream_t st) {
         cands.push_back({7, 1});
         if (g.K % 64 == 0 && g.K >= 2048 && g.M <= 2048) cands.push_back({8, 1});     // deeper load pipeline: pays on a long K with few tiles
         const long long t7 = (long long)((g.M + 63) / 64) * ((g.N + 127) / 128);
+        const long long t5 = (long long)((g.M + 255) / 256) * ((g.N + 127) / 128);
         if (g.ws && t7 <= 1024 && epi != EPI_QKV)
-          for (int sp : {2, 3, 4, 6, 8})
+          for (int sp : {2, 3, 4, 6, 8}) {
             // what the half batch picks the whole batch must be able to run too (same K split)
-            if (nk / sp >= 4 && (size_t)sp * (mode == 2 ? m.max_seqs : g.M) * g.N <= g.ws_elems) cands.push_back({7, sp});
+            if (nk / sp < 4 || (size_t)sp * (mode == 2 ? m.max_seqs : g.M) * g.N > g.ws_elems) continue;
+            cands.push_back({7, sp});
+            if (t5 * sp <= 256) cands.push_back({5, sp});
+          }
       }
       if (mode == 0 && tune_half) {
         const int keep = c->tuned[2][which].splits;
         std::vector<Cand> same;
-        if (keep >= 2) same.push_back({7, keep});     // fits: the half-batch candidates were sized for max_seqs rows
-        else
-          for (const Cand& cd : cands) if (cd.splits == 1) same.push_back(cd);
+        for (const Cand& cd : cands) if (cd.splits == keep) same.push_back(cd);
+        if (same.empty()) same.push_back({7, keep});   // fits: the half-batch candidates were sized for max_seqs rows
         cands = same;
       }
       // clocks drift with load, so the candidates take turns: one warm-up each, then three rounds in which
@@ -613,12 +641,43 @@ int tune_gemms(rlgen_ctx* c, hipStream_t st) {
           total[i] += ms;
         }
       if (!ok) { rc = RLGEN_ERR_DEVICE; break; }
+      // A half-batch GEMM runs beside the other half's attention, and both live on the path from L2 into the CUs:
+      // what counts there is how much longer the neighbour takes, not the GEMM's time alone (on the 2.8B shape 256x128
+      // tiles win for QKV and FFN-up although 64x128 tiles are 25 % faster alone: 6 % off the decode phase).  So the
+      // half-batch candidates are timed again beside the attention of the other half: the time of
+      // [two attention launches || `reps` GEMMs], with reps small enough that the GEMMs end first.
+      std::vector<float> score(total);
+      if (mode == 2 && nb_ms > 0.f && which != G_LMHEAD && ok) {
+        float best_alone = total[0];
+        for (float t : total) best_alone = std::min(best_alone, t);
+        best_alone /= 6.f;                                       // ms per launch
+        const int reps = std::max(1, std::min(8, (int)(nb_ms / (4.f * best_alone))));
+        std::fill(score.begin(), score.end(), 0.f);
+        for (int round = 0; ok && round < 3; ++round)
+          for (size_t i = 0; ok && i < cands.size(); ++i) {
+            ok = hipEventRecord(e0, st) == hipSuccess && hipEventRecord(c->ev_fork, st) == hipSuccess &&
+                 hipStreamWaitEvent(c->gstream[0], c->ev_fork, 0) == hipSuccess &&
+                 hipStreamWaitEvent(c->gstream[1], c->ev_fork, 0) == hipSuccess &&
+                 rl_attention_decode(nb, c->gstream[0]) == hipSuccess && rl_attention_decode(nb, c->gstream[0]) == hipSuccess;
+            for (int r = 0; ok && r < reps; ++r)
+              ok = run_choice(g, epi, cands[i].variant, cands[i].splits, c->gstream[1]) == hipSuccess;
+            for (int gi = 0; ok && gi < 2; ++gi)
+              ok = hipEventRecord(c->ev_join[gi], c->gstream[gi]) == hipSuccess &&
+                   hipStreamWaitEvent(st, c->ev_join[gi], 0) == hipSuccess;
+            if (ok) ok = hipEventRecord(e1, st) == hipSuccess && hipEventSynchronize(e1) == hipSuccess;
+            float ms = 0.f;
+            if (ok) ok = hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
+            score[i] += ms;
+          }
+        if (!ok) { rc = RLGEN_ERR_DEVICE; break; }
+      }
       size_t bi = 0;
-      for (size_t i = 1; i < cands.size(); ++i) if (total[i] < total[bi]) bi = i;
+      for (size_t i = 1; i < cands.size(); ++i) if (score[i] < score[bi]) bi = i;
       rlgen_ctx::GemmChoice pick{cands[bi].variant, cands[bi].splits};
       if (getenv("RLGEN_DEBUG_TUNE")) {
         fprintf(stderr, "rlgen tune: mode %d gemm %d M=%d N=%d K=%d:", mode, which, g.M, g.N, g.K);
-        for (size_t i = 0; i < cands.size(); ++i) fprintf(stderr, " v%d/s%d=%.0fus%s", cands[i].variant, cands[i].splits, total[i] / 6 * 1e3, i == bi ? "*" : "");
+        for (size_t i = 0; i < cands.size(); ++i)
+          fprintf(stderr, " v%d/s%d=%.0fus(%.0f)%s", cands[i].variant, cands[i].splits, total[i] / 6 * 1e3, score[i] / 3 * 1e3, i == bi ? "*" : "");
         fprintf(stderr, "\n");
       }
       c->tuned[mode][which] = pick;
@@ -626,6 +685,7 @@ int tune_gemms(rlgen_ctx* c, hipStream_t st) {
   }
   (void)hipEventDestroy(e0);
   (void)hipEventDestroy(e1);
+  if (nb_meta) (void)hipFree(nb_meta);
   return rc;
 }
 
