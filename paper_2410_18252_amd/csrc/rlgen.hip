@@ -532,9 +532,10 @@ int tune_gemms(rlgen_ctx* c, hipStream_t st) {
                        c->d_kv_cap, c->R, tseq, std::min(32, m.max_seq_len));
     HIPCHK(hipGetLastError());
   }
-  hipEvent_t e0, e1;
+  hipEvent_t e0, e1, e2;
   HIPCHK(hipEventCreate(&e0));
   HIPCHK(hipEventCreate(&e1));
+  HIPCHK(hipEventCreate(&e2));
   const LayerW& L = c->layers[0];
   int rc = RLGEN_OK;
   // the half-batch decode is worth tuning when a full cache would outweigh the weights four times (the run-time
@@ -606,6 +607,7 @@ int tune_gemms(rlgen_ctx* c, hipStream_t st) {
       const int nk = (g.K + 63) / 64;
       struct Cand { int variant, splits; };
       std::vector<Cand> cands = {{0, 1}, {3, 1}, {5, 1}};
+      if (mode == 2) { cands.push_back({1, 1}); cands.push_back({4, 1}); }     // beside attention other shapes can win
       if (!wide_only) {
         cands.push_back({7, 1});
         if (g.K % 64 == 0 && g.K >= 2048 && g.M <= 2048) cands.push_back({8, 1});     // deeper load pipeline: pays on a long K with few tiles
@@ -644,8 +646,9 @@ int tune_gemms(rlgen_ctx* c, hipStream_t st) {
       // A half-batch GEMM runs beside the other half's attention, and both live on the path from L2 into the CUs:
       // what counts there is how much longer the neighbour takes, not the GEMM's time alone (on the 2.8B shape 256x128
       // tiles win for QKV and FFN-up although 64x128 tiles are 25 % faster alone: 6 % off the decode phase).  So the
-      // half-batch candidates are timed again beside the attention of the other half: the time of
-      // [two attention launches || `reps` GEMMs], with reps small enough that the GEMMs end first.
+      // half-batch candidates are timed again beside the attention of the other half: [two attention launches ||
+      // `reps` GEMMs], with reps small enough that the GEMMs end first.  A candidate's cost is what it adds to the
+      // attention's time plus its own time in that company (the two halves take turns, so both are on the clock).
       std::vector<float> score(total);
       if (mode == 2 && nb_ms > 0.f && which != G_LMHEAD && ok) {
         float best_alone = total[0];
@@ -653,7 +656,7 @@ int tune_gemms(rlgen_ctx* c, hipStream_t st) {
         best_alone /= 6.f;                                       // ms per launch
         const int reps = std::max(1, std::min(8, (int)(nb_ms / (4.f * best_alone))));
         std::fill(score.begin(), score.end(), 0.f);
-        for (int round = 0; ok && round < 3; ++round)
+        for (int round = 0; ok && round < 5; ++round)
           for (size_t i = 0; ok && i < cands.size(); ++i) {
             ok = hipEventRecord(e0, st) == hipSuccess && hipEventRecord(c->ev_fork, st) == hipSuccess &&
                  hipStreamWaitEvent(c->gstream[0], c->ev_fork, 0) == hipSuccess &&
@@ -661,23 +664,31 @@ int tune_gemms(rlgen_ctx* c, hipStream_t st) {
                  rl_attention_decode(nb, c->gstream[0]) == hipSuccess && rl_attention_decode(nb, c->gstream[0]) == hipSuccess;
             for (int r = 0; ok && r < reps; ++r)
               ok = run_choice(g, epi, cands[i].variant, cands[i].splits, c->gstream[1]) == hipSuccess;
+            if (ok) ok = hipEventRecord(e2, c->gstream[1]) == hipSuccess;
             for (int gi = 0; ok && gi < 2; ++gi)
               ok = hipEventRecord(c->ev_join[gi], c->gstream[gi]) == hipSuccess &&
                    hipStreamWaitEvent(st, c->ev_join[gi], 0) == hipSuccess;
             if (ok) ok = hipEventRecord(e1, st) == hipSuccess && hipEventSynchronize(e1) == hipSuccess;
-            float ms = 0.f;
-            if (ok) ok = hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
-            score[i] += ms;
+            float ms = 0.f, ms_gemms = 0.f;
+            if (ok) ok = hipEventElapsedTime(&ms, e0, e1) == hipSuccess && hipEventElapsedTime(&ms_gemms, e0, e2) == hipSuccess;
+            // per GEMM: what it adds to the neighbour's time, plus how long the half that runs it waits for it
+            score[i] += ((ms - nb_ms) + ms_gemms) / (float)reps;
           }
         if (!ok) { rc = RLGEN_ERR_DEVICE; break; }
       }
-      size_t bi = 0;
-      for (size_t i = 1; i < cands.size(); ++i) if (score[i] < score[bi]) bi = i;
+      size_t bi = 0, alone = 0;
+      for (size_t i = 1; i < cands.size(); ++i) {
+        if (score[i] < score[bi]) bi = i;
+        if (total[i] < total[alone]) alone = i;
+      }
+      // the joint timing is the noisier one: the candidate that is fastest alone is kept unless another one is clearly
+      // cheaper in company
+      if (score[bi] > 0.97f * score[alone]) bi = alone;
       rlgen_ctx::GemmChoice pick{cands[bi].variant, cands[bi].splits};
       if (getenv("RLGEN_DEBUG_TUNE")) {
         fprintf(stderr, "rlgen tune: mode %d gemm %d M=%d N=%d K=%d:", mode, which, g.M, g.N, g.K);
         for (size_t i = 0; i < cands.size(); ++i)
-          fprintf(stderr, " v%d/s%d=%.0fus(%.0f)%s", cands[i].variant, cands[i].splits, total[i] / 6 * 1e3, score[i] / 3 * 1e3, i == bi ? "*" : "");
+          fprintf(stderr, " v%d/s%d=%.0fus(%.0f)%s", cands[i].variant, cands[i].splits, total[i] / 6 * 1e3, score[i] / (mode == 2 ? 5 : 6) * 1e3, i == bi ? "*" : "");
         fprintf(stderr, "\n");
       }
       c->tuned[mode][which] = pick;
@@ -685,6 +696,7 @@ int tune_gemms(rlgen_ctx* c, hipStream_t st) {
   }
   (void)hipEventDestroy(e0);
   (void)hipEventDestroy(e1);
+  (void)hipEventDestroy(e2);
   if (nb_meta) (void)hipFree(nb_meta);
   return rc;
 }
