@@ -115,7 +115,11 @@ size_t rlgen_workspace_bytes(const rlgen_model_cfg *cfg);
  * at least rlgen_workspace_bytes(cfg); it must stay alive, and must not be written by the caller,
  * until rlgen_destroy.  The weight tensors are converted/copied on `hip_stream` (a hipStream_t, or
  * null for the default stream); once that stream has been synchronised the library no longer reads
- * them.  *out receives the context.  Errors: NULL, BAD_CFG, WORKSPACE, DEVICE. */
+ * them.  *out receives the context.  Errors: NULL, BAD_CFG, WORKSPACE, DEVICE.
+ * Creation also times the tile shapes of every linear layer at this configuration's row counts (on
+ * `hip_stream` and two internal streams, a few hundred launches, 1-3 s at the 2.8B shape) and
+ * synchronises with them; it allocates a few kilobytes of device memory for that and frees them
+ * again, so it must not be called under stream capture. */
 int rlgen_create(const rlgen_model_cfg *cfg, const rlgen_weights *weights, void *workspace,
                  size_t workspace_bytes, void *hip_stream, rlgen_ctx **out);
 
