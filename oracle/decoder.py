@@ -25,7 +25,8 @@ Precision: matrix products in `dt` (float32 by default, float64 on request);
 normalisation statistics, softmax, log-sum-exp and the CDF scan in float64.
 
 Parity pins (tests/test_oracle_*.py): KV-cached decode against cache-free recompute,
-softmax rows summing to one, causality, explicit CDF scan, zero-weight closed forms,
+softmax rows summing to one, causality, explicit CDF scan, CDF buckets tiling [0, 1) and
+holding the uniform of the drawn token, sequence log-probs against exact sums, zero-weight closed forms,
 temperature/LM-head equivalence, GQA replication, rotary against complex
 multiplication, pieces against scipy/torch CPU routines, whole model against the
 installed `transformers` classes used as a black box.

@@ -164,6 +164,51 @@ def test_sampler_is_monotone_in_u_and_matches_distribution():
     assert chi2 < 50.0       # 15 degrees of freedom: P(chi2 > 50) ~ 1e-5
 
 
+def test_cdf_bucket_is_the_interval_of_uniforms_that_draw_the_token():
+    """Pins for cdf_bucket: a worked distribution written out; the buckets of consecutive tokens tile [0, 1) (each
+    starts where the previous one ends, the first at 0, the last ends at 1 up to rounding); bucket edges against
+    exact sums (math.fsum over Python floats); and the bucket of the token sample_inverse_cdf draws contains the
+    uniform it was drawn with, while every other token's bucket does not."""
+    lp = np.log(np.array([0.25, 0.5, 0.125, 0.125]))
+    assert O.cdf_bucket(lp, 0) == (0.0, 0.25)
+    assert O.cdf_bucket(lp, 1) == (0.25, 0.75)
+    assert O.cdf_bucket(lp, 2) == (0.75, 0.875)
+    assert O.cdf_bucket(lp, 3) == (0.875, 1.0)
+    g = rng(12)
+    for V in (3, 16, 257):
+        lp = O.tempered_log_softmax((g.normal(size=V) * 2).astype(np.float32), 0.7)
+        p = [math.exp(float(x)) for x in lp]
+        edges = [O.cdf_bucket(lp, j) for j in range(V)]
+        assert edges[0][0] == 0.0 and abs(edges[-1][1] - 1.0) < 1e-12
+        for j in range(V):
+            lo, hi = edges[j]
+            assert lo == pytest.approx(math.fsum(p[:j]), abs=1e-13) and hi == pytest.approx(math.fsum(p[:j + 1]), abs=1e-13)
+            assert hi - lo == pytest.approx(p[j], abs=1e-13)
+            if j:
+                assert lo == edges[j - 1][1]
+        for u in g.random(300, dtype=np.float32):
+            tok, margin = O.sample_inverse_cdf(lp, u)
+            lo, hi = edges[tok]
+            assert lo <= float(u) < hi
+            assert margin == pytest.approx(min(float(u) - lo, (1.0 if tok == V - 1 else hi) - float(u)), abs=1e-15)
+            inside = [j for j in range(V) if edges[j][0] <= float(u) < edges[j][1]]
+            assert inside == [tok]
+
+
+def test_sequence_logprob_is_the_exact_sum_of_the_response_terms():
+    """Pins for sequence_logprob: exact sums (math.fsum), the half-open range [score_from, length), and additivity
+    over a split of the range."""
+    g = rng(13)
+    tlp = (-g.random(70) * 12).astype(np.float32)
+    for lo, hi in [(0, 70), (5, 70), (17, 18), (33, 64), (69, 70)]:
+        assert O.sequence_logprob(tlp, lo, hi) == pytest.approx(math.fsum(float(x) for x in tlp[lo:hi]), abs=1e-12)
+    assert O.sequence_logprob(tlp, 40, 40) == 0.0 and O.sequence_logprob(tlp, 50, 40) == 0.0
+    assert O.sequence_logprob(tlp, 3, 60) == pytest.approx(O.sequence_logprob(tlp, 3, 31) + O.sequence_logprob(tlp, 31, 60), abs=1e-12)
+    # position `length` itself is outside, position `score_from` inside
+    one_hot = np.zeros(10, np.float32); one_hot[4] = -2.5
+    assert O.sequence_logprob(one_hot, 4, 5) == -2.5 and O.sequence_logprob(one_hot, 5, 10) == 0.0 and O.sequence_logprob(one_hot, 0, 4) == 0.0
+
+
 def test_dpo_pair_loss_closed_forms():
     assert O.dpo_pair_loss(-3.0, -3.0, -5.0, -5.0, 0.1) == pytest.approx(math.log(2.0), abs=1e-15)
     # beta * delta = 0.1 * ((-10+20) - (-30+30)) = 1  ->  -log sigmoid(1)
