@@ -11,7 +11,8 @@
  * Conventions
  *  - Plain C ABI.  Every pointer is a DEVICE pointer unless its comment says HOST.
  *  - The caller owns all memory, including the workspace.  The library allocates no device
- *    memory; rlgen_destroy frees only host-side state.
+ *    memory (host side it allocates its context, small pinned staging buffers, two internal streams
+ *    and a few events); rlgen_destroy frees only that host-side state.
  *  - rlgen_generate / rlgen_score enqueue work on the stream given to the call and return; outputs
  *    are valid once the caller has synchronised that stream.  HOST arrays are read before return.
  *  - One context serves one call at a time (calls on one context must not overlap).
@@ -49,12 +50,7 @@ extern "C" {
 #define RLGEN_DTYPE_BF16  1  /* tensors supplied as bf16                                          */
 
 /* Threads: calls on one context must not overlap; different contexts may be used from different
- * threads.  Environment variables read at rlgen_create (testing and measurement knobs, not needed
- * in normal use): RLGEN_DEBUG_TUNE=1 prints the GEMM tile-shape timings; RLGEN_NO_DECODE_SPLIT=1
- * keeps every decode on the caller's stream; RLGEN_DECODE_SPLIT_MIN=n replaces the 256-sequence
- * threshold of the two-stream decode (and its cache-traffic criterion); RLGEN_EOS_COMPACT_EVERY=n
- * replaces the 8-step interval at which ended sequences leave the batch (0: never);
- * RLGEN_UNFUSED_QKV=1 selects the separate rotary kernel instead of the fused QKV epilogue. */
+ * threads.  The library reads no environment variables. */
 typedef struct rlgen_ctx rlgen_ctx; /* opaque */
 
 typedef struct {
@@ -105,7 +101,7 @@ typedef struct {
   const rlgen_layer_weights *layers;         /* HOST array of n_layers entries            */
 } rlgen_weights;
 
-/* Bytes of workspace rlgen_create needs for this configuration (its private bf16 copy of the
+/* Bytes of workspace rlgen_create needs for this configuration (its private 16-bit copy of the
  * weights, the KV cache, activations and sampler partials), or 0 if cfg is null or invalid. */
 size_t rlgen_workspace_bytes(const rlgen_model_cfg *cfg);
 
@@ -118,8 +114,9 @@ size_t rlgen_workspace_bytes(const rlgen_model_cfg *cfg);
  * them.  *out receives the context.  Errors: NULL, BAD_CFG, WORKSPACE, DEVICE.
  * Creation also times the tile shapes of every linear layer at this configuration's row counts (on
  * `hip_stream` and two internal streams, a few hundred launches, 1-3 s at the 2.8B shape) and
- * synchronises with them; it allocates a few kilobytes of device memory for that and frees them
- * again, so it must not be called under stream capture. */
+ * synchronises with them, so it must not be called under stream capture.  Timing chooses tile shapes
+ * only: how a linear layer's sum over its inner dimension is cut and ordered is a fixed function of
+ * the configuration, so two contexts of one configuration return the same bits whatever they picked. */
 int rlgen_create(const rlgen_model_cfg *cfg, const rlgen_weights *weights, void *workspace,
                  size_t workspace_bytes, void *hip_stream, rlgen_ctx **out);
 
@@ -150,8 +147,8 @@ int rlgen_update_weights(rlgen_ctx *ctx, const rlgen_weights *weights, void *hip
  * first index of the largest logit, uniforms are not read (but must be non-null), and
  * token_logprobs = log softmax(z)[token].
  * With an EOS token set (rlgen_set_eos) a completion ends at its first EOS: the entries after it
- * hold the EOS id at log-prob 0 (forced entries after it are ignored).  The sequence stays in the
- * batch; its later positions cost the same as live ones. */
+ * hold the EOS id at log-prob 0 (forced entries after it are ignored); rlgen_set_eos says what then
+ * happens to the ended sequence's place in the batch. */
 int rlgen_generate(rlgen_ctx *ctx, const int32_t *prompts, const int32_t *prompt_lens, int32_t B,
                    int32_t prompt_stride, int32_t k, int32_t max_new, float temperature,
                    const float *uniforms, const int32_t *forced, int32_t *tokens,
@@ -246,9 +243,31 @@ int rlgen_set_score_groups(rlgen_ctx *ctx, int32_t k);
  * needs); on != 0 turns it back on.  Results do not depend on it. */
 int rlgen_set_decode_split(rlgen_ctx *ctx, int32_t on);
 
-/* Synchronises `hip_stream` and returns RLGEN_ERR_DEVICE if a kernel has flagged a bad token id or
- * uniform since the context was created (sticky), else RLGEN_OK. */
+/* ended sequences leave the batch every `every` decode steps (default 8; 0: never, they stay in the batch and
+ * only stop reading their cache).  Outputs do not depend on it.  Errors: NULL, BAD_ARG (every < 0). */
+int rlgen_set_eos_compaction(rlgen_ctx *ctx, int32_t every);
+
+/* min_seqs >= 2 replaces the 256-sequence threshold of the two-stream decode together with its criterion that a
+ * step's cache traffic must outweigh the weights four times (tests use it to send small batches down that path);
+ * 0 restores the default.  Results do not depend on it.  Errors: NULL, BAD_ARG. */
+int rlgen_set_decode_split_min(rlgen_ctx *ctx, int32_t min_seqs);
+
+/* The tile shape (`variant`, an index into the library's list of GEMM tilings) and the K split the context uses for
+ * linear layer `which` (0 QKV, 1 attention output, 2 FFN up, 3 FFN down, 4 LM head) in `mode` (0: decode of the whole
+ * batch, 1: prompt pass and scoring, 2: decode of half a batch).  variant -1 = chosen per call from the problem size.
+ * rlgen_debug_set_gemm replaces the tile shape (testing and measurement); the K split cannot be set: it is a function
+ * of the configuration.  Errors: NULL, BAD_ARG (mode, which or variant out of range, or a tile shape this layer's
+ * epilogue does not support). */
+int rlgen_debug_get_gemm(rlgen_ctx *ctx, int32_t mode, int32_t which, int32_t *variant, int32_t *splits);
+int rlgen_debug_set_gemm(rlgen_ctx *ctx, int32_t mode, int32_t which, int32_t variant);
+
+/* Synchronises `hip_stream` and returns RLGEN_ERR_DEVICE if a kernel has flagged a device-detected fault since the
+ * context was created (sticky), else RLGEN_OK: a token id outside [0, vocab), a uniform outside [0, 1), a score group
+ * whose members disagree on their shared part, or an activation beyond the largest finite fp16 value (65504), which
+ * the library's fp16 matrix-product inputs cannot hold: such a value is clamped to +-65504, never turned into
+ * infinity.  *faults (nullable, HOST) receives the bit set: 1 token id, 2 uniform, 4 score group, 8 fp16 range. */
 int rlgen_status(rlgen_ctx *ctx, void *hip_stream);
+int rlgen_status_bits(rlgen_ctx *ctx, void *hip_stream, uint32_t *faults);
 
 const char *rlgen_strerror(int code);
 void rlgen_destroy(rlgen_ctx *ctx);

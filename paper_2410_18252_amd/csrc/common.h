@@ -39,10 +39,22 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   return (uint32_t)f32_to_bf16_bits(lo) | ((uint32_t)f32_to_bf16_bits(hi) << 16);
 }
 
+// Sticky device-detected input faults (bit flags in ctx->status word).
+#define RLGEN_FAULT_TOKEN   1u
+#define RLGEN_FAULT_UNIFORM 2u
+#define RLGEN_FAULT_GROUP   4u      // sequences declared to share a prefix (rlgen_set_score_groups) do not
+#define RLGEN_FAULT_RANGE   8u      // an activation exceeded the largest finite fp16 value and was clamped
+
 // fp32 -> fp16, round to nearest even, saturating at the largest finite fp16.
 __device__ __forceinline__ uint16_t f32_to_f16_bits(float f) {
   const f16_t h = (f16_t)fminf(fmaxf(f, -65504.f), 65504.f);
   return __builtin_bit_cast(uint16_t, h);
+}
+// Would f32_to_f16_bits clamp this value?  (65520 is the first value that rounds beyond 65504; NaN counts.)
+__device__ __forceinline__ bool f16_out_of_range(float f) { return !(fabsf(f) < 65520.f); }
+// Raises the sticky fp16-range flag if this lane saw a value the fp16 conversion clamped (rare: one atomic per such lane).
+__device__ __forceinline__ void flag_f16_range(bool sat, unsigned* status) {
+  if (sat && status != nullptr) atomicOr(status, RLGEN_FAULT_RANGE);
 }
 __device__ __forceinline__ float f16_bits_to_f32(uint16_t b) { return (float)__builtin_bit_cast(f16_t, b); }
 __device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi) {
@@ -72,8 +84,3 @@ __device__ __forceinline__ float wave_max(float v) {
   for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, WAVE));
   return v;
 }
-
-// Sticky device-detected input faults (bit flags in ctx->status word).
-#define RLGEN_FAULT_TOKEN   1u
-#define RLGEN_FAULT_UNIFORM 2u
-#define RLGEN_FAULT_GROUP   4u      // sequences declared to share a prefix (rlgen_set_score_groups) do not

@@ -97,7 +97,7 @@ template <int NV>
 __global__ __launch_bounds__(256) void norm_kernel(const float* x, const int* row_index, int rows, int d, float eps,
                                                    const float* g1, const float* b1, uint16_t* out1,
                                                    const float* g2, const float* b2, uint16_t* out2,
-                                                   int out_rows, int out_row0) {
+                                                   int out_rows, int out_row0, unsigned* status) {
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
@@ -125,6 +125,7 @@ __global__ __launch_bounds__(256) void norm_kernel(const float* x, const int* ro
     }
   }
   const float rstd = rsqrtf(wave_sum(sq) / (float)d + eps);
+  bool sat = false;                 // did a value leave fp16's range (it is clamped; the context's status word records it)
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
     const int col = (i * 64 + lane) * 4;
@@ -132,19 +133,31 @@ __global__ __launch_bounds__(256) void norm_kernel(const float* x, const int* ro
     const f32x4 ga = *(const f32x4*)(g1 + col);
     f32x4 ba = f32x4{0.f, 0.f, 0.f, 0.f};
     if (!rms) ba = *(const f32x4*)(b1 + col);
+    f32x4 y;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      y[e] = v[i][e] * rstd * ga[e] + ba[e];
+      sat |= f16_out_of_range(y[e]);
+    }
     u32x2 w;
-    w[0] = pack_f16x2(v[i][0] * rstd * ga[0] + ba[0], v[i][1] * rstd * ga[1] + ba[1]);
-    w[1] = pack_f16x2(v[i][2] * rstd * ga[2] + ba[2], v[i][3] * rstd * ga[3] + ba[3]);
+    w[0] = pack_f16x2(y[0], y[1]);
+    w[1] = pack_f16x2(y[2], y[3]);
     *(u32x2*)(out1 + kblk_off(out_row0 + row, col, out_rows)) = w;
     if (out2) {
       const f32x4 gb = *(const f32x4*)(g2 + col);
       f32x4 bb = f32x4{0.f, 0.f, 0.f, 0.f};
       if (b2) bb = *(const f32x4*)(b2 + col);
-      w[0] = pack_f16x2(v[i][0] * rstd * gb[0] + bb[0], v[i][1] * rstd * gb[1] + bb[1]);
-      w[1] = pack_f16x2(v[i][2] * rstd * gb[2] + bb[2], v[i][3] * rstd * gb[3] + bb[3]);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        y[e] = v[i][e] * rstd * gb[e] + bb[e];
+        sat |= f16_out_of_range(y[e]);
+      }
+      w[0] = pack_f16x2(y[0], y[1]);
+      w[1] = pack_f16x2(y[2], y[3]);
       *(u32x2*)(out2 + kblk_off(out_row0 + row, col, out_rows)) = w;
     }
   }
+  flag_f16_range(sat, status);
 }
 
 // One thread per (row, head slot, 8-dim chunk).  Head slots: Hq query heads, Hkv key heads, Hkv
@@ -381,11 +394,11 @@ hipError_t rl_embed(float* x, const uint16_t* E, const int* tokens, const int* t
 }
 hipError_t rl_norm(const float* x, const int* row_index, int rows, int d, float eps, const float* g1, const float* b1,
                    uint16_t* out1, const float* g2, const float* b2, uint16_t* out2, int out_rows, int out_row0,
-                   hipStream_t s) {
+                   unsigned* status, hipStream_t s) {
   if (rows <= 0) return hipSuccess;
   const dim3 grid((rows + 3) / 4), block(256);
   const int nv = (d + 255) / 256;
-#define NORM(NV) hipLaunchKernelGGL((norm_kernel<NV>), grid, block, 0, s, x, row_index, rows, d, eps, g1, b1, out1, g2, b2, out2, out_rows, out_row0)
+#define NORM(NV) hipLaunchKernelGGL((norm_kernel<NV>), grid, block, 0, s, x, row_index, rows, d, eps, g1, b1, out1, g2, b2, out2, out_rows, out_row0, status)
   if (nv <= 1) NORM(1);
   else if (nv <= 2) NORM(2);
   else if (nv <= 4) NORM(4);

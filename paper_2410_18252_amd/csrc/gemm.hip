@@ -341,6 +341,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f16_kernel(GemmArgs g) {
       }
     }
   } else {
+    [[maybe_unused]] bool sat = false;        // an fp16 output was clamped
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
       const int row = wrow0 + i * 32 + frow;
@@ -414,6 +415,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f16_kernel(GemmArgs g) {
               const float lo1 = v[1] * cs[2] - v[3] * cs[3], hi1 = v[3] * cs[2] + v[1] * cs[3];
               v[0] = lo0; v[1] = lo1; v[2] = hi0; v[3] = hi1;
             }
+            // q is fp16; cached keys and values are bf16 but enter the attention products as fp16
+#pragma unroll
+            for (int r = 0; r < 4; ++r) sat |= f16_out_of_range(v[r]);
             if (head < e.Hq) {
               uint16_t* qp = q_row + head * e.h;
               *(uint32_t*)(qp + d0) = pack_f16x2(v[0], v[1]);
@@ -435,13 +439,18 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f16_kernel(GemmArgs g) {
             }
           } else if constexpr (EPI == EPI_GELU_F16) {
             uint16_t* p = (uint16_t*)g.out + kblk_off(row, col, g.M);     // four columns never straddle a K block
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              v[r] = gelu_erf(v[r]);
+              sat |= f16_out_of_range(v[r]) && col + r < g.N;
+            }
             if (full) {
               u32x2 w;
-              w[0] = pack_f16x2(gelu_erf(v[0]), gelu_erf(v[1]));
-              w[1] = pack_f16x2(gelu_erf(v[2]), gelu_erf(v[3]));
+              w[0] = pack_f16x2(v[0], v[1]);
+              w[1] = pack_f16x2(v[2], v[3]);
               *(u32x2*)p = w;
             } else {
-              for (int r = 0; r < 4 && col + r < g.N; ++r) p[r] = f32_to_f16_bits(gelu_erf(v[r]));
+              for (int r = 0; r < 4 && col + r < g.N; ++r) p[r] = f32_to_f16_bits(v[r]);
             }
           } else if constexpr (EPI == EPI_SWIGLU_F16) {
             // weight rows come in blocks of 32: block 2b = gate rows [32b, 32b+32), block 2b+1 = the
@@ -451,14 +460,20 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f16_kernel(GemmArgs g) {
               const int f = ((wcol0 + j * 32) >> 1) + 8 * q + 4 * fhalf;
               u32x2 w;
               const int ju = j + 1 < TN ? j + 1 : j;
-              w[0] = pack_f16x2(silu(v[0]) * acc[i][ju][4 * q], silu(v[1]) * acc[i][ju][4 * q + 1]);
-              w[1] = pack_f16x2(silu(v[2]) * acc[i][ju][4 * q + 2], silu(v[3]) * acc[i][ju][4 * q + 3]);
+#pragma unroll
+              for (int r = 0; r < 4; ++r) {
+                v[r] = silu(v[r]) * acc[i][ju][4 * q + r];
+                sat |= f16_out_of_range(v[r]);
+              }
+              w[0] = pack_f16x2(v[0], v[1]);
+              w[1] = pack_f16x2(v[2], v[3]);
               *(u32x2*)((uint16_t*)g.out + kblk_off(row, f, g.M)) = w;
             }
           }
         }
       }
     }
+    if constexpr (EPI == EPI_QKV || EPI == EPI_GELU_F16 || EPI == EPI_SWIGLU_F16) flag_f16_range(sat, g.status);
   }
 }
 
@@ -479,7 +494,9 @@ __global__ void splitk_epilogue_kernel(GemmArgs g) {
     float* p = (float*)g.out + (size_t)row * g.ldo + col;
     *p = *p + v;
   } else if constexpr (EPI == EPI_GELU_F16) {
-    ((uint16_t*)g.out)[kblk_off(row, col, g.M)] = f32_to_f16_bits(gelu_erf(v));
+    v = gelu_erf(v);
+    flag_f16_range(f16_out_of_range(v), g.status);
+    ((uint16_t*)g.out)[kblk_off(row, col, g.M)] = f32_to_f16_bits(v);
   }
 }
 
@@ -575,7 +592,8 @@ hipError_t rl_gemm_splitk(const GemmArgs& g, int epi, int variant, hipStream_t s
   return hipGetLastError();
 }
 
-// Tile shape by problem size (measured on MI355X): the largest tile that still gives every CU work.
+// Tile shape by problem size (measured on MI355X): the largest tile that still gives every CU work.  The K split is
+// the caller's (g.splits >= 2 with g.ws set), never chosen here: it fixes the order of the sums.
 hipError_t rl_gemm(const GemmArgs& g, int epi, hipStream_t s) {
   auto tiles = [&](int bm, int bn) { return (long long)((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn); };
   const bool wide_only = (epi == EPI_SWIGLU_F16 || epi == EPI_LMHEAD);   // a wave must own 64 columns
@@ -584,20 +602,6 @@ hipError_t rl_gemm(const GemmArgs& g, int epi, hipStream_t s) {
   else if (tiles(256, 128) >= 200) variant = 5;
   else if (tiles(128, 128) >= 400 || wide_only) variant = 0;
   else variant = 7;
-  if (variant == 7 && g.ws && epi != EPI_QKV) {
-    // few 64x128 tiles (three fit on a CU): cut K so that about 800 blocks exist, each keeping >= 4 K tiles;
-    // with more than one tile per CU already, only a long K is worth the second pass over the partial sums
-    const long long t = tiles(64, 128);
-    const int nk = (g.K + BK - 1) / BK;
-    long long splits = (t <= 256 || (t <= 400 && nk >= 96)) ? (800 + t / 2) / t : 1;
-    splits = std::min<long long>(splits, 8);
-    splits = std::min<long long>(splits, nk / (t <= 256 ? 4 : 8));
-    splits = std::min<long long>(splits, (long long)(g.ws_elems / ((size_t)g.M * g.N)));
-    if (splits >= 2) {
-      GemmArgs h = g;
-      h.splits = (int)splits;
-      return rl_gemm_splitk(h, epi, 7, s);
-    }
-  }
+  if (g.splits >= 2 && g.ws) return rl_gemm_splitk(g, epi, wide_only ? 0 : 7, s);
   return rl_gemm_variant(g, epi, variant, s);
 }

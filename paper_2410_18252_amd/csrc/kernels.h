@@ -78,7 +78,10 @@ struct GemmArgs {
   // split-K scratch (nullable: no split-K): fp32 [splits, M, N], ws_elems floats available
   float* ws; size_t ws_elems; int splits;
   QkvEpi qe;                    // EPI_QKV only (out / ldo unused)
+  unsigned* status;             // nullable: receives RLGEN_FAULT_RANGE when an fp16 (or cached bf16, later read as fp16)
+                                // output of the epilogue exceeds fp16's range and is clamped
 };
+// tile shape chosen from the problem size; g.splits >= 2 (with g.ws) cuts K into that many parts (rl_gemm_splitk)
 hipError_t rl_gemm(const GemmArgs& g, int epi, hipStream_t s);
 // the same with an explicit tile shape (tuning and tests): 0 = 128x128, 1 = 256x128, 2 = 256x256, ...
 hipError_t rl_gemm_variant(const GemmArgs& g, int epi, int variant, hipStream_t s);
@@ -138,9 +141,10 @@ hipError_t rl_embed(float* x, const uint16_t* E, const int* tokens, const int* t
 // LayerNorm / RMSNorm of fp32 rows into fp16.  out2/g2/b2 nullable (second normalisation of the same
 // row with other gains, NeoX); b1 null selects RMSNorm.  row_index nullable: source row of output row i.
 // Outputs are K-block major matrices of out_rows rows; output row i goes to row out_row0 + i.
+// status (nullable): receives RLGEN_FAULT_RANGE if a normalised value does not fit fp16 (it is clamped).
 hipError_t rl_norm(const float* x, const int* row_index, int rows, int d, float eps, const float* g1,
                    const float* b1, uint16_t* out1, const float* g2, const float* b2, uint16_t* out2,
-                   int out_rows, int out_row0, hipStream_t s);
+                   int out_rows, int out_row0, unsigned* status, hipStream_t s);
 
 // Rotary + KV write.  qkv fp32 [rows, (Hq + 2 Hkv) h] (bias already added) ->
 //   q fp16 [rows, Hq h] rotated; k (rotated) and v written as bf16 to the cache of `ncopy` consecutive cache

@@ -1,7 +1,7 @@
 // Host side of librlgen.so: configuration checks, workspace carving, weight packing and the
 // scheduler that turns rlgen_generate / rlgen_score into kernel launches on the caller's stream.
-// No device memory is allocated here; the host allocations are the context, two pinned buffers (per-call
-// sequence metadata; the flags and index lists of EOS compaction), two internal streams and a few events.
+// No device memory is allocated here (no hipMalloc, no hipFree); the host allocations are the context, two pinned
+// buffers (per-call sequence metadata; the flags and index lists of EOS compaction), two internal streams and a few events.
 #include "../../include/rlgen.h"
 #include "kernels.h"
 
@@ -351,18 +351,18 @@ int jobs_of(const rlgen_ctx* c, int len) {
 
 enum { G_QKV = 0, G_O = 1, G_UP = 2, G_DOWN = 3, G_LMHEAD = 4 };
 
+// variant < 0: the tile shape follows from the problem size.  splits >= 2 needs g.ws.
 hipError_t run_choice(const GemmArgs& g, int epi, int variant, int splits, hipStream_t st) {
-  if (variant < 0) return rl_gemm(g, epi, st);
-  if (splits >= 2) {
-    GemmArgs h = g;
-    h.splits = splits;
-    return rl_gemm_splitk(h, epi, variant, st);
-  }
-  return rl_gemm_variant(g, epi, variant, st);
+  GemmArgs h = g;
+  h.splits = (splits >= 2 && g.ws) ? splits : 1;
+  if (variant < 0) return rl_gemm(h, epi, st);
+  if (h.splits >= 2) return rl_gemm_splitk(h, epi, variant, st);
+  return rl_gemm_variant(h, epi, variant, st);
 }
 hipError_t gemm(rlgen_ctx* c, int which, bool decode, const GemmArgs& g, int epi, hipStream_t st) {
-  const auto& ch = c->tuned[decode ? (c->half_rows ? 2 : 0) : 1][which];
-  return run_choice(g, epi, ch.variant, ch.splits, st);
+  const int mode = decode ? (c->half_rows ? 2 : 0) : 1;
+  // the K split is that of the mode's family (decode / prompt pass) even where a mode was not tuned
+  return run_choice(g, epi, c->tuned[mode][which].variant, c->tuned[decode ? 0 : 1][which].splits, st);
 }
 
 QkvEpi qkv_epilogue(const RopeArgs& r, uint16_t* kvstage) {
@@ -385,7 +385,7 @@ struct DecView {
   const int* row_order = nullptr;
 };
 // Below this many sequences a decode step is too short to gain from running as two concurrent halves.
-constexpr int DECODE_SPLIT_MIN_SEQS = 256;     // RLGEN_DECODE_SPLIT_MIN overrides it at context creation
+constexpr int DECODE_SPLIT_MIN_SEQS = 256;     // rlgen_set_decode_split_min replaces it
 
 int run_layers(rlgen_ctx* c, int rows, bool decode, int t, int ncopy, bool use_cache_layers, int njobs, hipStream_t st,
                DecView dv = DecView{0, 0, 0}) {
@@ -396,11 +396,12 @@ int run_layers(rlgen_ctx* c, int rows, bool decode, int t, int ncopy, bool use_c
   for (int l = 0; l < m.n_layers; ++l) {
     const LayerW& L = c->layers[l];
     uint16_t* kvl = c->kv + (use_cache_layers ? (size_t)c->lay.layer_stride * l : 0);
-    if (llama) HIPCHK(rl_norm(c->x, nullptr, rows, d, m.norm_eps, L.n1g, nullptr, c->n1, nullptr, nullptr, nullptr, rows, 0, st));
-    else HIPCHK(rl_norm(c->x, nullptr, rows, d, m.norm_eps, L.n1g, L.n1b, c->n1, L.n2g, L.n2b, c->n2, rows, 0, st));
+    if (llama) HIPCHK(rl_norm(c->x, nullptr, rows, d, m.norm_eps, L.n1g, nullptr, c->n1, nullptr, nullptr, nullptr, rows, 0, c->status, st));
+    else HIPCHK(rl_norm(c->x, nullptr, rows, d, m.norm_eps, L.n1g, L.n1b, c->n1, L.n2g, L.n2b, c->n2, rows, 0, c->status, st));
     GemmArgs g{};
     g.A = c->n1; g.W = L.wqkv; g.M = rows; g.N = nqkv; g.K = d;
     g.bias = llama ? nullptr : L.bqkv; g.out = c->qkv; g.ldo = nqkv; g.ws = c->splitk; g.ws_elems = c->splitk_elems;
+    g.status = c->status;
     RopeArgs r{};
     r.qkv = c->qkv; r.rows = rows; r.Hq = m.n_q_heads; r.Hkv = m.n_kv_heads; r.h = h; r.r = m.rotary_dim;
     r.table = c->rope; r.q = c->q; r.kv = kvl; r.lay = c->lay; r.kv_off = c->d_kv_off; r.kv_cap = c->d_kv_cap;
@@ -458,10 +459,11 @@ int run_layers(rlgen_ctx* c, int rows, bool decode, int t, int ncopy, bool use_c
     g.A = c->attn; g.W = L.wo; g.M = rows; g.N = d; g.K = qd;
     g.bias = llama ? nullptr : L.bo; g.out = c->x; g.ldo = d; g.ws = c->splitk; g.ws_elems = c->splitk_elems;
     HIPCHK(gemm(c, G_O, decode, g, EPI_RESID, st));
-    if (llama) HIPCHK(rl_norm(c->x, nullptr, rows, d, m.norm_eps, L.n2g, nullptr, c->n2, nullptr, nullptr, nullptr, rows, 0, st));
+    if (llama) HIPCHK(rl_norm(c->x, nullptr, rows, d, m.norm_eps, L.n2g, nullptr, c->n2, nullptr, nullptr, nullptr, rows, 0, c->status, st));
     g = GemmArgs{};
     g.A = c->n2; g.W = L.wup; g.M = rows; g.N = llama ? 2 * F : F; g.K = d;
     g.bias = llama ? nullptr : L.bup; g.out = c->act; g.ldo = F; g.ws = c->splitk; g.ws_elems = c->splitk_elems;
+    g.status = c->status;
     HIPCHK(gemm(c, G_UP, decode, g, llama ? EPI_SWIGLU_F16 : EPI_GELU_F16, st));
     g = GemmArgs{};
     g.A = c->act; g.W = L.wdown; g.M = rows; g.N = d; g.K = F;
@@ -475,7 +477,7 @@ int run_layers(rlgen_ctx* c, int rows, bool decode, int t, int ncopy, bool use_c
 int final_norm(rlgen_ctx* c, const int* row_index, int rows, int out_rows, int out_row0, hipStream_t st) {
   const rlgen_model_cfg& m = c->cfg;
   HIPCHK(rl_norm(c->x, row_index, rows, m.d_model, m.norm_eps, c->fng, m.arch == RLGEN_ARCH_LLAMA ? nullptr : c->fnb, c->hfin,
-                 nullptr, nullptr, nullptr, out_rows, out_row0, st));
+                 nullptr, nullptr, nullptr, out_rows, out_row0, c->status, st));
   return RLGEN_OK;
 }
 
@@ -513,9 +515,43 @@ double weight_bytes_of(const rlgen_model_cfg& m) {
   return 2.0 * (per_layer * m.n_layers + (double)m.vocab * m.d_model);
 }
 
-// Times every tile shape (and K split) on each linear layer of this model at the row counts it will see --
-// max_seqs rows for a decode step, a full chunk for the prompt pass -- and keeps the fastest.  Inputs are the
-// activation scratch buffers filled with pseudo-random fp16; outputs land in scratch.
+// How the sum over a linear layer's inner dimension is cut (split-K): a function of the layer's shape and of the
+// context's capacity alone, never of a timing, so that a sequence's sums are taken in the same order whichever tile
+// shapes a context picked and whether a decode step covers the whole batch, half of it, or what EOS compaction left.
+// `rows` is the row count the launches are sized for.  The cut pays when 64x128 tiles leave CUs idle: about two blocks
+// per CU, every part keeping at least 4 K tiles, at most 8 parts, and the fp32 partial sums must fit the scratch.
+int split_rule(int rows, int cap_rows, int N, int K, int epi, size_t ws_elems) {
+  if (epi != EPI_F32 && epi != EPI_RESID && epi != EPI_GELU_F16) return 1;      // the other epilogues have no two-pass form
+  const long long t = (long long)((rows + 63) / 64) * ((N + 127) / 128);
+  const int nk = (K + 63) / 64;
+  long long sp = (512 + t / 2) / t;
+  sp = std::min<long long>(sp, 8);
+  sp = std::min<long long>(sp, nk / 4);
+  sp = std::min<long long>(sp, (long long)(ws_elems / ((size_t)cap_rows * N)));
+  return sp >= 2 ? (int)sp : 1;
+}
+
+struct Events3 {      // three timing events, destroyed on every path out of the tuner
+  hipEvent_t e[3] = {nullptr, nullptr, nullptr};
+  bool create() {
+    for (auto& x : e) if (hipEventCreate(&x) != hipSuccess) return false;
+    return true;
+  }
+  ~Events3() { for (auto x : e) if (x) (void)hipEventDestroy(x); }
+};
+
+// Is a half-batch decode worth preparing for: the context could hold a batch that decodes as two halves (see
+// rlgen_generate), i.e. a full cache would outweigh the weights four times.
+bool capacity_splits_decode(const rlgen_ctx* c) {
+  const rlgen_model_cfg& m = c->cfg;
+  if (!c->have_streams || m.max_seqs < DECODE_SPLIT_MIN_SEQS) return false;
+  return 4.0 * m.n_kv_heads * m.head_dim * (double)m.max_kv_tokens * m.n_layers >= 4.0 * weight_bytes_of(m);
+}
+
+// Fixes the K split of every linear layer by split_rule, then times the tile shapes on each layer at the row counts it
+// will see -- max_seqs rows (or half of them) for a decode step, a full chunk for the prompt pass -- and keeps the
+// fastest.  Tile shape does not change the order of any sum.  Inputs are the activation scratch buffers filled with
+// pseudo-random fp16; outputs land in scratch.
 int tune_gemms(rlgen_ctx* c, hipStream_t st) {
   const rlgen_model_cfg& m = c->cfg;
   const bool llama = m.arch == RLGEN_ARCH_LLAMA;
@@ -532,31 +568,28 @@ int tune_gemms(rlgen_ctx* c, hipStream_t st) {
                        c->d_kv_cap, c->R, tseq, std::min(32, m.max_seq_len));
     HIPCHK(hipGetLastError());
   }
-  hipEvent_t e0, e1, e2;
-  HIPCHK(hipEventCreate(&e0));
-  HIPCHK(hipEventCreate(&e1));
-  HIPCHK(hipEventCreate(&e2));
+  Events3 ev;
+  if (!ev.create()) return RLGEN_ERR_DEVICE;
+  hipEvent_t e0 = ev.e[0], e1 = ev.e[1], e2 = ev.e[2];
   const LayerW& L = c->layers[0];
   int rc = RLGEN_OK;
-  // the half-batch decode is worth tuning when a full cache would outweigh the weights four times (the run-time
-  // criterion of rlgen_generate, applied to the context's capacity)
-  bool tune_half = c->have_streams && m.max_seqs >= c->split_min_seqs;
-  if (tune_half && c->split_min_seqs == DECODE_SPLIT_MIN_SEQS)
-    tune_half = 4.0 * m.n_kv_heads * m.head_dim * (double)m.max_kv_tokens * m.n_layers >= 4.0 * weight_bytes_of(m);
+  const bool tune_half = capacity_splits_decode(c);
+  // rows a decode launch is sized for
+  const int dec_rows_eff = tune_half ? (m.max_seqs + 1) / 2 : m.max_seqs;
   for (int which = 0; which < 5; ++which) c->tuned[2][which] = {-1, 1};
   // The neighbour of the half-batch timing runs: the decode attention of the other half, over half a full batch of
-  // sequences that each hold their share of the cache (all zeros), twice in a row.
+  // sequences that each hold their share of the cache (all zeros), twice in a row.  Its three per-sequence arrays
+  // live in the (idle) index area of EOS compaction and are uploaded from that feature's pinned buffer.
   AttnArgs nb{};
-  int* nb_meta = nullptr;
   float nb_ms = 0.f;
   if (tune_half) {
     const int Sh = (m.max_seqs + 1) / 2;
     const int cap = (int)std::min<long long>(m.max_kv_tokens / m.max_seqs, m.max_seq_len) / 32 * 32;
     if (cap >= 32 && (long long)Sh * cap * 2 * m.n_kv_heads * m.head_dim <= c->lay.layer_stride) {
-      std::vector<int> meta(3 * (size_t)Sh);
+      int* meta = c->h_fin;                       // 4 * max_seqs ints, pinned
+      int* nb_meta = c->d_cmp;                    // 8 * max_seqs ints
       for (int i = 0; i < Sh; ++i) { meta[i] = i * cap; meta[Sh + i] = cap; meta[2 * Sh + i] = cap - 1; }
-      bool ok = hipMalloc((void**)&nb_meta, meta.size() * sizeof(int)) == hipSuccess &&
-                hipMemcpy(nb_meta, meta.data(), meta.size() * sizeof(int), hipMemcpyHostToDevice) == hipSuccess &&
+      bool ok = hipMemcpyAsync(nb_meta, meta, (size_t)3 * Sh * sizeof(int), hipMemcpyHostToDevice, st) == hipSuccess &&
                 rl_fill_zero(c->kv, (size_t)Sh * cap * 2 * m.n_kv_heads * m.head_dim * 2, st) == hipSuccess;
       nb.q = c->q; nb.q_ld = qd; nb.out = (uint16_t*)c->qkv; nb.out_rows = Sh; nb.kv = c->kv; nb.lay = c->lay;
       nb.kv_off = nb_meta; nb.kv_cap = nb_meta + Sh; nb.ctx_base = nb_meta + 2 * Sh; nb.ctx_add = 1; nb.S = Sh;
@@ -566,11 +599,9 @@ int tune_gemms(rlgen_ctx* c, hipStream_t st) {
              rl_attention_decode(nb, st) == hipSuccess && hipEventRecord(e1, st) == hipSuccess &&
              hipEventSynchronize(e1) == hipSuccess && hipEventElapsedTime(&nb_ms, e0, e1) == hipSuccess;
       }
-      if (!ok) rc = RLGEN_ERR_DEVICE;
+      if (!ok) return RLGEN_ERR_DEVICE;
     }
   }
-  // The half-batch decode is tuned first; the whole-batch decode may then pick another tile shape but keeps the
-  // K split, so that a sequence's arithmetic (the order of its sums) does not depend on how the batch was cut.
   const int modes[3] = {2, 0, 1};
   for (int mi = tune_half ? 0 : 1; mi < 3 && rc == RLGEN_OK; ++mi) {
     const int mode = modes[mi];
@@ -604,39 +635,25 @@ int tune_gemms(rlgen_ctx* c, hipStream_t st) {
                        g.partial = c->partial; g.ws = nullptr; epi = EPI_LMHEAD; break;
       }
       const bool wide_only = epi == EPI_SWIGLU_F16 || epi == EPI_LMHEAD;
-      const int nk = (g.K + 63) / 64;
-      struct Cand { int variant, splits; };
-      std::vector<Cand> cands = {{0, 1}, {3, 1}, {5, 1}};
-      if (mode == 2) { cands.push_back({1, 1}); cands.push_back({4, 1}); }     // beside attention other shapes can win
+      // the K split: by rule, the same for every decode mode
+      const int splits = !g.ws ? 1 : mode == 1 ? split_rule(c->R, c->R, g.N, g.K, epi, g.ws_elems)
+                                               : split_rule(dec_rows_eff, m.max_seqs, g.N, g.K, epi, g.ws_elems);
+      std::vector<int> cands = {0, 5};
+      if (splits == 1) cands.push_back(3);
+      if (mode == 2 && splits == 1) { cands.push_back(1); cands.push_back(4); }     // beside attention other shapes can win
       if (!wide_only) {
-        cands.push_back({7, 1});
-        if (g.K % 64 == 0 && g.K >= 2048 && g.M <= 2048) cands.push_back({8, 1});     // deeper load pipeline: pays on a long K with few tiles
-        const long long t7 = (long long)((g.M + 63) / 64) * ((g.N + 127) / 128);
-        const long long t5 = (long long)((g.M + 255) / 256) * ((g.N + 127) / 128);
-        if (g.ws && t7 <= 1024 && epi != EPI_QKV)
-          for (int sp : {2, 3, 4, 6, 8}) {
-            // what the half batch picks the whole batch must be able to run too (same K split)
-            if (nk / sp < 4 || (size_t)sp * (mode == 2 ? m.max_seqs : g.M) * g.N > g.ws_elems) continue;
-            cands.push_back({7, sp});
-            if (t5 * sp <= 256) cands.push_back({5, sp});
-          }
-      }
-      if (mode == 0 && tune_half) {
-        const int keep = c->tuned[2][which].splits;
-        std::vector<Cand> same;
-        for (const Cand& cd : cands) if (cd.splits == keep) same.push_back(cd);
-        if (same.empty()) same.push_back({7, keep});   // fits: the half-batch candidates were sized for max_seqs rows
-        cands = same;
+        cands.push_back(7);
+        if (g.K % 64 == 0 && g.K >= 2048 * splits && g.M <= 2048) cands.push_back(8);     // deeper load pipeline: pays on a long K with few tiles
       }
       // clocks drift with load, so the candidates take turns: one warm-up each, then three rounds in which
       // every candidate is timed over two launches; the smallest total wins
       std::vector<float> total(cands.size(), 0.f);
       bool ok = true;
-      for (size_t i = 0; ok && i < cands.size(); ++i) ok = run_choice(g, epi, cands[i].variant, cands[i].splits, st) == hipSuccess;
+      for (size_t i = 0; ok && i < cands.size(); ++i) ok = run_choice(g, epi, cands[i], splits, st) == hipSuccess;
       for (int round = 0; ok && round < 3; ++round)
         for (size_t i = 0; ok && i < cands.size(); ++i) {
           ok = hipEventRecord(e0, st) == hipSuccess;
-          for (int r = 0; ok && r < 2; ++r) ok = run_choice(g, epi, cands[i].variant, cands[i].splits, st) == hipSuccess;
+          for (int r = 0; ok && r < 2; ++r) ok = run_choice(g, epi, cands[i], splits, st) == hipSuccess;
           if (ok) ok = hipEventRecord(e1, st) == hipSuccess && hipEventSynchronize(e1) == hipSuccess;
           float ms = 0.f;
           if (ok) ok = hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
@@ -664,7 +681,7 @@ int tune_gemms(rlgen_ctx* c, hipStream_t st) {
                hipStreamWaitEvent(c->gstream[1], c->ev_fork, 0) == hipSuccess &&
                rl_attention_decode(nb, c->gstream[0]) == hipSuccess && rl_attention_decode(nb, c->gstream[0]) == hipSuccess;
           for (int r = 0; ok && r < reps; ++r)
-            ok = run_choice(g, epi, cands[i].variant, cands[i].splits, c->gstream[1]) == hipSuccess;
+            ok = run_choice(g, epi, cands[i], splits, c->gstream[1]) == hipSuccess;
           if (ok) ok = hipEventRecord(e2, c->gstream[1]) == hipSuccess;
           for (int gi = 0; ok && gi < 2; ++gi)
             ok = hipEventRecord(c->ev_join[gi], c->gstream[gi]) == hipSuccess &&
@@ -702,20 +719,9 @@ int tune_gemms(rlgen_ctx* c, hipStream_t st) {
       // the joint timing is the noisier one: the candidate that is fastest alone is kept unless another one is clearly
       // cheaper in company
       if (score[bi] > 0.985f * score[alone]) bi = alone;
-      rlgen_ctx::GemmChoice pick{cands[bi].variant, cands[bi].splits};
-      if (getenv("RLGEN_DEBUG_TUNE")) {
-        fprintf(stderr, "rlgen tune: mode %d gemm %d M=%d N=%d K=%d:", mode, which, g.M, g.N, g.K);
-        for (size_t i = 0; i < cands.size(); ++i)
-          fprintf(stderr, " v%d/s%d=%.0fus(%.0f)%s", cands[i].variant, cands[i].splits, total[i] / 6 * 1e3, (mode == 2 ? (score[i] > 1e29f ? 0.f : score[i]) : score[i] / 6) * 1e3, i == bi ? "*" : "");
-        fprintf(stderr, "\n");
-      }
-      c->tuned[mode][which] = pick;
+      c->tuned[mode][which] = {cands[bi], splits};
     }
   }
-  (void)hipEventDestroy(e0);
-  (void)hipEventDestroy(e1);
-  (void)hipEventDestroy(e2);
-  if (nb_meta) (void)hipFree(nb_meta);
   return rc;
 }
 
@@ -773,6 +779,7 @@ int score_impl(rlgen_ctx* c, const int32_t* seqs, const int32_t* seq_lens, const
   if (N < 1 || stride < 1) return RLGEN_ERR_BAD_ARG;
   if (!(temperature > 0.f) || !std::isfinite(temperature)) return RLGEN_ERR_BAD_ARG;
   if (N > m.max_seqs) return RLGEN_ERR_CAPACITY;
+  if ((long long)N * stride > INT32_MAX) return RLGEN_ERR_BAD_ARG;          // token and output offsets are 32-bit
   for (int n = 0; n < N; ++n) {
     if (seq_lens[n] < 1 || seq_lens[n] > stride) return RLGEN_ERR_BAD_ARG;
     if (seq_lens[n] > m.max_seq_len) return RLGEN_ERR_CAPACITY;
@@ -949,26 +956,19 @@ int rlgen_create(const rlgen_model_cfg* cfg, const rlgen_weights* weights, void*
     return fail(RLGEN_ERR_DEVICE);
   c->timed = true;
   c->eos_token = -1;
-  {
-    const char* e = getenv("RLGEN_EOS_COMPACT_EVERY");
-    c->eos_every = e ? atoi(e) : 8;
-    if (c->eos_every < 0) c->eos_every = 0;
-  }
+  c->eos_every = 8;
   if (hipHostMalloc((void**)&c->h_fin, (size_t)4 * S * sizeof(int), hipHostMallocDefault) != hipSuccess) return fail(RLGEN_ERR_DEVICE);
   c->h_lists = c->h_fin + S;
   // two internal streams (default priority) for the halves of a large decode batch
-  if (!getenv("RLGEN_NO_DECODE_SPLIT")) {
-    if (hipStreamCreateWithFlags(&c->gstream[0], hipStreamNonBlocking) != hipSuccess ||
-        hipStreamCreateWithFlags(&c->gstream[1], hipStreamNonBlocking) != hipSuccess ||
-        hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) != hipSuccess ||
-        hipEventCreateWithFlags(&c->ev_join[0], hipEventDisableTiming) != hipSuccess ||
-        hipEventCreateWithFlags(&c->ev_join[1], hipEventDisableTiming) != hipSuccess)
-      return fail(RLGEN_ERR_DEVICE);
-    c->have_streams = true;
-    const char* e = getenv("RLGEN_DECODE_SPLIT_MIN");
-    c->split_min_seqs = e && atoi(e) >= 2 ? atoi(e) : DECODE_SPLIT_MIN_SEQS;
-  }
-  c->fused_qkv = cfg->rotary_dim % 4 == 0 && !getenv("RLGEN_UNFUSED_QKV");
+  if (hipStreamCreateWithFlags(&c->gstream[0], hipStreamNonBlocking) != hipSuccess ||
+      hipStreamCreateWithFlags(&c->gstream[1], hipStreamNonBlocking) != hipSuccess ||
+      hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&c->ev_join[0], hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&c->ev_join[1], hipEventDisableTiming) != hipSuccess)
+    return fail(RLGEN_ERR_DEVICE);
+  c->have_streams = true;
+  c->split_min_seqs = DECODE_SPLIT_MIN_SEQS;
+  c->fused_qkv = cfg->rotary_dim % 4 == 0;
   rc = pack_weights(c, weights, st);
   if (rc) return fail(rc);
   if (rl_rope_table(c->rope, cfg->max_seq_len, cfg->rotary_dim, cfg->rope_theta, st) != hipSuccess) return fail(RLGEN_ERR_DEVICE);
@@ -996,6 +996,7 @@ int rlgen_generate(rlgen_ctx* c, const int32_t* prompts, const int32_t* prompt_l
   if (B < 1 || k < 1 || max_new < 1 || prompt_stride < 1) return RLGEN_ERR_BAD_ARG;
   if (!(temperature >= 0.f) || !std::isfinite(temperature)) return RLGEN_ERR_BAD_ARG;      // 0 = greedy
   if ((long long)B * k > m.max_seqs) return RLGEN_ERR_CAPACITY;
+  if ((long long)B * prompt_stride > INT32_MAX || (long long)B * k * max_new > INT32_MAX) return RLGEN_ERR_BAD_ARG;   // 32-bit offsets
   // shared prompt cache: one stream per prompt plus one short stream of new tokens per sequence; the k samples
   // of a prompt and the query heads of a kv head share the 16 columns of the attention MFMA
   const bool share = m.share_prompt_kv != 0;
@@ -1208,7 +1209,7 @@ int rlgen_debug_sample(rlgen_ctx* c, const float* hidden, int32_t R, float tempe
   hipStream_t st = (hipStream_t)hip_stream;
   const rlgen_model_cfg& m = c->cfg;
   HIPCHK(rl_norm(hidden, nullptr, R, m.d_model, m.norm_eps, c->fng, m.arch == RLGEN_ARCH_LLAMA ? nullptr : c->fnb, c->hfin,
-                 nullptr, nullptr, nullptr, R, 0, st));
+                 nullptr, nullptr, nullptr, R, 0, c->status, st));
   return sample_rows(c, R, temperature, uniforms, forced, 1, 0, tokens, token_logprobs, nullptr, st);
 }
 
@@ -1289,12 +1290,47 @@ int rlgen_set_decode_split(rlgen_ctx* c, int32_t on) {
   return RLGEN_OK;
 }
 
-int rlgen_status(rlgen_ctx* c, void* hip_stream) {
+int rlgen_status_bits(rlgen_ctx* c, void* hip_stream, uint32_t* faults) {
   if (!c) return RLGEN_ERR_NULL;
   unsigned v = 0;
   HIPCHK(hipMemcpyAsync(&v, c->status, sizeof(v), hipMemcpyDeviceToHost, (hipStream_t)hip_stream));
   HIPCHK(hipStreamSynchronize((hipStream_t)hip_stream));
+  if (faults) *faults = v;
   return v ? RLGEN_ERR_DEVICE : RLGEN_OK;
+}
+
+int rlgen_status(rlgen_ctx* c, void* hip_stream) { return rlgen_status_bits(c, hip_stream, nullptr); }
+
+int rlgen_set_eos_compaction(rlgen_ctx* c, int32_t every) {
+  if (!c) return RLGEN_ERR_NULL;
+  if (every < 0) return RLGEN_ERR_BAD_ARG;
+  c->eos_every = every;
+  return RLGEN_OK;
+}
+
+int rlgen_set_decode_split_min(rlgen_ctx* c, int32_t min_seqs) {
+  if (!c) return RLGEN_ERR_NULL;
+  if (min_seqs != 0 && min_seqs < 2) return RLGEN_ERR_BAD_ARG;
+  c->split_min_seqs = min_seqs ? min_seqs : DECODE_SPLIT_MIN_SEQS;
+  return RLGEN_OK;
+}
+
+int rlgen_debug_get_gemm(rlgen_ctx* c, int32_t mode, int32_t which, int32_t* variant, int32_t* splits) {
+  if (!c) return RLGEN_ERR_NULL;
+  if (mode < 0 || mode > 2 || which < 0 || which > 4) return RLGEN_ERR_BAD_ARG;
+  if (variant) *variant = c->tuned[mode][which].variant;
+  if (splits) *splits = c->tuned[mode == 1 ? 1 : 0][which].splits;
+  return RLGEN_OK;
+}
+
+int rlgen_debug_set_gemm(rlgen_ctx* c, int32_t mode, int32_t which, int32_t variant) {
+  if (!c) return RLGEN_ERR_NULL;
+  if (mode < 0 || mode > 2 || which < 0 || which > 4 || variant < -1 || variant > 8) return RLGEN_ERR_BAD_ARG;
+  // the fused gate/up and LM-head epilogues need a wave to own 64 columns: not the 64-column-per-wave-pair shapes
+  const bool wide_only = which == G_LMHEAD || (which == G_UP && c->cfg.arch == RLGEN_ARCH_LLAMA);
+  if (wide_only && variant >= 6) return RLGEN_ERR_BAD_ARG;
+  c->tuned[mode][which].variant = variant;
+  return RLGEN_OK;
 }
 
 const char* rlgen_strerror(int code) {

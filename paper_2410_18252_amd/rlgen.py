@@ -26,7 +26,10 @@ DTYPE_F32, DTYPE_BF16 = 0, 1
 
 EXPORTS = ["rlgen_workspace_bytes", "rlgen_create", "rlgen_update_weights", "rlgen_generate", "rlgen_score",
            "rlgen_debug_logits", "rlgen_debug_sample", "rlgen_sequence_logprob", "rlgen_dpo_loss", "rlgen_select_pairs", "rlgen_proximal_rloo",
-           "rlgen_get_timings", "rlgen_set_profiling", "rlgen_set_decode_split", "rlgen_set_eos", "rlgen_set_score_groups", "rlgen_status", "rlgen_strerror", "rlgen_destroy"]
+           "rlgen_get_timings", "rlgen_set_profiling", "rlgen_set_decode_split", "rlgen_set_decode_split_min", "rlgen_set_eos",
+           "rlgen_set_eos_compaction", "rlgen_set_score_groups", "rlgen_debug_get_gemm", "rlgen_debug_set_gemm", "rlgen_status",
+           "rlgen_status_bits", "rlgen_strerror", "rlgen_destroy"]
+FAULT_TOKEN, FAULT_UNIFORM, FAULT_GROUP, FAULT_RANGE = 1, 2, 4, 8
 
 
 class ModelCfg(C.Structure):
@@ -85,6 +88,16 @@ lib.rlgen_set_profiling.restype = C.c_int
 lib.rlgen_set_profiling.argtypes = [_vp, _i32]
 lib.rlgen_status.restype = C.c_int
 lib.rlgen_status.argtypes = [_vp, _vp]
+lib.rlgen_status_bits.restype = C.c_int
+lib.rlgen_status_bits.argtypes = [_vp, _vp, C.POINTER(C.c_uint32)]
+lib.rlgen_set_eos_compaction.restype = C.c_int
+lib.rlgen_set_eos_compaction.argtypes = [_vp, _i32]
+lib.rlgen_set_decode_split_min.restype = C.c_int
+lib.rlgen_set_decode_split_min.argtypes = [_vp, _i32]
+lib.rlgen_debug_get_gemm.restype = C.c_int
+lib.rlgen_debug_get_gemm.argtypes = [_vp, _i32, _i32, C.POINTER(_i32), C.POINTER(_i32)]
+lib.rlgen_debug_set_gemm.restype = C.c_int
+lib.rlgen_debug_set_gemm.argtypes = [_vp, _i32, _i32, _i32]
 lib.rlgen_strerror.restype = C.c_char_p
 lib.rlgen_strerror.argtypes = [C.c_int]
 lib.rlgen_destroy.restype = None
@@ -314,3 +327,29 @@ def rlgen_set_profiling(p: Policy, every: int):
 
 def rlgen_status(p: Policy) -> int:
     return int(lib.rlgen_status(p.ctx, _stream()))
+
+
+def rlgen_status_bits(p: Policy) -> int:
+    """The sticky fault bits (FAULT_*); synchronises the current stream."""
+    bits = C.c_uint32()
+    lib.rlgen_status_bits(p.ctx, _stream(), C.byref(bits))
+    return int(bits.value)
+
+
+def rlgen_set_eos_compaction(p: Policy, every: int):
+    _check(lib.rlgen_set_eos_compaction(p.ctx, int(every)), "rlgen_set_eos_compaction")
+
+
+def rlgen_set_decode_split_min(p: Policy, min_seqs: int):
+    _check(lib.rlgen_set_decode_split_min(p.ctx, int(min_seqs)), "rlgen_set_decode_split_min")
+
+
+def rlgen_debug_get_gemm(p: Policy, mode: int, which: int):
+    """(tile-shape variant, K split) of linear layer `which` in `mode`."""
+    v, sp = _i32(), _i32()
+    _check(lib.rlgen_debug_get_gemm(p.ctx, mode, which, C.byref(v), C.byref(sp)), "rlgen_debug_get_gemm")
+    return v.value, sp.value
+
+
+def rlgen_debug_set_gemm(p: Policy, mode: int, which: int, variant: int):
+    _check(lib.rlgen_debug_set_gemm(p.ctx, mode, which, int(variant)), "rlgen_debug_set_gemm")

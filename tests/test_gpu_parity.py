@@ -8,9 +8,9 @@ import pytest
 import torch
 
 from oracle import decoder as O
-from workloads import get_config, make_prompts, make_uniforms, make_weights, Weights
+from workloads import get_config, make_prompts, make_uniforms, make_weights, ModelShape, Weights
 from gpu_util import (report, GPU_SHAPES, MARGIN, TOL_LOGITS, TOL_LOGPROB, R, dev_f32, dev_i32, make_policy,
-                      oracle_generate_batch, padded, scaled_bf16_weights)
+                      oracle_generate_batch, padded, reference_decoder, scaled_bf16_weights)
 
 pytestmark = pytest.mark.gpu
 
@@ -25,7 +25,7 @@ def small(request):
     W = scaled_bf16_weights(m)
     # max_batch_tokens == max_seq_len forces several chunks in prefill and scoring
     pol = make_policy(W, max_seqs=12, max_seq_len=80, max_batch_tokens=80)
-    yield m, W, O.Decoder(W, m), pol
+    yield m, W, reference_decoder(W, m), pol
     pol.close()
 
 
@@ -186,6 +186,150 @@ def test_sampler_in_isolation_on_exact_logits(peak):
     pol.close()
 
 
+BIG_VOCAB_SHAPES = {V: ModelShape(0, 1, 64, 4, 4, 16, 64, V, rotary_dim=4) for V in (50304, 128256)}
+
+
+@pytest.mark.parametrize("V", [50304, 128256])
+def test_sampler_group_search_at_full_vocabulary(V):
+    """The vocabularies of workloads 2-5 have 786 and 2004 groups of 64 columns, so every lane of the sampler's wave
+    owns a run of several groups (the small shapes have at most 16 groups: one per lane).  (1) All-zero model: every
+    logit is exactly 0 on both sides, token = floor(u V) and log-prob = -ln V with no rounding slack.  (2) Exact-logit
+    model (final-norm gain 0, one-hot bias: the LM-head input is e_j, the logits column j of the bf16 LM head on both
+    sides), flat and peaked: tokens must agree with the oracle's draw wherever its margin exceeds 1e-6, which at this
+    vocabulary is only possible if the group search, the exclusive prefix and the in-group scan are all right."""
+    m = BIG_VOCAB_SHAPES[V]
+    r = R()
+    W0 = make_weights(m, 1, bf16=False)
+    zero = Weights(m, {k: np.zeros_like(v) for k, v in W0.tensors.items()}, False)
+    pol = make_policy(zero, max_seqs=64, max_seq_len=40)
+    rng = np.random.default_rng(135)
+    u = rng.random((32, 2, 3), dtype=np.float32)
+    u[0, 0, :] = [0.0, 0.99999994, (V - 0.5) / V]
+    t, l = r.rlgen_generate(pol, dev_i32(np.zeros((32, 3), np.int32)), np.full(32, 3), 2, 3, 0.7, dev_f32(u))
+    t, l = t.cpu().numpy(), l.cpu().numpy()
+    uv = u.astype(np.float64) * V
+    keep = np.abs(uv - np.round(uv)) > 1e-2           # the 2e-5-wide buckets sit 1e-2 buckets away from u
+    np.testing.assert_array_equal(t[keep], np.floor(uv).astype(np.int32)[keep])
+    assert keep.mean() > 0.9 and np.abs(l + math.log(V)).max() < 1e-5
+    pol.close()
+    from workloads import f32_to_bf16_bits
+    for peak in (1.0, 8.0):
+        Wp = scaled_bf16_weights(m, seed=36, scale=30.0, lm_head_scale=peak)
+        tens = dict(Wp.tensors)
+        b = np.zeros(m.d_model, np.float32)
+        b[7] = 1.0
+        tens["final_norm_g"], tens["final_norm_b"] = f32_to_bf16_bits(np.zeros(m.d_model, np.float32)), f32_to_bf16_bits(b)
+        Wp = Weights(m, tens, True)
+        dec = O.Decoder(Wp, m)
+        pol = make_policy(Wp, max_seqs=256, max_seq_len=40, max_batch_tokens=256)
+        Rr = 200
+        hidden = rng.normal(size=(Rr, m.d_model)).astype(np.float32)
+        uu = rng.random(Rr, dtype=np.float32)
+        tok, lp = r.rlgen_debug_sample(pol, dev_f32(hidden), 0.7, dev_f32(uu))
+        tok, lp = tok.cpu().numpy(), lp.cpu().numpy()
+        logp = O.tempered_log_softmax(dec.logits(hidden[:1])[0], 0.7)       # every row has the same logits
+        np.testing.assert_array_equal(dec.logits(hidden[:1])[0], Wp.f32("lm_head")[:, 7])
+        checked = 0
+        for i in range(Rr):
+            want, margin = O.sample_inverse_cdf(logp, uu[i])
+            lo, hi = O.cdf_bucket(logp, int(tok[i]))
+            assert lo - 1e-6 <= uu[i] <= hi + 1e-6, (i, tok[i], want)       # a valid draw in any case
+            if margin > 1e-6:
+                assert tok[i] == want, (i, peak)
+                checked += 1
+            assert abs(lp[i] - logp[tok[i]]) < 2e-5
+        report("sampler-big-vocab", V=V, peak=peak, checked=checked / Rr, max_p=float(np.exp(logp.max())))
+        assert checked > (0.5 if peak == 1.0 else 0.9) * Rr
+        pol.close()
+
+
+# an FFN wide enough (K = 1024 for the down projection) that the K split of the decode GEMMs is more than one part
+WIDE_FFN = ModelShape(0, 2, 64, 4, 4, 16, 1024, 200, rotary_dim=4)
+
+
+@pytest.mark.parametrize("name", ["neox-h80", "llama-gqa4-h16", "neox-wide-ffn"])
+def test_results_do_not_depend_on_the_tile_shapes_a_context_picked(name):
+    """A context chooses its GEMM tile shapes by timing them, so two contexts may choose differently; how a sum over the
+    inner dimension is cut and ordered is fixed by the configuration.  Two contexts with the same weights are forced onto
+    different tile shapes for every linear layer and every mode: tokens and log-probs must agree bit for bit."""
+    m = WIDE_FFN if name == "neox-wide-ffn" else GPU_SHAPES[name]
+    W = scaled_bf16_weights(m)
+    r = R()
+    rng = np.random.default_rng(91)
+    prompts = rand_seqs(rng, m.vocab, [30, 1, 33, 64, 71])
+    arr, lens = padded(prompts)
+    u = rng.random((5, 2, 7), dtype=np.float32)
+    outs, picks = [], []
+    for shift in (0, 1, 2):
+        pol = make_policy(W, max_seqs=12, max_seq_len=80, max_batch_tokens=80)
+        try:
+            r.rlgen_set_decode_split_min(pol, 2 if shift == 2 else 0)      # the third context also decodes as two halves
+            chosen = []
+            for mode in (0, 1, 2):
+                for which in range(5):
+                    v0, sp = r.rlgen_debug_get_gemm(pol, mode, which)
+                    wide_only = which == 4 or (which == 2 and m.arch == 1)
+                    nv = 6 if wide_only else 9
+                    v = v0 if shift == 0 else (max(v0, 0) + 1 + 2 * shift) % nv
+                    if shift:
+                        r.rlgen_debug_set_gemm(pol, mode, which, v)
+                    chosen.append((v, sp))
+            picks.append(chosen)
+            t, l = r.rlgen_generate(pol, dev_i32(arr), lens, 2, 7, 0.7, dev_f32(u))
+            full, flens = padded([np.concatenate([prompts[b], t[b, j].cpu().numpy()]) for b in range(5) for j in range(2)])
+            sc = r.rlgen_score(pol, dev_i32(full), flens, 0.7)
+            z = r.rlgen_debug_logits(pol, dev_i32(full), flens)
+            assert r.rlgen_status(pol) == 0
+            outs.append((t.cpu(), l.cpu(), sc.cpu(), z.cpu()))
+        finally:
+            pol.close()
+    assert [sp for _, sp in picks[0]] == [sp for _, sp in picks[1]] == [sp for _, sp in picks[2]]     # the K split is the rule's
+    assert [v for v, _ in picks[0]] != [v for v, _ in picks[1]]
+    if name == "neox-wide-ffn":
+        assert any(sp > 1 for _, sp in picks[0])                               # the test covers a split product
+    for o in outs[1:]:
+        for a, b in zip(outs[0], o):
+            assert torch.equal(a, b)
+
+
+def test_values_beyond_fp16_are_clamped_and_flagged():
+    """The inputs of the matrix products are fp16.  A value just inside its range (60 000) passes unflagged and the result
+    matches the oracle; a value beyond it (70 000) is clamped, never becomes infinity, and raises the sticky range bit.
+    The large values meet zero weights (an LM-head column, an FFN-down column), so the oracle's result is the same in
+    all three cases and the outputs must stay within tolerance of it."""
+    from workloads import f32_to_bf16_bits, bf16_bits_to_f32
+    m = GPU_SHAPES["neox-h80"]
+    W = scaled_bf16_weights(m)
+    r = R()
+    rng = np.random.default_rng(92)
+    seqs = rand_seqs(rng, m.vocab, [5, 40, 64])
+    arr, lens = padded(seqs)
+
+    def variant(final_bias, up_bias):
+        t = dict(W.tensors)
+        fb = bf16_bits_to_f32(t["final_norm_b"]).copy(); fb[5] = final_bias
+        lm = bf16_bits_to_f32(t["lm_head"]).copy(); lm[:, 5] = 0.0
+        bu = bf16_bits_to_f32(t["layers.0.b_up"]).copy(); bu[9] = up_bias
+        wd = bf16_bits_to_f32(t["layers.0.w_down"]).copy(); wd[:, 9] = 0.0
+        t.update({"final_norm_b": f32_to_bf16_bits(fb), "lm_head": f32_to_bf16_bits(lm), "layers.0.b_up": f32_to_bf16_bits(bu),
+                  "layers.0.w_down": f32_to_bf16_bits(wd)})
+        return Weights(m, t, True)
+
+    for final_bias, up_bias, want_bits in ((60000.0, 60000.0, 0), (70000.0, 0.5, r.FAULT_RANGE), (0.5, 70000.0, r.FAULT_RANGE)):
+        Wv = variant(final_bias, up_bias)
+        ref = np.stack([O.last_logits(O.Decoder(Wv, m), s) for s in seqs])
+        pol = make_policy(Wv, max_seqs=4, max_seq_len=80)
+        try:
+            z = r.rlgen_debug_logits(pol, dev_i32(arr), lens).cpu().numpy()
+            sc = r.rlgen_score(pol, dev_i32(arr), lens, 0.7).cpu().numpy()
+            assert r.rlgen_status_bits(pol) == want_bits, (final_bias, up_bias)
+            assert r.rlgen_status(pol) == (r.ERR_DEVICE if want_bits else 0)
+            assert np.isfinite(z).all() and np.isfinite(sc).all()
+            assert np.abs(z - ref).max() < TOL_LOGITS, (final_bias, up_bias)
+        finally:
+            pol.close()
+
+
 def test_config1_end_to_end():
     """Config 1 as specified: fp32 weights (the library rounds them to bf16), 4 prompts x 32 tokens,
     K = 2, 16 new tokens, temperature 0.7."""
@@ -335,6 +479,14 @@ def test_update_weights_replaces_the_policy():
         r.rlgen_update_weights(pol, r.upload_weights(W2.tensors))
         a2 = r.rlgen_generate(pol, dev_i32(arr), lens, 2, 6, 0.7, dev_f32(u))
         assert torch.equal(a2[0], b2[0]) and torch.equal(a2[1], b2[1])
+        # and what the oracle generates from the new weights (the old ones give something else)
+        t_o, l_o, margins, _, _ = oracle_generate_batch(O.Decoder(W2, m), arr, lens, 2, 6, 0.7, u)
+        forced = np.where(margins > MARGIN, -1, t_o).astype(np.int32)
+        t_g, l_g = r.rlgen_generate(pol, dev_i32(arr), lens, 2, 6, 0.7, dev_f32(u), dev_i32(forced))
+        np.testing.assert_array_equal(t_g.cpu().numpy(), t_o)
+        assert np.abs(l_g.cpu().numpy() - l_o).max() < TOL_LOGPROB
+        _, l_old, _, _, _ = oracle_generate_batch(O.Decoder(W1, m), arr, lens, 2, 6, 0.7, u, forced=t_o)
+        assert np.abs(l_g.cpu().numpy() - l_old).max() > 10 * TOL_LOGPROB
         farr, flens = padded([np.concatenate([prompts[b], a2[0][b, j].cpu().numpy()]) for b in range(3) for j in range(2)])
         assert torch.equal(r.rlgen_score(pol, dev_i32(farr), flens, 0.7), r.rlgen_score(ref2, dev_i32(farr), flens, 0.7))
     finally:
@@ -348,7 +500,7 @@ def shared(request):
     m = GPU_SHAPES[request.param]
     W = scaled_bf16_weights(m)
     pol = make_policy(W, max_seqs=20, max_seq_len=112, max_kv_tokens=2048, max_batch_tokens=112, share_prompt_kv=1)
-    yield m, W, O.Decoder(W, m), pol
+    yield m, W, reference_decoder(W, m), pol
     pol.close()
 
 
@@ -428,14 +580,14 @@ def test_shared_prompt_cache_capacity(shared):
 # ---------------------------------------------------------------- large batches decode as two concurrent halves
 @pytest.mark.parametrize("share", [0, 1])
 @pytest.mark.parametrize("name", ["neox-h80", "llama-gqa4-h16"])
-def test_split_decode_matches_oracle_and_unsplit(name, share, monkeypatch):
+def test_split_decode_matches_oracle_and_unsplit(name, share):
     """The two-stream decode normally starts at 256 sequences; the threshold is lowered so that a batch the
     oracle can follow takes it (odd prompt count: the halves differ in size)."""
-    monkeypatch.setenv("RLGEN_DECODE_SPLIT_MIN", "2")
     m = GPU_SHAPES[name]
     W = scaled_bf16_weights(m)
-    dec = O.Decoder(W, m)
+    dec = reference_decoder(W, m)
     pol = make_policy(W, max_seqs=12, max_seq_len=80, max_batch_tokens=80, share_prompt_kv=share)
+    R().rlgen_set_decode_split_min(pol, 2)
     try:
         rng = np.random.default_rng(77)
         B, k, T, temp = 5, 2, 7, 0.7
@@ -548,17 +700,17 @@ def _check_eos(m, dec, pol, temp):
 
 # ---------------------------------------------------------------- degenerate sizes
 @pytest.mark.parametrize("share", [0, 1])
-def test_degenerate_sizes(small, share, monkeypatch):
+def test_degenerate_sizes(small, share):
     """One prompt of one token, one sample, one new token (no decode step at all); then the context filled to its
     exact capacity in sequences, sequence length and cache tokens; with the two-stream decode forced on."""
     m, W, dec, _ = small
     if share and 3 * (m.n_q_heads // m.n_kv_heads) > 16:
         pytest.skip("k samples x query heads per kv head exceed the 16 MFMA columns")
-    monkeypatch.setenv("RLGEN_DECODE_SPLIT_MIN", "2")
     r = R()
     S, L = 6, 40
     need = S * 64 if not share else 3 * 32 + S * 32            # 3 prompts x 2 samples: prompts of 8 + 32 new tokens
     pol = make_policy(W, max_seqs=S, max_seq_len=L, max_kv_tokens=need, max_batch_tokens=L, share_prompt_kv=share)
+    r.rlgen_set_decode_split_min(pol, 2)
     try:
         rng = np.random.default_rng(61)
         for B, k, P, T in ((1, 1, 1, 1), (1, 1, L - 1, 1), (3, 2, 8, 32), (2, 3, 8, 1)):
@@ -580,13 +732,13 @@ def test_degenerate_sizes(small, share, monkeypatch):
 
 @pytest.mark.parametrize("every", [1, 2, 5])
 @pytest.mark.parametrize("name", ["neox-h80", "llama-gqa4-h16"])
-def test_ended_sequences_leave_the_batch(name, every, monkeypatch):
+def test_ended_sequences_leave_the_batch(name, every):
     """EOS is forced at chosen steps of chosen sequences (a forced token counts as emitted on both sides), so the
     batch shrinks several times, down to nothing before the last step in one case; outputs must match the oracle
     and, bit for bit, a context that keeps ended sequences in the batch."""
     m = GPU_SHAPES[name]
     W = scaled_bf16_weights(m)
-    dec = O.Decoder(W, m)
+    dec = reference_decoder(W, m)
     rng = np.random.default_rng(71)
     B, k, T, temp = 4, 2, 14, 0.7
     prompts = rand_seqs(rng, m.vocab, [30, 5, 64, 17])
@@ -603,9 +755,9 @@ def test_ended_sequences_leave_the_batch(name, every, monkeypatch):
         forced = np.where(plan >= 0, plan, np.where(margins > MARGIN, -1, t_o)).astype(np.int32)
         outs = []
         for ev in (every, 0):
-            monkeypatch.setenv("RLGEN_EOS_COMPACT_EVERY", str(ev))
             pol = make_policy(W, max_seqs=8, max_seq_len=80, max_batch_tokens=80)
             try:
+                r.rlgen_set_eos_compaction(pol, ev)
                 r.rlgen_set_eos(pol, eos)
                 t_g, l_g = r.rlgen_generate(pol, dev_i32(arr), lens, k, T, temp, dev_f32(u), dev_i32(forced))
                 assert r.rlgen_status(pol) == 0
