@@ -176,6 +176,20 @@ int rlgen_debug_sample(rlgen_ctx *ctx, const float *hidden, int32_t R, float tem
                        const float *uniforms, const int32_t *forced, int32_t *tokens,
                        float *token_logprobs, void *hip_stream);
 
+/* rlgen_debug_sample for callers that cannot allocate or hand over scratch memory at the time of the call: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, same results;
+ * the stage's intermediate buffers (the normalised rows, the per-row per-64-column softmax partials) live in a static
+ * device array of the library (about 4.3 MB per GPU, held until the process ends) instead of the context's workspace,
+ * so the call does not touch the workspace's activation buffers.  It allocates nothing, on the host or the device.
+ * Limits: R <= 64 rows, d_model <= 8192, vocab <= 262144; beyond them RLGEN_ERR_CAPACITY.  The device the context was
+ * created on must be current.  All calls on one GPU, from any context, share the one array: calls that overlap in time
+ * on that GPU (different streams or contexts) race; calls on one stream are ordered.  Nothing in the array needs to
+ * start at zero: every element a call reads it has written itself.
+ * Errors: NULL, BAD_ARG, CAPACITY, DEVICE. */
+int rlgen_sample_static(rlgen_ctx *ctx, const float *hidden, int32_t R, float temperature,
+                        const float *uniforms, const int32_t *forced, int32_t *tokens,
+                        float *token_logprobs, void *hip_stream);
+
 /* Consumers of the log-probs (Section 2.1, DPO objective).  seq_logprob[n] = sum of
  * token_logprobs[n, t] over from[n] <= t < lens[n] (from, lens: DEVICE [N] int32). */
 int rlgen_sequence_logprob(const float *token_logprobs, const int32_t *from, const int32_t *lens,

@@ -13,6 +13,19 @@
 #include <new>
 #include <vector>
 
+// ------------------------------------------------------------------ rlgen_sample_static's scratch
+// The final-norm + LM-head + sampling stage needs three intermediate buffers: the normalised rows (16-bit, K-block
+// major), the (max, sum exp) pair per row and 64 vocabulary columns, and one captured logit per row.  rlgen_sample_static
+// keeps them here instead of in the caller's workspace, for at most STATIC_MAX_ROWS rows of a model with d_model <=
+// STATIC_MAX_D and vocab <= 64 STATIC_MAX_GROUPS.  Every GPU the library runs on holds its own copy of the array (about
+// 4.3 MB) until the process ends; its address on a device is asked for once, in rlgen_create, with that device current.
+constexpr int STATIC_MAX_ROWS = 64, STATIC_MAX_D = 8192, STATIC_MAX_GROUPS = 4096;
+constexpr size_t STATIC_HFIN_BYTES = (size_t)STATIC_MAX_ROWS * STATIC_MAX_D * 2 * 2;      // two 16-bit values per element at most
+constexpr size_t STATIC_PARTIAL_BYTES = (size_t)STATIC_MAX_ROWS * STATIC_MAX_GROUPS * sizeof(float2);
+constexpr size_t STATIC_TARGET_BYTES = 256;
+static __device__ __align__(256) unsigned char scratch[STATIC_HFIN_BYTES + STATIC_PARTIAL_BYTES + STATIC_TARGET_BYTES];
+static unsigned char* scratch_on_device[64];      // device address of `scratch` per device, null until rlgen_create ran there
+
 namespace {
 
 constexpr size_t ALIGN = 256;
@@ -116,6 +129,7 @@ struct rlgen_ctx {
   // [decode of max_seqs rows | prompt pass | decode of half of max_seqs rows][which GEMM]
   struct GemmChoice { int variant, splits; } tuned[3][5];
   bool half_rows;         // the decode steps being enqueued cover half of the batch
+  int device;             // the device the context was created on
 };
 
 namespace {
@@ -969,6 +983,17 @@ int rlgen_create(const rlgen_model_cfg* cfg, const rlgen_weights* weights, void*
   c->have_streams = true;
   c->split_min_seqs = DECODE_SPLIT_MIN_SEQS;
   c->fused_qkv = cfg->rotary_dim % 4 == 0;
+  {
+    // where this device keeps the scratch array of rlgen_sample_static (the array's name is no device address)
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return fail(RLGEN_ERR_DEVICE);
+    if (!scratch_on_device[dev]) {
+      unsigned char* ptr = nullptr;
+      if (hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return fail(RLGEN_ERR_DEVICE);
+      scratch_on_device[dev] = ptr;
+    }
+    c->device = dev;
+  }
   rc = pack_weights(c, weights, st);
   if (rc) return fail(rc);
   if (rl_rope_table(c->rope, cfg->max_seq_len, cfg->rotary_dim, cfg->rope_theta, st) != hipSuccess) return fail(RLGEN_ERR_DEVICE);
@@ -1211,6 +1236,37 @@ int rlgen_debug_sample(rlgen_ctx* c, const float* hidden, int32_t R, float tempe
   HIPCHK(rl_norm(hidden, nullptr, R, m.d_model, m.norm_eps, c->fng, m.arch == RLGEN_ARCH_LLAMA ? nullptr : c->fnb, c->hfin,
                  nullptr, nullptr, nullptr, R, 0, c->status, st));
   return sample_rows(c, R, temperature, uniforms, forced, 1, 0, tokens, token_logprobs, nullptr, st);
+}
+
+int rlgen_sample_static(rlgen_ctx* c, const float* hidden, int32_t R, float temperature, const float* uniforms,
+                        const int32_t* forced, int32_t* tokens, float* token_logprobs, void* hip_stream) {
+  if (!c || !hidden || !uniforms || !tokens || !token_logprobs) return RLGEN_ERR_NULL;
+  if (R < 1) return RLGEN_ERR_BAD_ARG;
+  if (!(temperature > 0.f) || !std::isfinite(temperature)) return RLGEN_ERR_BAD_ARG;
+  const rlgen_model_cfg& m = c->cfg;
+  if (R > STATIC_MAX_ROWS || m.d_model > STATIC_MAX_D || c->ngroups > STATIC_MAX_GROUPS) return RLGEN_ERR_CAPACITY;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev != c->device) return RLGEN_ERR_DEVICE;      // the context's device must be current
+  unsigned char* base = scratch_on_device[dev];
+  if (!base) return RLGEN_ERR_DEVICE;
+  hipStream_t st = (hipStream_t)hip_stream;
+  // The stage's kernels take their intermediate buffers from the context's current activation set: point that at the
+  // static array for the duration of the call.  Every element the kernels read is written earlier in this same call
+  // (R normalised rows, R x ngroups partials), so nothing left over from a previous call is ever read and nothing needs
+  // clearing.
+  uint16_t* const keep_hfin = c->hfin;
+  float2* const keep_partial = c->partial;
+  float* const keep_target = c->target_logit;
+  c->hfin = (uint16_t*)base;
+  c->partial = (float2*)(base + STATIC_HFIN_BYTES);
+  c->target_logit = (float*)(base + STATIC_HFIN_BYTES + STATIC_PARTIAL_BYTES);
+  int rc = RLGEN_OK;
+  if (rl_norm(hidden, nullptr, R, m.d_model, m.norm_eps, c->fng, m.arch == RLGEN_ARCH_LLAMA ? nullptr : c->fnb, c->hfin, nullptr,
+              nullptr, nullptr, R, 0, c->status, st) != hipSuccess)
+    rc = RLGEN_ERR_DEVICE;
+  if (rc == RLGEN_OK) rc = sample_rows(c, R, temperature, uniforms, forced, 1, 0, tokens, token_logprobs, nullptr, st);
+  c->hfin = keep_hfin; c->partial = keep_partial; c->target_logit = keep_target;
+  return rc;
 }
 
 int rlgen_sequence_logprob(const float* token_logprobs, const int32_t* from, const int32_t* lens, int32_t N, int32_t stride,

@@ -25,7 +25,7 @@ ARCH_NEOX, ARCH_LLAMA = 0, 1
 DTYPE_F32, DTYPE_BF16 = 0, 1
 
 EXPORTS = ["rlgen_workspace_bytes", "rlgen_create", "rlgen_update_weights", "rlgen_generate", "rlgen_score",
-           "rlgen_debug_logits", "rlgen_debug_sample", "rlgen_sequence_logprob", "rlgen_dpo_loss", "rlgen_select_pairs", "rlgen_proximal_rloo",
+           "rlgen_debug_logits", "rlgen_debug_sample", "rlgen_sample_static", "rlgen_sequence_logprob", "rlgen_dpo_loss", "rlgen_select_pairs", "rlgen_proximal_rloo",
            "rlgen_get_timings", "rlgen_set_profiling", "rlgen_set_decode_split", "rlgen_set_decode_split_min", "rlgen_set_eos",
            "rlgen_set_eos_compaction", "rlgen_set_score_groups", "rlgen_debug_get_gemm", "rlgen_debug_set_gemm", "rlgen_status",
            "rlgen_status_bits", "rlgen_strerror", "rlgen_destroy"]
@@ -68,6 +68,8 @@ lib.rlgen_debug_logits.restype = C.c_int
 lib.rlgen_debug_logits.argtypes = [_vp, _vp, C.POINTER(_i32), _i32, _i32, _vp, _vp]
 lib.rlgen_debug_sample.restype = C.c_int
 lib.rlgen_debug_sample.argtypes = [_vp, _vp, _i32, _f32, _vp, _vp, _vp, _vp, _vp]
+lib.rlgen_sample_static.restype = C.c_int
+lib.rlgen_sample_static.argtypes = [_vp, _vp, _i32, _f32, _vp, _vp, _vp, _vp, _vp]
 lib.rlgen_sequence_logprob.restype = C.c_int
 lib.rlgen_sequence_logprob.argtypes = [_vp, _vp, _vp, _i32, _i32, _vp, _vp]
 lib.rlgen_select_pairs.restype = C.c_int
@@ -257,6 +259,19 @@ def rlgen_debug_sample(p: Policy, hidden: torch.Tensor, temperature: float, unif
     lps = torch.empty(R, dtype=torch.float32, device=hidden.device)
     _check(lib.rlgen_debug_sample(p.ctx, _ptr(hidden), R, temperature, _ptr(uniforms), _ptr(forced), _ptr(tokens),
                                   _ptr(lps), _stream()), "rlgen_debug_sample")
+    return tokens, lps
+
+
+def rlgen_sample_static(p: Policy, hidden: torch.Tensor, temperature: float, uniforms: torch.Tensor,
+                        forced: Optional[torch.Tensor] = None, out=None):
+    """rlgen_debug_sample with the library's static scratch; `out` = (tokens, token_logprobs) to write into."""
+    R, d = hidden.shape
+    assert hidden.dtype == torch.float32 and hidden.is_contiguous() and d == p.cfg.d_model
+    assert uniforms.dtype == torch.float32 and tuple(uniforms.shape) == (R,)
+    tokens, lps = out if out is not None else (torch.empty(R, dtype=torch.int32, device=hidden.device),
+                                               torch.empty(R, dtype=torch.float32, device=hidden.device))
+    _check(lib.rlgen_sample_static(p.ctx, _ptr(hidden), R, temperature, _ptr(uniforms), _ptr(forced), _ptr(tokens),
+                                   _ptr(lps), _stream()), "rlgen_sample_static")
     return tokens, lps
 
 
