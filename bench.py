@@ -21,6 +21,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+MFMA_F16_PEAK_TFLOPS = 2500.0        # dense fp16 / bf16 matrix peak of MI355X
 # HBM bytes per decode-attention launch over its algorithmic bytes on workload 4, measured with rocprofv3
 # FETCH_SIZE + WRITE_SIZE, each scaled by its reading for a plain 1 GiB copy (profiles/attention_decode_c4_hbm_traffic.txt).
 TRAFFIC_OVER_ALGORITHMIC = 1.039
@@ -203,6 +204,21 @@ def main():
     decode_bytes = sum(wbytes + m.n_layers * (per_key * keys(t) + per_key * S) for t in range(1, T))
     decode_gbs = decode_bytes / (np.mean(decode_ms) * 1e-3) / 1e9 if T > 1 else 0.0
 
+    # ---- matrix-core roofline of the prompt pass and of the score pass: algorithmic flops over the measured time.
+    # Linear layers: 2 flops per weight and row (every matrix of every block; the LM head only for the rows it serves);
+    # attention: QK^T and PV over the causal triangle, 4 h flops per (query, visible key) and query head.
+    body = m.n_params - 2 * m.vocab * m.d_model                     # weights of all blocks
+    lm = m.vocab * m.d_model
+    tri = lambda n: n * (n + 1) // 2
+    L64 = lens.astype(np.int64)
+    prefill_flops = 2.0 * float(L64.sum()) * body + 2.0 * S * lm \
+        + 4.0 * m.head_dim * m.n_q_heads * m.n_layers * float(sum(tri(int(n)) for n in L64))
+
+    def mfma_roofline(flops, ms, what):
+        tf = flops / (ms * 1e-3) / 1e12 if ms else 0.0
+        return {"bound": "mfma", "pass": what, "achieved": round(tf, 1), "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(tf / MFMA_F16_PEAK_TFLOPS, 4), "flops": float(flops), "ms": round(ms, 2)}
+
     result = {
         "metric": "generated tokens/s (K=2/prompt) at 1 GPU; decode HBM GB/s as % of peak",
         "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -223,7 +239,22 @@ def main():
         if args.config == 4 and halves > 1 and not share and not args.k and not args.eos_mix else None,
         "setup_s": round(setup_s, 1),
         "roofline": roofline,
+        "roofline_prefill": mfma_roofline(prefill_flops, float(np.mean(prefill_ms)),
+                                          "prompt pass of rlgen_generate (all layers, K-way cache fan-out, first LM head)"),
     }
+    if roofline["traffic"] is not None:
+        roofline["traffic_source"] = ("algorithmic bytes x 1.039, the ratio rocprofv3 FETCH_SIZE + WRITE_SIZE gave for this kernel "
+                                      "on this workload (profiles/attention_decode_c4_hbm_traffic.txt); not re-measured in this run")
+    if score_ms:
+        # rows the score pass sends through the blocks: with grouping a prompt once and each completion's tail; else every sequence
+        if args.score_plain:
+            rows, att = float((L64 + T).sum() * k), float(sum(tri(int(n) + T) for n in L64) * k)
+        else:
+            rows = float(L64.sum() + S * T)
+            att = float(sum(tri(int(n)) + k * (T * int(n) + tri(T)) for n in L64))
+        score_flops = 2.0 * rows * body + 2.0 * S * T * lm + 4.0 * m.head_dim * m.n_q_heads * m.n_layers * att
+        result["roofline_score"] = mfma_roofline(score_flops, float(np.mean(score_ms)),
+                                                 "rlgen_score over the generated sequences (LM head on the response positions)")
     if halves > 1 and not args.no_kernel_events and not args.no_alone_pass:
         # the same kernel with nothing beside it: one more pass (not part of `value`) with the two-stream decode
         # switched off, so that a launch covers the whole batch and runs alone

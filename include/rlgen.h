@@ -23,6 +23,7 @@
  *  - Arithmetic: weights are bf16 values (held in fp16, which represents them exactly in its normal
  *    range); GEMM and attention inputs are fp16; the KV cache is bf16; accumulation, the residual
  *    stream, normalisation statistics, softmax and log-sum-exp are fp32 (fp64 for the CDF scan).
+ *    cfg.precise = 1 widens every 16-bit activation and cache entry to a pair of bf16 numbers.
  */
 #ifndef RLGEN_H
 #define RLGEN_H
@@ -79,6 +80,15 @@ typedef struct {
                               order.  Then k * (n_q_heads / n_kv_heads) <= 16 is required and the
                               max_kv_tokens need is sum over prompts of round32(prompt_len) +
                               prompts * k * round32(max_new).  rlgen_score is unaffected.        */
+  int32_t precise;         /* 0: the formats of the Conventions above (fp16 matrix-product inputs, bf16 cache).
+                              1: every 16-bit activation and every cached key and value is held as the sum of
+                              two bf16 numbers (16 significant bits, fp32's exponent range), the queries stay
+                              fp32, the weights stay the caller's bf16 values, and each matrix product runs once
+                              per half on the bf16 matrix instructions.  For checking a policy against an fp32
+                              reference where the 16-bit formats themselves exceed the tolerance (random
+                              Llama-shaped weights amplify every rounding: Appendix A.2's model shape); it
+                              doubles the cache, the activation buffers and the matrix work.  Requires
+                              rotary_dim % 4 == 0 and head_dim <= 128.                              */
 } rlgen_model_cfg;
 
 /* Per-layer tensors, row-major, linear layers stored [out, in] and applied as y = W x + b.

@@ -18,6 +18,9 @@
 // columns, so K/V are read once per group; with G = 1 the query is replicated over the columns.
 // With a shared prompt cache (share_k = K samples per prompt) the K samples sit in the columns as well:
 // the prompt's stream is read once for all of them, then each sample's short stream of new tokens.
+// Precise mode (PR): every operand is a bf16 hi/lo pair -- the cache holds a second plane with the lo halves, the
+// queries arrive as fp32 and are split in registers, the probabilities are split after the softmax -- and each product
+// is three bf16 matrix instructions (hi hi + lo hi + hi lo; the lo lo term is below fp32's own rounding).
 #include "kernels.h"
 
 #ifndef ATTN_PREFETCH
@@ -49,13 +52,16 @@ namespace {
 
 // QB = query blocks of 16 columns a wave carries through one pass over the keys (prompt pass only: two blocks halve
 // the key / value traffic per query; a.jobs then counts blocks of 16 QB tokens).
-template <int HD, bool DECODE, int QB = 1>
-__global__ __launch_bounds__(256, (!DECODE && HD <= 128) ? ATTN_PROMPT_BLOCKS : 1) void attention_kernel(AttnArgs a) {
+template <int HD, bool DECODE, int QB = 1, bool PR = false>
+__global__ __launch_bounds__(256, (!DECODE && HD <= 128 && !PR) ? ATTN_PROMPT_BLOCKS : 1) void attention_kernel(AttnArgs a) {
   static_assert(!DECODE || QB == 1, "decode has one query block");
   constexpr int NCH = HD / 8;            // 16-byte chunks per key row
   constexpr int KSTEPS = (HD + 31) / 32; // MFMA steps over head_dim for the scores
   constexpr int VT = HD / 16;            // 16-row tiles of V^T / O^T
-  constexpr bool PF = DECODE || !ATTN_PROMPT_NOPF;     // is the next super-block requested one iteration ahead
+  // is the next super-block requested one iteration ahead (precise mode holds two planes per super-block in registers
+  // and loads them at the top of the iteration instead)
+  constexpr bool PF = (DECODE || !ATTN_PROMPT_NOPF) && !PR;
+  constexpr int NP = PR ? 2 : 1;         // cache planes: hi, lo
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int c = lane & 15, g = lane >> 4;
   const int Hkv = a.lay.Hkv, G = a.Hq / Hkv;
@@ -122,18 +128,37 @@ __global__ __launch_bounds__(256, (!DECODE && HD <= 128) ? ATTN_PROMPT_BLOCKS : 
 
   // query fragments (B operand): lane (c, g) holds q[col c][32 i + 8 g .. + 7]
   f16x8 qf[QB][KSTEPS];
+  [[maybe_unused]] u32x4 qlo[QB][KSTEPS];          // precise mode: qf holds the bf16 hi halves (as bits), qlo the lo halves
 #pragma unroll
   for (int b = 0; b < QB; ++b) {
-    const uint16_t* qp = a.q + (size_t)qrow[b] * a.q_ld + qhead * HD;
+    const uint16_t* qp = a.q + ((size_t)qrow[b] * a.q_ld + qhead * HD) * (PR ? 2 : 1);
 #pragma unroll
     for (int i = 0; i < KSTEPS; ++i) {
       const int d0 = 32 * i + 8 * g;
+      if constexpr (PR) {
+        u32x4 hi = u32x4{0, 0, 0, 0}, lo = u32x4{0, 0, 0, 0};
+        if (d0 < HD) {
+          const f32x4 x0 = *(const f32x4*)((const float*)qp + d0), x1 = *(const f32x4*)((const float*)qp + d0 + 4);
+          SPLIT_BF16X2(x0[0], x0[1], hi[0], lo[0]);
+          SPLIT_BF16X2(x0[2], x0[3], hi[1], lo[1]);
+          SPLIT_BF16X2(x1[0], x1[1], hi[2], lo[2]);
+          SPLIT_BF16X2(x1[2], x1[3], hi[3], lo[3]);
+        }
+        qf[b][i] = __builtin_bit_cast(f16x8, hi);
+        qlo[b][i] = lo;
+      } else {
       if (d0 < HD) qf[b][i] = *(const f16x8*)(qp + d0);
       else
 #pragma unroll
         for (int e = 0; e < 8; ++e) qf[b][i][e] = (f16_t)0.f;
+      }
     }
   }
+  // one 16x16x32 matrix instruction on 16-bit fragments: fp16, or bf16 in precise mode
+  auto mfma = [](f16x8 x, f16x8 y, f32x4 acc) {
+    if constexpr (PR) return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, x), __builtin_bit_cast(bf16x8, y), acc, 0, 0, 0);
+    else return __builtin_amdgcn_mfma_f32_16x16x32_f16(x, y, acc, 0, 0, 0);
+  };
 
   f32x4 o[QB][VT];
   float m[QB], lsum[QB];
@@ -161,8 +186,8 @@ __global__ __launch_bounds__(256, (!DECODE && HD <= 128) ? ATTN_PROMPT_BLOCKS : 
 
   const int nsb = (nkeys + 31) >> 5;
   // the whole next super-block (32 keys, 32 values) is requested before the current one is consumed
-  auto load_sb = [&](int sb, u32x4 (&kraw)[2][KSTEPS], u32x4 (&vraw)[VT]) {
-    const uint16_t* kb = st + (size_t)sb * 64 * HD;      // 32 keys, then the 32 values of the same positions
+  auto load_sb = [&](int sb, u32x4 (&kraw)[2][KSTEPS], u32x4 (&vraw)[VT], int plane = 0) {
+    const uint16_t* kb = st + (size_t)sb * 64 * HD + (plane ? a.kv_lo_off : 0);      // 32 keys, then the 32 values of the same positions
     const uint16_t* vb = kb + 32 * HD;
 #pragma unroll
     for (int t = 0; t < 2; ++t)
@@ -175,6 +200,7 @@ __global__ __launch_bounds__(256, (!DECODE && HD <= 128) ? ATTN_PROMPT_BLOCKS : 
     for (int t = 0; t < VT; ++t) vraw[t] = ATTN_LOAD((const u32x4*)(vb + ((((t * 4 + g) * 16) + c) << 3)));
   };
   u32x4 kraw[2][KSTEPS], vraw[VT];
+  [[maybe_unused]] u32x4 kraw_lo[NP - 1 ? 2 : 1][KSTEPS], vraw_lo[VT];
 #if ATTN_PREFETCH
   u32x4 knext[2][KSTEPS], vnext[VT];
   if (PF && nsb > 0) load_sb(0, kraw, vraw);
@@ -183,7 +209,7 @@ __global__ __launch_bounds__(256, (!DECODE && HD <= 128) ? ATTN_PROMPT_BLOCKS : 
   // decode: a second super-block in flight (the kernel is bound by bytes in flight, and registers allow it)
   u32x4 knext2[2][KSTEPS], vnext2[VT];
   // measured: head size 128 gains 4 % from it, head sizes 64 and 80 lose (fewer waves fit), 256 would spill
-  constexpr bool P2 = DECODE && HD > 96 && HD <= 128;
+  constexpr bool P2 = DECODE && HD > 96 && HD <= 128 && !PR;
   if (P2 && nsb > 1) load_sb(1, knext, vnext);
 #endif
   for (int sb = 0; sb < nsb; ++sb) {
@@ -191,7 +217,10 @@ __global__ __launch_bounds__(256, (!DECODE && HD <= 128) ? ATTN_PROMPT_BLOCKS : 
     if (P2) {
       if (sb + 2 < nsb) load_sb(sb + 2, knext2, vnext2);
     } else if (PF) { if (sb + 1 < nsb) load_sb(sb + 1, knext, vnext); }
-    else load_sb(sb, kraw, vraw);
+    else {
+      load_sb(sb, kraw, vraw);
+      if constexpr (PR) load_sb(sb, kraw_lo, vraw_lo, 1);
+    }
 #elif ATTN_PREFETCH
     if (sb + 1 < nsb) load_sb(sb + 1, knext, vnext);
 #else
@@ -203,9 +232,9 @@ __global__ __launch_bounds__(256, (!DECODE && HD <= 128) ? ATTN_PROMPT_BLOCKS : 
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
-      for (int i = 0; i < KSTEPS; ++i) kf[t][i] = bf16x8_to_f16x8(kraw[t][i]);
+      for (int i = 0; i < KSTEPS; ++i) kf[t][i] = PR ? __builtin_bit_cast(f16x8, kraw[t][i]) : bf16x8_to_f16x8(kraw[t][i]);
 #pragma unroll
-    for (int t = 0; t < VT; ++t) vf[t] = bf16x8_to_f16x8(vraw[t]);
+    for (int t = 0; t < VT; ++t) vf[t] = PR ? __builtin_bit_cast(f16x8, vraw[t]) : bf16x8_to_f16x8(vraw[t]);
     // straight-line code over the query blocks: their chains (MFMA -> softmax -> MFMA) are independent, and the
     // scheduler interleaves them only if no branch separates them
     f32x4 sc[QB][2];
@@ -215,8 +244,13 @@ __global__ __launch_bounds__(256, (!DECODE && HD <= 128) ? ATTN_PROMPT_BLOCKS : 
       for (int t = 0; t < 2; ++t) {
         sc[b][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int i = 0; i < KSTEPS; ++i)
-          sc[b][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[t][i], qf[b][i], sc[b][t], 0, 0, 0);
+        for (int i = 0; i < KSTEPS; ++i) {
+          sc[b][t] = mfma(kf[t][i], qf[b][i], sc[b][t]);
+          if constexpr (PR) {
+            sc[b][t] = mfma(__builtin_bit_cast(f16x8, kraw_lo[t][i]), qf[b][i], sc[b][t]);
+            sc[b][t] = mfma(kf[t][i], __builtin_bit_cast(f16x8, qlo[b][i]), sc[b][t]);
+          }
+        }
       }
     // lane (c, g) now holds the scores of keys 32 sb + 8 g + 4 t + j against column c
     float p[QB][8], alpha[QB];
@@ -249,12 +283,24 @@ __global__ __launch_bounds__(256, (!DECODE && HD <= 128) ? ATTN_PROMPT_BLOCKS : 
 #pragma unroll
     for (int b = 0; b < QB; ++b) {
       f16x8 pf;
+      [[maybe_unused]] u32x4 plo;
+      if constexpr (PR) {
+        u32x4 phi;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) pf[e] = (f16_t)p[b][e];
+        for (int e = 0; e < 4; ++e) SPLIT_BF16X2(p[b][2 * e], p[b][2 * e + 1], phi[e], plo[e]);
+        pf = __builtin_bit_cast(f16x8, phi);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pf[e] = (f16_t)p[b][e];
+      }
 #pragma unroll
       for (int t = 0; t < VT; ++t) {
         o[b][t] *= alpha[b];
-        o[b][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vf[t], pf, o[b][t], 0, 0, 0);
+        o[b][t] = mfma(vf[t], pf, o[b][t]);
+        if constexpr (PR) {
+          o[b][t] = mfma(__builtin_bit_cast(f16x8, vraw_lo[t]), pf, o[b][t]);
+          o[b][t] = mfma(vf[t], __builtin_bit_cast(f16x8, plo), o[b][t]);
+        }
       }
     }
 #if ATTN_PREFETCH
@@ -289,9 +335,17 @@ __global__ __launch_bounds__(256, (!DECODE && HD <= 128) ? ATTN_PROMPT_BLOCKS : 
 #pragma unroll
       for (int t = 0; t < VT; ++t) {
         u32x2 w;
-        w[0] = pack_f16x2(o[b][t][0] * inv, o[b][t][1] * inv);
-        w[1] = pack_f16x2(o[b][t][2] * inv, o[b][t][3] * inv);
-        *(u32x2*)(a.out + kblk_off(qrow[b], qhead * HD + 16 * t + 4 * g, a.out_rows)) = w;
+        uint16_t* dst = a.out + kblk_off(qrow[b], qhead * HD + 16 * t + 4 * g, a.out_rows);
+        if constexpr (PR) {
+          u32x2 wl;
+          SPLIT_BF16X2(o[b][t][0] * inv, o[b][t][1] * inv, w[0], wl[0]);
+          SPLIT_BF16X2(o[b][t][2] * inv, o[b][t][3] * inv, w[1], wl[1]);
+          *(u32x2*)(dst + a.out_lo_off) = wl;
+        } else {
+          w[0] = pack_f16x2(o[b][t][0] * inv, o[b][t][1] * inv);
+          w[1] = pack_f16x2(o[b][t][2] * inv, o[b][t][3] * inv);
+        }
+        *(u32x2*)dst = w;
       }
     }
   }
@@ -301,6 +355,15 @@ template <bool DECODE, int QB>
 hipError_t dispatch(const AttnArgs& a, int jobs, hipStream_t s) {
   if (jobs <= 0) return hipSuccess;
   dim3 grid((jobs + 3) / 4), block(256);
+  if (a.precise) {
+    switch (a.lay.h) {
+#define CASE(H) case H: hipLaunchKernelGGL((attention_kernel<H, DECODE, (QB > 1 && H > 80) ? 1 : QB, true>), grid, block, 0, s, a); break;
+      CASE(16) CASE(32) CASE(48) CASE(64) CASE(80) CASE(96) CASE(112) CASE(128)
+#undef CASE
+      default: return hipErrorInvalidValue;     // head size 256 would not fit the register file with two planes
+    }
+    return hipGetLastError();
+  }
   switch (a.lay.h) {
 #define CASE(H) case H: hipLaunchKernelGGL((attention_kernel<H, DECODE, (QB > 1 && H > 80) ? 1 : QB>), grid, block, 0, s, a); break;
     CASE(16) CASE(32) CASE(48) CASE(64) CASE(80) CASE(96) CASE(112) CASE(128) CASE(256)

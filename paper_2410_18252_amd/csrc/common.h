@@ -45,6 +45,24 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 #define RLGEN_FAULT_GROUP   4u      // sequences declared to share a prefix (rlgen_set_score_groups) do not
 #define RLGEN_FAULT_RANGE   8u      // an activation exceeded the largest finite fp16 value and was clamped
 
+// A value held as the sum of two bf16 numbers, hi = bf16(f) and lo = bf16(f - hi): 16 significant bits with bf16's
+// exponent range (the operand format of the library's precise mode).  f - hi is exact in fp32.
+__device__ __forceinline__ void split_bf16(float f, uint16_t& hi, uint16_t& lo) {
+  hi = f32_to_bf16_bits(f);
+  lo = f32_to_bf16_bits(f - bf16_bits_to_f32(hi));
+}
+// the same for two values, packed for 32-bit stores: returns (hi, lo) with hi = (bf16 a, bf16 b) and lo likewise
+__device__ __forceinline__ u32x2 split_bf16x2(float a, float b) {
+  uint16_t ah, al, bh, bl;
+  split_bf16(a, ah, al);
+  split_bf16(b, bh, bl);
+  u32x2 r;
+  r[0] = (uint32_t)ah | ((uint32_t)bh << 16);
+  r[1] = (uint32_t)al | ((uint32_t)bl << 16);
+  return r;
+}
+#define SPLIT_BF16X2(a, b, hi, lo) do { const u32x2 t_ = split_bf16x2(a, b); (hi) = t_[0]; (lo) = t_[1]; } while (0)
+
 // fp32 -> fp16, round to nearest even, saturating at the largest finite fp16.
 __device__ __forceinline__ uint16_t f32_to_f16_bits(float f) {
   const f16_t h = (f16_t)fminf(fmaxf(f, -65504.f), 65504.f);

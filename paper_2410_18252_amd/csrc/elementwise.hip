@@ -13,15 +13,16 @@ __global__ void to_bf16_kernel(uint16_t* dst, const void* src, int src_is_bf16, 
   for (; i < n; i += stride)
     dst[i] = src_is_bf16 ? ((const uint16_t*)src)[i] : f32_to_bf16_bits(((const float*)src)[i]);
 }
+// as_bf16: the bf16 bit patterns themselves are stored (precise mode) instead of their fp16 equivalents
 __global__ void to_f16w_kernel(uint16_t* dst, const void* src, int src_is_bf16, int rows, int K, int rows_total, int row0,
-                               int perm_h, int perm_r) {
+                               int perm_h, int perm_r, int as_bf16) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const size_t n = (size_t)rows * K, stride = (size_t)gridDim.x * blockDim.x;
   for (; i < n; i += stride) {
     const uint16_t b = src_is_bf16 ? ((const uint16_t*)src)[i] : f32_to_bf16_bits(((const float*)src)[i]);
     int row = (int)(i / K);
     if (perm_h > 0) row = row / perm_h * perm_h + qkv_packed_pos(row % perm_h, perm_r);
-    dst[kblk_off(row0 + row, (int)(i % K), rows_total)] = f32_to_f16_bits(bf16_bits_to_f32(b));
+    dst[kblk_off(row0 + row, (int)(i % K), rows_total)] = as_bf16 ? b : f32_to_f16_bits(bf16_bits_to_f32(b));
   }
 }
 __global__ void to_f32_kernel(float* dst, const void* src, int src_is_bf16, size_t n, int perm_h, int perm_r) {
@@ -33,7 +34,7 @@ __global__ void to_f32_kernel(float* dst, const void* src, int src_is_bf16, size
     dst[o] = v;
   }
 }
-__global__ void pack_gate_up_kernel(uint16_t* dst, const void* gate, const void* up, int src_is_bf16, int F, int d) {
+__global__ void pack_gate_up_kernel(uint16_t* dst, const void* gate, const void* up, int src_is_bf16, int F, int d, int as_bf16) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const size_t n = (size_t)2 * F * d, stride = (size_t)gridDim.x * blockDim.x;
   for (; i < n; i += stride) {
@@ -42,7 +43,7 @@ __global__ void pack_gate_up_kernel(uint16_t* dst, const void* gate, const void*
     const void* src = (blk & 1) ? up : gate;
     const size_t si = (size_t)((blk >> 1) * 32 + in) * d + col;
     const uint16_t b = src_is_bf16 ? ((const uint16_t*)src)[si] : f32_to_bf16_bits(((const float*)src)[si]);
-    dst[kblk_off(row, col, 2 * F)] = f32_to_f16_bits(bf16_bits_to_f32(b));
+    dst[kblk_off(row, col, 2 * F)] = as_bf16 ? b : f32_to_f16_bits(bf16_bits_to_f32(b));
   }
 }
 __global__ void rope_table_kernel(float2* tab, int max_pos, int r, double theta) {
@@ -59,13 +60,14 @@ __global__ void fill_zero_kernel(u32x4* p, size_t n16) {
   for (; i < n16; i += stride) p[i] = u32x4{0, 0, 0, 0};
 }
 
-__global__ void fill_random_f16_kernel(uint16_t* p, size_t n, unsigned seed) {
+__global__ void fill_random_f16_kernel(uint16_t* p, size_t n, unsigned seed, int as_bf16) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const size_t stride = (size_t)gridDim.x * blockDim.x;
   for (; i < n; i += stride) {
     unsigned x = (unsigned)i * 2654435761u + seed;
     x ^= x >> 16; x *= 0x85ebca6bu; x ^= x >> 13;
-    p[i] = f32_to_f16_bits((x & 0xffff) / 65536.0f - 0.5f);
+    const float v = (x & 0xffff) / 65536.0f - 0.5f;
+    p[i] = as_bf16 ? f32_to_bf16_bits(v) : f32_to_f16_bits(v);
   }
 }
 
@@ -97,7 +99,7 @@ template <int NV>
 __global__ __launch_bounds__(256) void norm_kernel(const float* x, const int* row_index, int rows, int d, float eps,
                                                    const float* g1, const float* b1, uint16_t* out1,
                                                    const float* g2, const float* b2, uint16_t* out2,
-                                                   int out_rows, int out_row0, unsigned* status) {
+                                                   int out_rows, int out_row0, unsigned* status, size_t lo_off) {
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
@@ -140,8 +142,15 @@ __global__ __launch_bounds__(256) void norm_kernel(const float* x, const int* ro
       sat |= f16_out_of_range(y[e]);
     }
     u32x2 w;
-    w[0] = pack_f16x2(y[0], y[1]);
-    w[1] = pack_f16x2(y[2], y[3]);
+    if (lo_off) {          // precise mode: bf16 hi/lo pairs, the lo halves lo_off elements behind the hi halves
+      u32x2 wl;
+      SPLIT_BF16X2(y[0], y[1], w[0], wl[0]);
+      SPLIT_BF16X2(y[2], y[3], w[1], wl[1]);
+      *(u32x2*)(out1 + lo_off + kblk_off(out_row0 + row, col, out_rows)) = wl;
+    } else {
+      w[0] = pack_f16x2(y[0], y[1]);
+      w[1] = pack_f16x2(y[2], y[3]);
+    }
     *(u32x2*)(out1 + kblk_off(out_row0 + row, col, out_rows)) = w;
     if (out2) {
       const f32x4 gb = *(const f32x4*)(g2 + col);
@@ -152,12 +161,19 @@ __global__ __launch_bounds__(256) void norm_kernel(const float* x, const int* ro
         y[e] = v[i][e] * rstd * gb[e] + bb[e];
         sat |= f16_out_of_range(y[e]);
       }
-      w[0] = pack_f16x2(y[0], y[1]);
-      w[1] = pack_f16x2(y[2], y[3]);
+      if (lo_off) {
+        u32x2 wl;
+        SPLIT_BF16X2(y[0], y[1], w[0], wl[0]);
+        SPLIT_BF16X2(y[2], y[3], w[1], wl[1]);
+        *(u32x2*)(out2 + lo_off + kblk_off(out_row0 + row, col, out_rows)) = wl;
+      } else {
+        w[0] = pack_f16x2(y[0], y[1]);
+        w[1] = pack_f16x2(y[2], y[3]);
+      }
       *(u32x2*)(out2 + kblk_off(out_row0 + row, col, out_rows)) = w;
     }
   }
-  flag_f16_range(sat, status);
+  flag_f16_range(sat && lo_off == 0, status);        // bf16 pairs have fp32's range
 }
 
 // One thread per (row, head slot, 8-dim chunk).  Head slots: Hq query heads, Hkv key heads, Hkv
@@ -350,12 +366,12 @@ hipError_t rl_to_bf16(uint16_t* dst, const void* src, int src_is_bf16, size_t n,
   return hipGetLastError();
 }
 hipError_t rl_to_f16w(uint16_t* dst, const void* src, int src_is_bf16, int rows, int K, int rows_total, int row0, hipStream_t s,
-                      int perm_h, int perm_r) {
+                      int perm_h, int perm_r, int as_bf16) {
   if (perm_h > 0 && (rows % perm_h != 0 || perm_r % 4 != 0 || perm_r > perm_h)) return hipErrorInvalidValue;
   const size_t n = (size_t)rows * K;
   if (!n) return hipSuccess;
   hipLaunchKernelGGL(to_f16w_kernel, dim3(min(blocks_for(n), 65536)), dim3(TPB), 0, s, dst, src, src_is_bf16, rows, K, rows_total, row0,
-                     perm_h, perm_r);
+                     perm_h, perm_r, as_bf16);
   return hipGetLastError();
 }
 hipError_t rl_to_f32(float* dst, const void* src, int src_is_bf16, size_t n, hipStream_t s, int perm_h, int perm_r) {
@@ -364,9 +380,9 @@ hipError_t rl_to_f32(float* dst, const void* src, int src_is_bf16, size_t n, hip
   hipLaunchKernelGGL(to_f32_kernel, dim3(min(blocks_for(n), 65536)), dim3(TPB), 0, s, dst, src, src_is_bf16, n, perm_h, perm_r);
   return hipGetLastError();
 }
-hipError_t rl_pack_gate_up(uint16_t* dst, const void* gate, const void* up, int src_is_bf16, int F, int d, hipStream_t s) {
+hipError_t rl_pack_gate_up(uint16_t* dst, const void* gate, const void* up, int src_is_bf16, int F, int d, hipStream_t s, int as_bf16) {
   hipLaunchKernelGGL(pack_gate_up_kernel, dim3(min(blocks_for((size_t)2 * F * d), 65536)), dim3(TPB), 0, s, dst, gate, up,
-                     src_is_bf16, F, d);
+                     src_is_bf16, F, d, as_bf16);
   return hipGetLastError();
 }
 hipError_t rl_rope_table(float2* tab, int max_pos, int rotary_dim, float theta, hipStream_t s) {
@@ -381,9 +397,9 @@ hipError_t rl_fill_zero(void* p, size_t bytes, hipStream_t s) {
   hipLaunchKernelGGL(fill_zero_kernel, dim3(min(blocks_for(bytes / 16), 262144)), dim3(TPB), 0, s, (u32x4*)p, bytes / 16);
   return hipGetLastError();
 }
-hipError_t rl_fill_random_f16(uint16_t* p, size_t n, unsigned seed, hipStream_t s) {
+hipError_t rl_fill_random_f16(uint16_t* p, size_t n, unsigned seed, hipStream_t s, int as_bf16) {
   if (!n) return hipSuccess;
-  hipLaunchKernelGGL(fill_random_f16_kernel, dim3(min(blocks_for(n), 65536)), dim3(TPB), 0, s, p, n, seed);
+  hipLaunchKernelGGL(fill_random_f16_kernel, dim3(min(blocks_for(n), 65536)), dim3(TPB), 0, s, p, n, seed, as_bf16);
   return hipGetLastError();
 }
 hipError_t rl_embed(float* x, const uint16_t* E, const int* tokens, const int* tok_index, int rows, int d, int vocab,
@@ -394,11 +410,11 @@ hipError_t rl_embed(float* x, const uint16_t* E, const int* tokens, const int* t
 }
 hipError_t rl_norm(const float* x, const int* row_index, int rows, int d, float eps, const float* g1, const float* b1,
                    uint16_t* out1, const float* g2, const float* b2, uint16_t* out2, int out_rows, int out_row0,
-                   unsigned* status, hipStream_t s) {
+                   unsigned* status, hipStream_t s, size_t lo_off) {
   if (rows <= 0) return hipSuccess;
   const dim3 grid((rows + 3) / 4), block(256);
   const int nv = (d + 255) / 256;
-#define NORM(NV) hipLaunchKernelGGL((norm_kernel<NV>), grid, block, 0, s, x, row_index, rows, d, eps, g1, b1, out1, g2, b2, out2, out_rows, out_row0, status)
+#define NORM(NV) hipLaunchKernelGGL((norm_kernel<NV>), grid, block, 0, s, x, row_index, rows, d, eps, g1, b1, out1, g2, b2, out2, out_rows, out_row0, status, lo_off)
   if (nv <= 1) NORM(1);
   else if (nv <= 2) NORM(2);
   else if (nv <= 4) NORM(4);

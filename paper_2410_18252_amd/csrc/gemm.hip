@@ -66,7 +66,9 @@ __device__ __forceinline__ void wait_loads_then_barrier() {
 
 // NS = 0: tiles travel global -> registers -> LDS (two LDS stages).  NS >= 2: NS LDS stages filled by direct
 // global -> LDS loads, issued NS - 1 K steps ahead (needs K % 64 == 0).
-template <int BM, int BN, int WM, int WN, int EPI, bool KTAIL, int NS = 0>
+// PR: precise mode (see GemmArgs): bf16 operands, A as hi/lo pairs, the K loop runs over the hi blocks and then the
+// lo blocks of A against the same blocks of W.
+template <int BM, int BN, int WM, int WN, int EPI, bool KTAIL, int NS = 0, bool PR = false>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_f16_kernel(GemmArgs g) {
   constexpr int NT = WM * WN * 64;               // threads
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;   // 32x32 MFMA tiles per wave in each direction
@@ -108,19 +110,27 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f16_kernel(GemmArgs g) {
     pb[i] = W + (size_t)r * 64 + ld_chunk * 8;
   }
   const size_t ka = (size_t)g.M * 64, kw = (size_t)g.N * 64;    // elements between K tiles
+  const int nkb = (g.K + BK - 1) / BK;                          // K blocks of W (and of each half of a hi/lo A)
+  // K tile kt of the loop reads block kt of A and block wk(kt) of W
+  auto wk = [&](int kt) { return PR && kt >= nkb ? kt - nkb : kt; };
   auto load_global = [&](int kt) {
     if constexpr (KTAIL) {     // K is not a multiple of BK: chunks beyond K read as zero
-      const bool ok = kt * BK + ld_chunk * 8 < g.K;
+      const bool ok = wk(kt) * BK + ld_chunk * 8 < g.K;
 #pragma unroll
       for (int i = 0; i < PA; ++i) ra[i] = ok ? *(const u32x4*)(pa[i] + kt * ka) : u32x4{0, 0, 0, 0};
 #pragma unroll
-      for (int i = 0; i < PB; ++i) rb[i] = ok ? *(const u32x4*)(pb[i] + kt * kw) : u32x4{0, 0, 0, 0};
+      for (int i = 0; i < PB; ++i) rb[i] = ok ? *(const u32x4*)(pb[i] + wk(kt) * kw) : u32x4{0, 0, 0, 0};
     } else {
 #pragma unroll
       for (int i = 0; i < PA; ++i) ra[i] = *(const u32x4*)(pa[i] + kt * ka);
 #pragma unroll
-      for (int i = 0; i < PB; ++i) rb[i] = *(const u32x4*)(pb[i] + kt * kw);
+      for (int i = 0; i < PB; ++i) rb[i] = *(const u32x4*)(pb[i] + wk(kt) * kw);
     }
+  };
+  // one 32x32x16 matrix instruction on 16-bit fragments: fp16, or bf16 in precise mode
+  auto mfma = [](f16x8 b, f16x8 a, f32x16 c) {
+    if constexpr (PR) return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, b), __builtin_bit_cast(bf16x8, a), c, 0, 0, 0);
+    else return __builtin_amdgcn_mfma_f32_32x32x16_f16(b, a, c, 0, 0, 0);
   };
   auto store_lds = [&](int buf) {
     uint16_t* la = lds + buf * STAGE;
@@ -145,7 +155,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f16_kernel(GemmArgs g) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  const int nk_all = (g.K + BK - 1) / BK;
+  const int nk_all = PR ? 2 * nkb : nkb;
   const int kt0 = (int)((long long)split * nk_all / splits);          // this block's share of the K tiles
   const int nk = (int)((long long)(split + 1) * nk_all / splits);
   const int frow = lane & 31, fhalf = lane >> 5;
@@ -177,7 +187,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f16_kernel(GemmArgs g) {
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[kk & 1][j], fa[kk & 1][i], acc[i][j], 0, 0, 0);
+          acc[i][j] = mfma(fb[kk & 1][j], fa[kk & 1][i], acc[i][j]);
     }
   };
 
@@ -215,7 +225,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f16_kernel(GemmArgs g) {
         __builtin_amdgcn_global_load_lds((gptr_t)(qa[i] + kt * ka), (lptr_t)(la + i * RPP * BK), 16, 0, 0);
 #pragma unroll
       for (int i = 0; i < PB; ++i)
-        __builtin_amdgcn_global_load_lds((gptr_t)(qb[i] + kt * kw), (lptr_t)(la + (BM + i * RPP) * BK), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((gptr_t)(qb[i] + wk(kt) * kw), (lptr_t)(la + (BM + i * RPP) * BK), 16, 0, 0);
     };
     constexpr int L = PA + PB;                      // loads per wave and stage
     if constexpr (NS == 2) {
@@ -244,8 +254,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f16_kernel(GemmArgs g) {
 #pragma unroll
         for (int t = 0; t < TM * TN; ++t)
           if (t >= lo && t < hi)
-            acc[t / TN][t % TN] =
-                __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[slot][t % TN], fa[slot][t / TN], acc[t / TN][t % TN], 0, 0, 0);
+            acc[t / TN][t % TN] = mfma(fb[slot][t % TN], fa[slot][t / TN], acc[t / TN][t % TN]);
       };
       issue(kt0, 0);
       wait_loads_then_barrier<0>();
@@ -356,7 +365,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f16_kernel(GemmArgs g) {
         const QkvEpi& e = g.qe;
         const int qpos = e.pos[row] + e.pos_add;
         rope_row = e.table + (size_t)qpos * (e.r >> 1);
-        q_row = e.q + (size_t)row * (e.Hq * e.h);
+        q_row = e.q + (size_t)row * (e.Hq * e.h) * (PR ? 2 : 1);         // precise: a row of floats
         if (e.kvstage) {
           stage_row = e.kvstage + (size_t)row * (2 * e.Hkv * e.h);
         } else {
@@ -415,6 +424,37 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f16_kernel(GemmArgs g) {
               const float lo1 = v[1] * cs[2] - v[3] * cs[3], hi1 = v[3] * cs[2] + v[1] * cs[3];
               v[0] = lo0; v[1] = lo1; v[2] = hi0; v[3] = hi1;
             }
+            if constexpr (PR) {
+              // precise mode: q stays fp32; keys and values are stored as bf16 hi/lo pairs (the lo halves a fixed
+              // distance behind the hi halves)
+              if (head < e.Hq) {
+                float* qp = (float*)q_row + head * e.h;
+                *(float2*)(qp + d0) = make_float2(v[0], v[1]);
+                *(float2*)(qp + d1) = make_float2(v[2], v[3]);
+              } else {
+                uint32_t h01, l01, h23, l23;
+                SPLIT_BF16X2(v[0], v[1], h01, l01);
+                SPLIT_BF16X2(v[2], v[3], h23, l23);
+                if (e.kvstage) {
+                  uint16_t* sp = stage_row + (head - e.Hq) * e.h;
+                  *(uint32_t*)(sp + d0) = h01;
+                  *(uint32_t*)(sp + d1) = h23;
+                  *(uint32_t*)(sp + e.stage_lo_off + d0) = l01;
+                  *(uint32_t*)(sp + e.stage_lo_off + d1) = l23;
+                } else if (!is_v) {
+                  uint16_t* st = k_row + (size_t)(head - e.Hq) * per_head;
+                  *(uint32_t*)(st + ((d0 >> 3) << 7) + (d0 & 7)) = h01;
+                  *(uint32_t*)(st + ((d1 >> 3) << 7) + (d1 & 7)) = h23;
+                  *(uint32_t*)(st + e.kv_lo_off + ((d0 >> 3) << 7) + (d0 & 7)) = l01;
+                  *(uint32_t*)(st + e.kv_lo_off + ((d1 >> 3) << 7) + (d1 & 7)) = l23;
+                } else {
+                  uint16_t* st = v_row + (size_t)(head - e.Hq - e.Hkv) * per_head + ((p0 >> 4) << 9) + ((p0 & 15) << 3);
+                  st[0] = (uint16_t)h01; st[8] = (uint16_t)(h01 >> 16); st[16] = (uint16_t)h23; st[24] = (uint16_t)(h23 >> 16);
+                  st += e.kv_lo_off;
+                  st[0] = (uint16_t)l01; st[8] = (uint16_t)(l01 >> 16); st[16] = (uint16_t)l23; st[24] = (uint16_t)(l23 >> 16);
+                }
+              }
+            } else {
             // q is fp16; cached keys and values are bf16 but enter the attention products as fp16
 #pragma unroll
             for (int r = 0; r < 4; ++r) sat |= f16_out_of_range(v[r]);
@@ -437,14 +477,28 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f16_kernel(GemmArgs g) {
 #pragma unroll
               for (int r = 0; r < 4; ++r) st[r << 3] = f32_to_bf16_bits(v[r]);
             }
+            }
           } else if constexpr (EPI == EPI_GELU_F16) {
             uint16_t* p = (uint16_t*)g.out + kblk_off(row, col, g.M);     // four columns never straddle a K block
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
               v[r] = gelu_erf(v[r]);
-              sat |= f16_out_of_range(v[r]) && col + r < g.N;
+              if constexpr (!PR) sat |= f16_out_of_range(v[r]) && col + r < g.N;
             }
-            if (full) {
+            if constexpr (PR) {
+              u32x2 wh, wl;
+              SPLIT_BF16X2(v[0], v[1], wh[0], wl[0]);
+              SPLIT_BF16X2(v[2], v[3], wh[1], wl[1]);
+              if (full) {
+                *(u32x2*)p = wh;
+                *(u32x2*)(p + g.out_lo_off) = wl;
+              } else {
+                for (int r = 0; r < 4 && col + r < g.N; ++r) {
+                  p[r] = (uint16_t)(wh[r >> 1] >> (16 * (r & 1)));
+                  p[g.out_lo_off + r] = (uint16_t)(wl[r >> 1] >> (16 * (r & 1)));
+                }
+              }
+            } else if (full) {
               u32x2 w;
               w[0] = pack_f16x2(v[0], v[1]);
               w[1] = pack_f16x2(v[2], v[3]);
@@ -463,11 +517,19 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f16_kernel(GemmArgs g) {
 #pragma unroll
               for (int r = 0; r < 4; ++r) {
                 v[r] = silu(v[r]) * acc[i][ju][4 * q + r];
-                sat |= f16_out_of_range(v[r]);
+                if constexpr (!PR) sat |= f16_out_of_range(v[r]);
               }
-              w[0] = pack_f16x2(v[0], v[1]);
-              w[1] = pack_f16x2(v[2], v[3]);
-              *(u32x2*)((uint16_t*)g.out + kblk_off(row, f, g.M)) = w;
+              uint16_t* p = (uint16_t*)g.out + kblk_off(row, f, g.M);
+              if constexpr (PR) {
+                u32x2 wl;
+                SPLIT_BF16X2(v[0], v[1], w[0], wl[0]);
+                SPLIT_BF16X2(v[2], v[3], w[1], wl[1]);
+                *(u32x2*)(p + g.out_lo_off) = wl;
+              } else {
+                w[0] = pack_f16x2(v[0], v[1]);
+                w[1] = pack_f16x2(v[2], v[3]);
+              }
+              *(u32x2*)p = w;
             }
           }
         }
@@ -495,12 +557,17 @@ __global__ void splitk_epilogue_kernel(GemmArgs g) {
     *p = *p + v;
   } else if constexpr (EPI == EPI_GELU_F16) {
     v = gelu_erf(v);
-    flag_f16_range(f16_out_of_range(v), g.status);
-    ((uint16_t*)g.out)[kblk_off(row, col, g.M)] = f32_to_f16_bits(v);
+    uint16_t* p = (uint16_t*)g.out + kblk_off(row, col, g.M);
+    if (g.precise) {
+      split_bf16(v, p[0], p[g.out_lo_off]);
+    } else {
+      flag_f16_range(f16_out_of_range(v), g.status);
+      *p = f32_to_f16_bits(v);
+    }
   }
 }
 
-template <int BM, int BN, int WM, int WN, int EPI, bool KTAIL, int NS = 0>
+template <int BM, int BN, int WM, int WN, int EPI, bool KTAIL, int NS = 0, bool PR = false>
 hipError_t launch_k(const GemmArgs& g, hipStream_t s) {
   constexpr size_t lds_bytes = (NS ? NS : 2) * (size_t)(BM + BN) * BK * sizeof(uint16_t);
   static_assert(lds_bytes <= 160 * 1024, "LDS of one CU");
@@ -511,26 +578,41 @@ hipError_t launch_k(const GemmArgs& g, hipStream_t s) {
   bool& configured = configured_on[dev];
   if (!configured) {
     if (lds_bytes > 65536) {
-      hipError_t e = hipFuncSetAttribute((const void*)gemm_f16_kernel<BM, BN, WM, WN, EPI, KTAIL, NS>,
+      hipError_t e = hipFuncSetAttribute((const void*)gemm_f16_kernel<BM, BN, WM, WN, EPI, KTAIL, NS, PR>,
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
       if (e != hipSuccess) return e;
     }
     configured = true;
   }
   const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN) * (EPI == EPI_PARTIAL ? g.splits : 1);
-  hipLaunchKernelGGL((gemm_f16_kernel<BM, BN, WM, WN, EPI, KTAIL, NS>), dim3(tiles), dim3(WM * WN * 64), lds_bytes, s, g);
+  hipLaunchKernelGGL((gemm_f16_kernel<BM, BN, WM, WN, EPI, KTAIL, NS, PR>), dim3(tiles), dim3(WM * WN * 64), lds_bytes, s, g);
   return hipGetLastError();
 }
 
 // Whole K tiles take the direct-load pipeline with two LDS stages (more stages measured slower: the extra LDS
 // costs a resident block); a ragged K falls back to register staging, which can zero-fill the tail.
-template <int BM, int BN, int WM, int WN, int EPI, int NS = 2>
+template <int BM, int BN, int WM, int WN, int EPI, int NS = 2, bool PR = false>
 hipError_t launch(const GemmArgs& g, hipStream_t s) {
-  return g.K % BK == 0 ? launch_k<BM, BN, WM, WN, EPI, false, NS>(g, s) : launch_k<BM, BN, WM, WN, EPI, true, 0>(g, s);
+  return g.K % BK == 0 ? launch_k<BM, BN, WM, WN, EPI, false, NS, PR>(g, s) : launch_k<BM, BN, WM, WN, EPI, true, 0, PR>(g, s);
+}
+
+// precise mode is compiled for four of the tile shapes (128x128, 256x256, 256x128 with 8 waves, 64x128)
+template <int EPI>
+hipError_t launch_variant_precise(const GemmArgs& g, int variant, hipStream_t s) {
+  switch (variant) {
+    case 0: return launch<128, 128, 2, 2, EPI, 2, true>(g, s);
+    case 3: return launch<256, 256, 4, 2, EPI, 2, true>(g, s);
+    case 5: return launch<256, 128, 4, 2, EPI, 2, true>(g, s);
+    case 7:
+      if constexpr (EPI != EPI_SWIGLU_F16 && EPI != EPI_LMHEAD) return launch<64, 128, 1, 4, EPI, 2, true>(g, s);
+      else return hipErrorInvalidValue;
+  }
+  return hipErrorInvalidValue;
 }
 
 template <int EPI>
 hipError_t launch_variant(const GemmArgs& g, int variant, hipStream_t s) {
+  if (g.precise) return launch_variant_precise<EPI>(g, variant, s);
   switch (variant) {
     case 0: return launch<128, 128, 2, 2, EPI>(g, s);
     case 1: return launch<256, 128, 2, 2, EPI>(g, s);

@@ -42,6 +42,9 @@ enum { EPI_F32 = 0, EPI_RESID = 1, EPI_GELU_F16 = 2, EPI_SWIGLU_F16 = 3, EPI_LMH
 // in four consecutive output columns, which one lane holds.  Requires r % 4 == 0.
 struct QkvEpi {
   int Hq, Hkv, h, r;
+  // precise mode: q is written as fp32 [M, Hq h] (q points at floats); keys and values as bf16 hi/lo pairs, the lo
+  // halves kv_lo_off elements behind the hi halves in the cache and stage_lo_off elements behind them in the staging rows
+  long long kv_lo_off, stage_lo_off;
   float inv_h;                   // 1 / h
   const float2* table;           // [max_pos, r/2] cos, sin
   const int* pos; int pos_add;   // position of row i = pos[i] + pos_add
@@ -67,6 +70,11 @@ struct GemmArgs {
   const void* A;                // [M, K] fp16, K-block major (kblk_off with rows = M)
   const void* W;                // [N, K] fp16, K-block major (rows = N)
   int M, N, K;
+  // Precise mode (precise = 1): W holds bf16 bit patterns; A is a bf16 hi/lo pair per element, stored as a matrix of
+  // twice the K blocks (the hi blocks, then the lo blocks: kblk_elems(M, K) elements apart), and the product is
+  // A_hi W^T + A_lo W^T on the bf16 matrix instructions: 16 significant bits of every activation instead of fp16's 11.
+  // The *_F16 epilogues then write bf16 hi/lo pairs too, the lo halves out_lo_off elements behind the hi halves.
+  int precise; size_t out_lo_off;
   const float* bias;            // [N] or null
   void* out; int ldo;           // EPI_F32 / EPI_RESID: fp32 [M, N] row-major, leading dim ldo;
                                 // *_F16: fp16 K-block major with rows = M (ldo unused)
@@ -94,6 +102,9 @@ struct AttnJob { int cache_seq, row0, len, qblock, pre_seq, pre_len; };
 struct AttnArgs {
   const uint16_t* q; int q_ld;        // fp16 [rows, Hq * h], rotated
   uint16_t* out; int out_rows;        // fp16 [out_rows, Hq * h], K-block major (input of the O projection)
+  // precise mode: q points at fp32 [rows, Hq * h]; the cache holds bf16 hi/lo pairs, the lo halves kv_lo_off elements
+  // behind the hi halves; the output is bf16 hi/lo pairs, the lo halves out_lo_off elements behind the hi halves
+  int precise; long long kv_lo_off; size_t out_lo_off;
   const uint16_t* kv;                 // this layer's cache base
   KvLayout lay;
   const int* kv_off; const int* kv_cap;  // per cache sequence
@@ -122,18 +133,19 @@ hipError_t rl_to_bf16(uint16_t* dst, const void* src, int src_is_bf16, size_t n,
 // dst fp16 K-block major [rows_total, K] <- the bf16 values of src [rows, K] row-major placed at rows
 // row0 .. row0 + rows - 1 (fp32 sources are first rounded to bf16, nearest even)
 // perm_h > 0: source row head * perm_h + dim lands at row head * perm_h + qkv_packed_pos(dim, perm_r)
+// as_bf16: store the bf16 bit patterns themselves (the weight format of precise mode)
 hipError_t rl_to_f16w(uint16_t* dst, const void* src, int src_is_bf16, int rows, int K, int rows_total, int row0, hipStream_t s,
-                      int perm_h = 0, int perm_r = 0);
+                      int perm_h = 0, int perm_r = 0, int as_bf16 = 0);
 // dst fp32 <- src (fp32 copied, or bf16 expanded); n elements
 // perm_h > 0: element head * perm_h + dim lands at head * perm_h + qkv_packed_pos(dim, perm_r)
 hipError_t rl_to_f32(float* dst, const void* src, int src_is_bf16, size_t n, hipStream_t s, int perm_h = 0, int perm_r = 0);
 // gate/up rows interleaved in blocks of 32 rows: dst [2F, d] fp16 (bf16 values), K-block major
-hipError_t rl_pack_gate_up(uint16_t* dst, const void* gate, const void* up, int src_is_bf16, int F, int d, hipStream_t s);
+hipError_t rl_pack_gate_up(uint16_t* dst, const void* gate, const void* up, int src_is_bf16, int F, int d, hipStream_t s, int as_bf16 = 0);
 // cos/sin table [max_pos, r/2] (float2), angles pos * theta^(-2i/r) evaluated in fp64
 hipError_t rl_rope_table(float2* tab, int max_pos, int rotary_dim, float theta, hipStream_t s);
 hipError_t rl_fill_zero(void* p, size_t bytes, hipStream_t s);
 // n pseudo-random fp16 values in [-0.5, 0.5) (inputs for timing runs)
-hipError_t rl_fill_random_f16(uint16_t* p, size_t n, unsigned seed, hipStream_t s);
+hipError_t rl_fill_random_f16(uint16_t* p, size_t n, unsigned seed, hipStream_t s, int as_bf16 = 0);
 
 // x[row, :] = float(E[tok[row]]), tok gathered as tokens[tok_index[row]] ; flags a bad id
 hipError_t rl_embed(float* x, const uint16_t* E, const int* tokens, const int* tok_index, int rows, int d,
@@ -142,9 +154,10 @@ hipError_t rl_embed(float* x, const uint16_t* E, const int* tokens, const int* t
 // row with other gains, NeoX); b1 null selects RMSNorm.  row_index nullable: source row of output row i.
 // Outputs are K-block major matrices of out_rows rows; output row i goes to row out_row0 + i.
 // status (nullable): receives RLGEN_FAULT_RANGE if a normalised value does not fit fp16 (it is clamped).
+// lo_off > 0 (precise mode): outputs are bf16 hi/lo pairs, the lo halves lo_off elements behind the hi halves.
 hipError_t rl_norm(const float* x, const int* row_index, int rows, int d, float eps, const float* g1,
                    const float* b1, uint16_t* out1, const float* g2, const float* b2, uint16_t* out2,
-                   int out_rows, int out_row0, unsigned* status, hipStream_t s);
+                   int out_rows, int out_row0, unsigned* status, hipStream_t s, size_t lo_off = 0);
 
 // Rotary + KV write.  qkv fp32 [rows, (Hq + 2 Hkv) h] (bias already added) ->
 //   q fp16 [rows, Hq h] rotated; k (rotated) and v written as bf16 to the cache of `ncopy` consecutive cache
@@ -172,6 +185,8 @@ hipError_t rl_rope_kv(const RopeArgs& a, hipStream_t s);
 // log Z, find the column group where the CDF crosses u, recompute that group's 64 logits from hfin and
 // the LM head, scan it, and emit token and log-prob.  forced nullable.  Output index out_index[row].
 struct SampleArgs {
+  int precise;                          // hfin holds bf16 hi/lo pairs (lo halves hfin_lo_off elements behind), lm_head bf16
+  size_t hfin_lo_off;
   const float2* partial; int ngroups;
   const uint16_t* hfin; int d;          // fp16 [R, d] rows fed to the LM head GEMM (K-block major)
   const uint16_t* lm_head; int vocab;   // fp16 [V, d] (K-block major)

@@ -129,6 +129,10 @@ struct rlgen_ctx {
   // [decode of max_seqs rows | prompt pass | decode of half of max_seqs rows][which GEMM]
   struct GemmChoice { int variant, splits; } tuned[3][5];
   bool half_rows;         // the decode steps being enqueued cover half of the batch
+  // precise mode (cfg.precise): 16-bit activations and cached keys/values are bf16 hi/lo pairs.  pw = 2 then (else 1):
+  // 16-bit values per activation element; kv_plane = elements between the hi and the lo plane of the cache
+  int pw;
+  long long kv_plane;
   int device;             // the device the context was created on
 };
 
@@ -155,6 +159,8 @@ int check_cfg(const rlgen_model_cfg* c) {
   if (c->max_batch_tokens != 0 && c->max_batch_tokens < c->max_seq_len) return RLGEN_ERR_BAD_CFG;
   if (c->max_batch_tokens > (1 << 22)) return RLGEN_ERR_BAD_CFG;
   if (c->share_prompt_kv != 0 && c->share_prompt_kv != 1) return RLGEN_ERR_BAD_CFG;
+  // precise mode runs the fused QKV epilogue only and keeps two cache planes per attention wave in registers
+  if (c->precise != 0 && (c->precise != 1 || c->rotary_dim % 4 != 0 || h > 128)) return RLGEN_ERR_BAD_CFG;
   return RLGEN_OK;
 }
 
@@ -199,7 +205,9 @@ size_t carve(rlgen_ctx* c, char* base) {
   c->lay.Hkv = m.n_kv_heads;
   c->lay.h = m.head_dim;
   c->lay.layer_stride = 2LL * m.max_kv_tokens * m.n_kv_heads * m.head_dim;
-  c->kv = k.take<uint16_t>(base, (size_t)c->lay.layer_stride * m.n_layers);
+  c->pw = m.precise ? 2 : 1;
+  c->kv_plane = c->lay.layer_stride * m.n_layers;
+  c->kv = k.take<uint16_t>(base, (size_t)c->kv_plane * c->pw);
   c->d_meta = k.take<SeqMeta>(base, 2 * S);       // grouped scoring adds one shared prefix per group
   c->d_kv_off = k.take<int>(base, 2 * S); c->d_kv_cap = k.take<int>(base, 2 * S);   // prompt + per-sequence streams
   c->d_ctx_base = k.take<int>(base, S); c->d_iota = k.take<int>(base, S);
@@ -215,13 +223,14 @@ size_t carve(rlgen_ctx* c, char* base) {
     const size_t rows = i == 0 ? R : (size_t)c->Sg, lm = i == 0 ? LM : (size_t)c->Sg;
     rlgen_ctx::Bufs& b = c->set[i];
     b.x = k.take<float>(base, rows * d);
-    b.n1 = k.take<uint16_t>(base, kblk_elems(rows, d));
-    b.n2 = k.take<uint16_t>(base, kblk_elems(rows, d));
+    const size_t pw = c->pw;                   // precise mode: hi and lo halves (q: fp32)
+    b.n1 = k.take<uint16_t>(base, pw * kblk_elems(rows, d));
+    b.n2 = k.take<uint16_t>(base, pw * kblk_elems(rows, d));
     b.qkv = k.take<float>(base, rows * nqkv);
-    b.q = k.take<uint16_t>(base, rows * qd);
-    b.attn = k.take<uint16_t>(base, kblk_elems(rows, qd));
-    b.act = k.take<uint16_t>(base, kblk_elems(rows, F));
-    b.hfin = k.take<uint16_t>(base, kblk_elems(lm, d));
+    b.q = k.take<uint16_t>(base, pw * rows * qd);
+    b.attn = k.take<uint16_t>(base, pw * kblk_elems(rows, qd));
+    b.act = k.take<uint16_t>(base, pw * kblk_elems(rows, F));
+    b.hfin = k.take<uint16_t>(base, pw * kblk_elems(lm, d));
     b.partial = k.take<float2>(base, lm * (size_t)c->ngroups);
     b.target_logit = k.take<float>(base, lm);
     b.splitk_elems = (size_t)12 << 20;          // 48 MB of split-K partial sums
@@ -249,7 +258,8 @@ int pack_weights(rlgen_ctx* c, const rlgen_weights* w, hipStream_t st) {
       return RLGEN_ERR_NULL;
   }
   HIPCHK(rl_to_bf16(c->embed, w->embed_in, bf, V * d, st));
-  HIPCHK(rl_to_f16w(c->lm_head, w->lm_head, bf, (int)V, (int)d, (int)V, 0, st));
+  const int pb = m.precise;           // precise mode keeps the bf16 bit patterns
+  HIPCHK(rl_to_f16w(c->lm_head, w->lm_head, bf, (int)V, (int)d, (int)V, 0, st, 0, 0, pb));
   HIPCHK(rl_to_f32(c->fng, w->final_norm_g, bf, d, st));
   if (!llama) HIPCHK(rl_to_f32(c->fnb, w->final_norm_b, bf, d, st));
   for (int l = 0; l < m.n_layers; ++l) {
@@ -259,15 +269,15 @@ int pack_weights(rlgen_ctx* c, const rlgen_weights* w, hipStream_t st) {
     HIPCHK(rl_to_f32(L.n2g, s.norm2_g, bf, d, st));
     // fused QKV epilogue: query and key rows of a head in the order that puts rotary pairs side by side
     const int ph = c->fused_qkv ? (int)h : 0, pr = m.rotary_dim;
-    HIPCHK(rl_to_f16w(L.wqkv, s.wq, bf, (int)qd, (int)d, nqkv, 0, st, ph, pr));
-    HIPCHK(rl_to_f16w(L.wqkv, s.wk, bf, (int)kvd, (int)d, nqkv, (int)qd, st, ph, pr));
-    HIPCHK(rl_to_f16w(L.wqkv, s.wv, bf, (int)kvd, (int)d, nqkv, (int)(qd + kvd), st));
-    HIPCHK(rl_to_f16w(L.wo, s.wo, bf, (int)d, (int)qd, (int)d, 0, st));
-    HIPCHK(rl_to_f16w(L.wdown, s.w_down, bf, (int)d, (int)F, (int)d, 0, st));
+    HIPCHK(rl_to_f16w(L.wqkv, s.wq, bf, (int)qd, (int)d, nqkv, 0, st, ph, pr, pb));
+    HIPCHK(rl_to_f16w(L.wqkv, s.wk, bf, (int)kvd, (int)d, nqkv, (int)qd, st, ph, pr, pb));
+    HIPCHK(rl_to_f16w(L.wqkv, s.wv, bf, (int)kvd, (int)d, nqkv, (int)(qd + kvd), st, 0, 0, pb));
+    HIPCHK(rl_to_f16w(L.wo, s.wo, bf, (int)d, (int)qd, (int)d, 0, st, 0, 0, pb));
+    HIPCHK(rl_to_f16w(L.wdown, s.w_down, bf, (int)d, (int)F, (int)d, 0, st, 0, 0, pb));
     if (llama) {
-      HIPCHK(rl_pack_gate_up(L.wup, s.w_gate, s.w_up, bf, (int)F, (int)d, st));
+      HIPCHK(rl_pack_gate_up(L.wup, s.w_gate, s.w_up, bf, (int)F, (int)d, st, pb));
     } else {
-      HIPCHK(rl_to_f16w(L.wup, s.w_up, bf, (int)F, (int)d, (int)F, 0, st));
+      HIPCHK(rl_to_f16w(L.wup, s.w_up, bf, (int)F, (int)d, (int)F, 0, st, 0, 0, pb));
       HIPCHK(rl_to_f32(L.n1b, s.norm1_b, bf, d, st));
       HIPCHK(rl_to_f32(L.n2b, s.norm2_b, bf, d, st));
       HIPCHK(rl_to_f32(L.bqkv, s.bq, bf, qd, st, ph, pr));
@@ -379,8 +389,10 @@ hipError_t gemm(rlgen_ctx* c, int which, bool decode, const GemmArgs& g, int epi
   return run_choice(g, epi, c->tuned[mode][which].variant, c->tuned[decode ? 0 : 1][which].splits, st);
 }
 
-QkvEpi qkv_epilogue(const RopeArgs& r, uint16_t* kvstage) {
+QkvEpi qkv_epilogue(const rlgen_ctx* c, const RopeArgs& r, uint16_t* kvstage) {
   QkvEpi e{};
+  e.kv_lo_off = c->kv_plane;                                    // used in precise mode only
+  e.stage_lo_off = (long long)r.rows * 2 * r.Hkv * r.h;         // the lo staging rows follow the hi staging rows
   e.Hq = r.Hq; e.Hkv = r.Hkv; e.h = r.h; e.r = r.r; e.inv_h = 1.0f / (float)r.h;
   e.table = r.table; e.pos = r.pos; e.pos_add = r.pos_add; e.slot_sub = r.slot_sub; e.dst_seq = r.dst_seq;
   e.q = r.q; e.kv = r.kv; e.lay = r.lay; e.kv_off = r.kv_off; e.kv_cap = r.kv_cap; e.kvstage = kvstage;
@@ -410,9 +422,13 @@ int run_layers(rlgen_ctx* c, int rows, bool decode, int t, int ncopy, bool use_c
   for (int l = 0; l < m.n_layers; ++l) {
     const LayerW& L = c->layers[l];
     uint16_t* kvl = c->kv + (use_cache_layers ? (size_t)c->lay.layer_stride * l : 0);
-    if (llama) HIPCHK(rl_norm(c->x, nullptr, rows, d, m.norm_eps, L.n1g, nullptr, c->n1, nullptr, nullptr, nullptr, rows, 0, c->status, st));
-    else HIPCHK(rl_norm(c->x, nullptr, rows, d, m.norm_eps, L.n1g, L.n1b, c->n1, L.n2g, L.n2b, c->n2, rows, 0, c->status, st));
+    const int pr = m.precise;
+    // precise mode: distance between the hi and the lo halves of a 16-bit activation matrix of `rows` rows and K columns
+    auto lo_off = [&](int K) { return pr ? kblk_elems(rows, K) : (size_t)0; };
+    if (llama) HIPCHK(rl_norm(c->x, nullptr, rows, d, m.norm_eps, L.n1g, nullptr, c->n1, nullptr, nullptr, nullptr, rows, 0, c->status, st, lo_off(d)));
+    else HIPCHK(rl_norm(c->x, nullptr, rows, d, m.norm_eps, L.n1g, L.n1b, c->n1, L.n2g, L.n2b, c->n2, rows, 0, c->status, st, lo_off(d)));
     GemmArgs g{};
+    g.precise = pr;
     g.A = c->n1; g.W = L.wqkv; g.M = rows; g.N = nqkv; g.K = d;
     g.bias = llama ? nullptr : L.bqkv; g.out = c->qkv; g.ldo = nqkv; g.ws = c->splitk; g.ws_elems = c->splitk_elems;
     g.status = c->status;
@@ -427,12 +443,18 @@ int run_layers(rlgen_ctx* c, int rows, bool decode, int t, int ncopy, bool use_c
     else { r.pos = c->d_pos; r.pos_add = 0; r.dst_seq = c->d_dst_seq; r.ncopy = ncopy; r.v_by_blocks = 1; r.jobs = c->d_jobs; r.njobs = njobs; }
     if (c->fused_qkv) {
       // the prompt pass leaves k and v as bf16 rows in the (otherwise unused) fp32 qkv buffer for the block-wise writer
-      g.qe = qkv_epilogue(r, decode ? nullptr : (uint16_t*)c->qkv);
+      g.qe = qkv_epilogue(c, r, decode ? nullptr : (uint16_t*)c->qkv);
       g.ws = nullptr;
       HIPCHK(gemm(c, G_QKV, decode, g, EPI_QKV, st));
       if (!decode) {
         r.kvstage = (const uint16_t*)c->qkv;
         HIPCHK(rl_kv_prefill(r, st));
+        if (pr) {           // the lo halves: staged behind the hi rows, cached one plane further
+          RopeArgs rl = r;
+          rl.kvstage = r.kvstage + g.qe.stage_lo_off;
+          rl.kv = r.kv + c->kv_plane;
+          HIPCHK(rl_kv_prefill(rl, st));
+        }
       }
     } else {
       HIPCHK(gemm(c, G_QKV, decode, g, EPI_F32, st));
@@ -441,6 +463,7 @@ int run_layers(rlgen_ctx* c, int rows, bool decode, int t, int ncopy, bool use_c
     AttnArgs a{};
     a.q = c->q; a.q_ld = qd; a.out = c->attn; a.out_rows = rows; a.kv = kvl; a.lay = c->lay;
     a.kv_off = c->d_kv_off; a.kv_cap = c->d_kv_cap; a.Hq = m.n_q_heads; a.scale = 1.0f / sqrtf((float)h);
+    a.precise = pr; a.kv_lo_off = c->kv_plane; a.out_lo_off = lo_off(qd);
     if (decode) {
       // the kernel indexes sequences (prompts, if shared) from 0: hand it the arrays at this view's first entry
       const int u0 = c->share_k ? dv.b0 : dv.g0;
@@ -470,16 +493,19 @@ int run_layers(rlgen_ctx* c, int rows, bool decode, int t, int ncopy, bool use_c
       HIPCHK(rl_attention_prefill(a, st));
     }
     g = GemmArgs{};
+    g.precise = pr;
     g.A = c->attn; g.W = L.wo; g.M = rows; g.N = d; g.K = qd;
     g.bias = llama ? nullptr : L.bo; g.out = c->x; g.ldo = d; g.ws = c->splitk; g.ws_elems = c->splitk_elems;
     HIPCHK(gemm(c, G_O, decode, g, EPI_RESID, st));
-    if (llama) HIPCHK(rl_norm(c->x, nullptr, rows, d, m.norm_eps, L.n2g, nullptr, c->n2, nullptr, nullptr, nullptr, rows, 0, c->status, st));
+    if (llama) HIPCHK(rl_norm(c->x, nullptr, rows, d, m.norm_eps, L.n2g, nullptr, c->n2, nullptr, nullptr, nullptr, rows, 0, c->status, st, lo_off(d)));
     g = GemmArgs{};
+    g.precise = pr; g.out_lo_off = lo_off(F);
     g.A = c->n2; g.W = L.wup; g.M = rows; g.N = llama ? 2 * F : F; g.K = d;
     g.bias = llama ? nullptr : L.bup; g.out = c->act; g.ldo = F; g.ws = c->splitk; g.ws_elems = c->splitk_elems;
     g.status = c->status;
     HIPCHK(gemm(c, G_UP, decode, g, llama ? EPI_SWIGLU_F16 : EPI_GELU_F16, st));
     g = GemmArgs{};
+    g.precise = pr;
     g.A = c->act; g.W = L.wdown; g.M = rows; g.N = d; g.K = F;
     g.bias = llama ? nullptr : L.bdown; g.out = c->x; g.ldo = d; g.ws = c->splitk; g.ws_elems = c->splitk_elems;
     HIPCHK(gemm(c, G_DOWN, decode, g, EPI_RESID, st));
@@ -491,13 +517,14 @@ int run_layers(rlgen_ctx* c, int rows, bool decode, int t, int ncopy, bool use_c
 int final_norm(rlgen_ctx* c, const int* row_index, int rows, int out_rows, int out_row0, hipStream_t st) {
   const rlgen_model_cfg& m = c->cfg;
   HIPCHK(rl_norm(c->x, row_index, rows, m.d_model, m.norm_eps, c->fng, m.arch == RLGEN_ARCH_LLAMA ? nullptr : c->fnb, c->hfin,
-                 nullptr, nullptr, nullptr, out_rows, out_row0, c->status, st));
+                 nullptr, nullptr, nullptr, out_rows, out_row0, c->status, st, m.precise ? kblk_elems(out_rows, m.d_model) : 0));
   return RLGEN_OK;
 }
 
 int lm_head_stats(rlgen_ctx* c, const uint16_t* hfin, int rows, float temperature, const int* target, hipStream_t st) {
   GemmArgs g{};
   g.A = hfin; g.W = c->lm_head;   g.M = rows; g.N = c->cfg.vocab; g.K = c->cfg.d_model;
+  g.precise = c->cfg.precise;
   g.temperature = temperature; g.partial = c->partial; g.target = target; g.target_logit = c->target_logit;
   HIPCHK(gemm(c, G_LMHEAD, rows <= c->cfg.max_seqs, g, EPI_LMHEAD, st));
   return RLGEN_OK;
@@ -512,6 +539,7 @@ int sample_rows(rlgen_ctx* c, int rows, float temperature, const float* uniforms
   int rc = lm_head_stats(c, c->hfin, rows, temperature, nullptr, st);
   if (rc) return rc;
   SampleArgs s{};
+  s.precise = c->cfg.precise; s.hfin_lo_off = c->cfg.precise ? kblk_elems(rows, c->cfg.d_model) : 0;
   s.partial = c->partial; s.ngroups = c->ngroups; s.hfin = c->hfin; s.d = c->cfg.d_model;
   s.lm_head = c->lm_head; s.vocab = c->cfg.vocab; s.temperature = temperature;
   s.uniforms = uniforms; s.forced = forced; s.io_index = io_index; s.io_stride = io_stride; s.io_add = io_add;
@@ -570,11 +598,14 @@ int tune_gemms(rlgen_ctx* c, hipStream_t st) {
   const rlgen_model_cfg& m = c->cfg;
   const bool llama = m.arch == RLGEN_ARCH_LLAMA;
   const int d = m.d_model, F = m.d_ffn, qd = m.n_q_heads * m.head_dim, nqkv = qd + 2 * m.n_kv_heads * m.head_dim;
-  HIPCHK(rl_fill_random_f16(c->n1, kblk_elems(c->R, d), 11, st));
-  HIPCHK(rl_fill_random_f16(c->n2, kblk_elems(c->R, d), 12, st));
-  HIPCHK(rl_fill_random_f16(c->attn, kblk_elems(c->R, qd), 13, st));
-  HIPCHK(rl_fill_random_f16(c->act, kblk_elems(c->R, F), 14, st));
-  HIPCHK(rl_fill_random_f16(c->hfin, kblk_elems(c->LM, d), 15, st));
+  const int pr = m.precise;
+  const size_t pw = c->pw;
+  HIPCHK(rl_fill_random_f16(c->n1, pw * kblk_elems(c->R, d), 11, st, pr));
+  HIPCHK(rl_fill_random_f16(c->n2, pw * kblk_elems(c->R, d), 12, st, pr));
+  HIPCHK(rl_fill_random_f16(c->attn, pw * kblk_elems(c->R, qd), 13, st, pr));
+  HIPCHK(rl_fill_random_f16(c->act, pw * kblk_elems(c->R, F), 14, st, pr));
+  HIPCHK(rl_fill_random_f16(c->hfin, pw * kblk_elems(c->LM, d), 15, st, pr));
+  if (pr) HIPCHK(rl_fill_zero(c->q, align_up((size_t)c->R * qd * 4, 16), st));      // fp32 queries of the neighbour attention
   HIPCHK(rl_fill_zero(c->x, align_up((size_t)c->R * d * 4, 16), st));
   {
     const int tseq = (int)std::min<long long>(m.max_seqs, m.max_kv_tokens / 32);
@@ -608,6 +639,8 @@ int tune_gemms(rlgen_ctx* c, hipStream_t st) {
       nb.q = c->q; nb.q_ld = qd; nb.out = (uint16_t*)c->qkv; nb.out_rows = Sh; nb.kv = c->kv; nb.lay = c->lay;
       nb.kv_off = nb_meta; nb.kv_cap = nb_meta + Sh; nb.ctx_base = nb_meta + 2 * Sh; nb.ctx_add = 1; nb.S = Sh;
       nb.Hq = m.n_q_heads; nb.scale = 1.0f / sqrtf((float)m.head_dim);
+      nb.precise = pr; nb.kv_lo_off = c->kv_plane; nb.out_lo_off = pr ? kblk_elems(Sh, qd) : 0;
+      if (pr && ok) ok = rl_fill_zero(c->kv + c->kv_plane, (size_t)Sh * cap * 2 * m.n_kv_heads * m.head_dim * 2, st) == hipSuccess;
       for (int r = 0; ok && r < 2; ++r) {          // the second pair is the timed one
         ok = hipEventRecord(e0, st) == hipSuccess && rl_attention_decode(nb, st) == hipSuccess &&
              rl_attention_decode(nb, st) == hipSuccess && hipEventRecord(e1, st) == hipSuccess &&
@@ -621,6 +654,7 @@ int tune_gemms(rlgen_ctx* c, hipStream_t st) {
     const int mode = modes[mi];
     for (int which = 0; which < 5 && rc == RLGEN_OK; ++which) {
       GemmArgs g{};
+      g.precise = pr;
       int epi = EPI_F32;
       // a decode step sees max_seqs rows, or about half of them when the batch is split in two
       const int dec_rows = mode == 2 ? (m.max_seqs + 1) / 2 : m.max_seqs;
@@ -634,14 +668,15 @@ int tune_gemms(rlgen_ctx* c, hipStream_t st) {
             RopeArgs r{};
             r.Hq = m.n_q_heads; r.Hkv = m.n_kv_heads; r.h = m.head_dim; r.r = m.rotary_dim; r.table = c->rope; r.q = c->q;
             r.kv = c->kv; r.lay = c->lay; r.kv_off = c->d_kv_off; r.kv_cap = c->d_kv_cap;
-            r.pos = c->d_pos; r.dst_seq = c->d_dst_seq; r.ncopy = 1;
-            g.qe = qkv_epilogue(r, mode != 1 ? nullptr : (uint16_t*)c->qkv);
+            r.pos = c->d_pos; r.dst_seq = c->d_dst_seq; r.ncopy = 1; r.rows = g.M;
+            g.qe = qkv_epilogue(c, r, mode != 1 ? nullptr : (uint16_t*)c->qkv);
             g.ws = nullptr;          // the fused epilogue has no split-K form
             epi = EPI_QKV;
           }
           break;
         case G_O: g.A = c->attn; g.W = L.wo; g.N = d; g.K = qd; g.bias = llama ? nullptr : L.bo; g.out = c->x; g.ldo = d; epi = EPI_RESID; break;
         case G_UP: g.A = c->n2; g.W = L.wup; g.N = llama ? 2 * F : F; g.K = d; g.bias = llama ? nullptr : L.bup; g.out = c->act; g.ldo = F;
+                   g.out_lo_off = pr ? kblk_elems(g.M, F) : 0;
                    epi = llama ? EPI_SWIGLU_F16 : EPI_GELU_F16; break;
         case G_DOWN: g.A = c->act; g.W = L.wdown; g.N = d; g.K = F; g.bias = llama ? nullptr : L.bdown; g.out = c->x; g.ldo = d; epi = EPI_RESID;
                      break;
@@ -654,10 +689,11 @@ int tune_gemms(rlgen_ctx* c, hipStream_t st) {
                                                : split_rule(dec_rows_eff, m.max_seqs, g.N, g.K, epi, g.ws_elems);
       std::vector<int> cands = {0, 5};
       if (splits == 1) cands.push_back(3);
-      if (mode == 2 && splits == 1) { cands.push_back(1); cands.push_back(4); }     // beside attention other shapes can win
+      if (mode == 2 && splits == 1 && !pr) { cands.push_back(1); cands.push_back(4); }     // beside attention other shapes can win
       if (!wide_only) {
         cands.push_back(7);
-        if (g.K % 64 == 0 && g.K >= 2048 * splits && g.M <= 2048) cands.push_back(8);     // deeper load pipeline: pays on a long K with few tiles
+        // deeper load pipeline: pays on a long K with few tiles (precise mode is compiled for four tile shapes only)
+        if (g.K % 64 == 0 && g.K >= 2048 * splits && g.M <= 2048 && !pr) cands.push_back(8);
       }
       // clocks drift with load, so the candidates take turns: one warm-up each, then three rounds in which
       // every candidate is timed over two launches; the smallest total wins
@@ -904,7 +940,7 @@ int score_impl(rlgen_ctx* c, const int32_t* seqs, const int32_t* seq_lens, const
       rc = final_norm(c, c->d_lastrow + ch.first, ch.count, ch.count, 0, st);
       if (rc) return rc;
       GemmArgs g{};
-      g.A = c->hfin; g.W = c->lm_head; g.M = ch.count; g.N = m.vocab; g.K = m.d_model;
+      g.A = c->hfin; g.W = c->lm_head; g.M = ch.count; g.N = m.vocab; g.K = m.d_model; g.precise = m.precise;
       g.out = logits + (size_t)ch.first * m.vocab; g.ldo = m.vocab;
       HIPCHK(rl_gemm(g, EPI_F32, st));
     } else {
@@ -1003,7 +1039,7 @@ int rlgen_create(const rlgen_model_cfg* cfg, const rlgen_weights* weights, void*
   if (rl_fill_zero(c->status, 256, st) != hipSuccess) return fail(RLGEN_ERR_DEVICE);
   // The cache must hold finite values everywhere: a partly filled super-block is read whole and the
   // unused keys are masked to probability zero, which only cancels finite values.
-  if (rl_fill_zero(c->kv, (size_t)c->lay.layer_stride * cfg->n_layers * 2, st) != hipSuccess) return fail(RLGEN_ERR_DEVICE);
+  if (rl_fill_zero(c->kv, (size_t)c->kv_plane * c->pw * 2, st) != hipSuccess) return fail(RLGEN_ERR_DEVICE);
   *out = c;
   return RLGEN_OK;
 }
@@ -1234,7 +1270,7 @@ int rlgen_debug_sample(rlgen_ctx* c, const float* hidden, int32_t R, float tempe
   hipStream_t st = (hipStream_t)hip_stream;
   const rlgen_model_cfg& m = c->cfg;
   HIPCHK(rl_norm(hidden, nullptr, R, m.d_model, m.norm_eps, c->fng, m.arch == RLGEN_ARCH_LLAMA ? nullptr : c->fnb, c->hfin,
-                 nullptr, nullptr, nullptr, R, 0, c->status, st));
+                 nullptr, nullptr, nullptr, R, 0, c->status, st, m.precise ? kblk_elems(R, m.d_model) : 0));
   return sample_rows(c, R, temperature, uniforms, forced, 1, 0, tokens, token_logprobs, nullptr, st);
 }
 
@@ -1262,7 +1298,7 @@ int rlgen_sample_static(rlgen_ctx* c, const float* hidden, int32_t R, float temp
   c->target_logit = (float*)(base + STATIC_HFIN_BYTES + STATIC_PARTIAL_BYTES);
   int rc = RLGEN_OK;
   if (rl_norm(hidden, nullptr, R, m.d_model, m.norm_eps, c->fng, m.arch == RLGEN_ARCH_LLAMA ? nullptr : c->fnb, c->hfin, nullptr,
-              nullptr, nullptr, R, 0, c->status, st) != hipSuccess)
+              nullptr, nullptr, R, 0, c->status, st, m.precise ? kblk_elems(R, m.d_model) : 0) != hipSuccess)
     rc = RLGEN_ERR_DEVICE;
   if (rc == RLGEN_OK) rc = sample_rows(c, R, temperature, uniforms, forced, 1, 0, tokens, token_logprobs, nullptr, st);
   c->hfin = keep_hfin; c->partial = keep_partial; c->target_logit = keep_target;
@@ -1385,6 +1421,7 @@ int rlgen_debug_set_gemm(rlgen_ctx* c, int32_t mode, int32_t which, int32_t vari
   // the fused gate/up and LM-head epilogues need a wave to own 64 columns: not the 64-column-per-wave-pair shapes
   const bool wide_only = which == G_LMHEAD || (which == G_UP && c->cfg.arch == RLGEN_ARCH_LLAMA);
   if (wide_only && variant >= 6) return RLGEN_ERR_BAD_ARG;
+  if (c->cfg.precise && variant != -1 && variant != 0 && variant != 3 && variant != 5 && variant != 7) return RLGEN_ERR_BAD_ARG;
   c->tuned[mode][which].variant = variant;
   return RLGEN_OK;
 }

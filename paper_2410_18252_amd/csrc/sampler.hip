@@ -103,6 +103,19 @@ __global__ __launch_bounds__(256) void sample_kernel(SampleArgs a) {
   float logit = -INFINITY;
   if (col < a.vocab) {
     float acc = 0.f;
+    if (a.precise) {
+      // bf16 weights; the normalised row as bf16 hi/lo pairs (their sum is formed in fp32, where it is exact)
+      for (int k = 0; k < a.d; k += 8) {
+        const u32x4 wv = *(const u32x4*)(a.lm_head + kblk_off(col, k, a.vocab));
+        const u32x4 hh = *(const u32x4*)(a.hfin + kblk_off(row, k, a.R));
+        const u32x4 hl = *(const u32x4*)(a.hfin + a.hfin_lo_off + kblk_off(row, k, a.R));
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          acc += __uint_as_float(wv[e] << 16) * (__uint_as_float(hh[e] << 16) + __uint_as_float(hl[e] << 16));
+          acc += __uint_as_float(wv[e] & 0xffff0000u) * (__uint_as_float(hh[e] & 0xffff0000u) + __uint_as_float(hl[e] & 0xffff0000u));
+        }
+      }
+    } else
     for (int k = 0; k < a.d; k += 8) {      // both operands are K-block major: 64 lanes read 8 KB contiguous per K block
       const u32x4 wv = *(const u32x4*)(a.lm_head + kblk_off(col, k, a.vocab));
       const u32x4 hv = *(const u32x4*)(a.hfin + kblk_off(row, k, a.R));

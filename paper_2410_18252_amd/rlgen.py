@@ -37,7 +37,8 @@ class ModelCfg(C.Structure):
                 ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("d_ffn", C.c_int32), ("vocab", C.c_int32),
                 ("rotary_dim", C.c_int32), ("rope_theta", C.c_float), ("norm_eps", C.c_float),
                 ("weight_dtype", C.c_int32), ("max_seqs", C.c_int32), ("max_seq_len", C.c_int32),
-                ("max_kv_tokens", C.c_int64), ("max_batch_tokens", C.c_int32), ("share_prompt_kv", C.c_int32)]
+                ("max_kv_tokens", C.c_int64), ("max_batch_tokens", C.c_int32), ("share_prompt_kv", C.c_int32),
+                ("precise", C.c_int32)]
 
 
 LAYER_FIELDS = ["norm1_g", "norm1_b", "norm2_g", "norm2_b", "wq", "wk", "wv", "bq", "bk", "bv", "wo", "bo",
@@ -135,11 +136,11 @@ def _host_i32(a):
 
 
 def make_cfg(model, *, weight_dtype: int, max_seqs: int, max_seq_len: int, max_kv_tokens: int,
-             max_batch_tokens: int = 0, share_prompt_kv: int = 0) -> ModelCfg:
+             max_batch_tokens: int = 0, share_prompt_kv: int = 0, precise: int = 0) -> ModelCfg:
     """ModelCfg from any object with the model-shape fields (arch, n_layers, d_model, ...)."""
     return ModelCfg(model.arch, model.n_layers, model.d_model, model.n_q_heads, model.n_kv_heads, model.head_dim,
                     model.d_ffn, model.vocab, model.rotary_dim, model.rope_theta, model.norm_eps, weight_dtype,
-                    max_seqs, max_seq_len, max_kv_tokens, max_batch_tokens, share_prompt_kv)
+                    max_seqs, max_seq_len, max_kv_tokens, max_batch_tokens, share_prompt_kv, precise)
 
 
 def rlgen_workspace_bytes(cfg: ModelCfg) -> int:

@@ -91,14 +91,14 @@ def reference_decoder(W: Weights, m, precise=0):
     return O.Decoder(W, m)
 
 
-def make_policy(W: Weights, *, max_seqs, max_seq_len, max_kv_tokens=None, max_batch_tokens=0, share_prompt_kv=0):
+def make_policy(W: Weights, *, max_seqs, max_seq_len, max_kv_tokens=None, max_batch_tokens=0, share_prompt_kv=0, precise=0):
     r = R()
     if max_kv_tokens is None:
         max_kv_tokens = max_seqs * ((max_seq_len + 31) // 32 * 32)
     dev = r.upload_weights(W.tensors)
     cfg = r.make_cfg(W.model, weight_dtype=r.DTYPE_BF16 if W.is_bf16 else r.DTYPE_F32, max_seqs=max_seqs,
                      max_seq_len=max_seq_len, max_kv_tokens=max_kv_tokens, max_batch_tokens=max_batch_tokens,
-                     share_prompt_kv=share_prompt_kv)
+                     share_prompt_kv=share_prompt_kv, precise=precise)
     return r.Policy(cfg, dev)
 
 

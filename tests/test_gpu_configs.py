@@ -4,10 +4,16 @@ The GPU runs the whole workload (all prompts, K samples, all new tokens).  The o
 runs a deterministic subset -- the shortest prompt, the longest prompt and the first one or two by
 index, K samples, the first 8 new tokens -- and the GPU's outputs for exactly those sequences are
 compared element by element: tokens (oracle's token forced where its CDF margin <= 1e-3), token
-log-probs (1e-2) and raw logits after the 8th token (2e-2).  The remaining outputs are checked through
-properties that hold at any size: tokens in range, finite log-probs, equal uniforms giving equal
-samples, run-to-run bit-identity, and (workload 4, as its definition asks) rlgen_score over all
-generated sequences reproducing rlgen_generate's log-probs."""
+log-probs (1e-2) and raw logits after the 8th token (2e-2).  An unforced run adds, for the shortest prompt, that every
+token the GPU drew on its own is a valid draw under the oracle's CDF along the GPU's own path (at these vocabularies
+every bucket is narrower than the forcing margin, so the forced comparison alone could not fail on a token).
+The remaining outputs are checked through properties that hold at any size: tokens in range, finite log-probs, equal
+uniforms giving equal samples, run-to-run bit-identity, and rlgen_score over all generated sequences reproducing
+rlgen_generate's log-probs (prompt-pass kernels against decode kernels).
+
+Workload 5 (Llama-3.1-8B-shaped) is held to the stated tolerances in the library's precise mode: in the default formats
+its error is several times the tolerance, which tests/test_rounding_model.py derives from the oracle alone; the default
+formats are run on it too, for their tokens, their properties and a report of their error."""
 import time
 
 import numpy as np
@@ -20,11 +26,22 @@ from gpu_util import MARGIN, TOL_LOGITS, TOL_LOGPROB, R, dev_f32, dev_i32, oracl
 
 pytestmark = pytest.mark.gpu
 N_ORACLE_TOKENS = 8
-RESULTS = {}
 
 
 def log(msg):
     print(f"[{time.strftime('%H:%M:%S')}] {msg}", flush=True)
+
+
+def _policy(r, m, W, B, k, T, lens, share=0, precise=0):
+    r32 = lambda n: (int(n) + 31) // 32 * 32
+    kv = int(sum(r32(n) + k * r32(T) for n in lens)) if share else int(sum(k * r32(int(n) + T) for n in lens))
+    cfg = r.make_cfg(m, weight_dtype=r.DTYPE_BF16, max_seqs=B * k, max_seq_len=int(lens.max()) + T, max_kv_tokens=kv,
+                     share_prompt_kv=share, precise=precise)
+    dev = r.upload_weights(W.tensors)
+    pol = r.Policy(cfg, dev)
+    del dev
+    torch.cuda.empty_cache()
+    return pol
 
 
 @pytest.mark.parametrize("ci", [2, 3, 4, 5])
@@ -39,142 +56,111 @@ def test_full_size_workload(ci):
     B, k, T = w.n_prompts, w.k, w.max_new
     u[1, 1] = u[1, 0]                                    # one prompt draws the same sample twice
     subset = parity_subset(lens, n_first=1 if ci == 5 else 2)
-
-    log("uploading weights and building the context")
-    kv_tokens = int(sum(k * ((int(n) + T + 31) // 32 * 32) for n in lens))
-    cfg = r.make_cfg(m, weight_dtype=r.DTYPE_BF16, max_seqs=B * k, max_seq_len=int(lens.max()) + T,
-                     max_kv_tokens=kv_tokens)
-    dev = r.upload_weights(W.tensors)
-    pol = r.Policy(cfg, dev)
-    del dev
-    torch.cuda.empty_cache()
-
-    log(f"oracle on prompts {subset} (lengths {[int(lens[i]) for i in subset]}), {N_ORACLE_TOKENS} tokens each")
-    dec = O.Decoder(W, m)
     n8 = N_ORACLE_TOKENS
+
+    log(f"oracle on prompts {subset} (lengths {[int(lens[i]) for i in subset]}), {n8} tokens each")
+    dec = O.Decoder(W, m)
     t0 = time.time()
     t_o, l_o, margins, z_o, _ = oracle_generate_batch(dec, arr[subset], lens[subset], k, n8, w.temperature, u[subset][:, :, :n8])
     log(f"oracle done in {time.time() - t0:.1f}s")
     forced = np.full((B, k, T), -1, np.int32)
     forced[subset, :, :n8] = np.where(margins > MARGIN, -1, t_o)
-
-    log("GPU: full workload")
     d_arr, d_u, d_forced = dev_i32(arr), dev_f32(u), dev_i32(forced)
-    t_g, l_g = r.rlgen_generate(pol, d_arr, lens, k, T, w.temperature, d_u, d_forced)
-    torch.cuda.synchronize()
-    tm = r.rlgen_get_timings(pol)
-    log(f"GPU done: prefill {tm['prefill_ms']:.1f} ms, decode {tm['decode_ms']:.1f} ms")
-    assert r.rlgen_status(pol) == 0
-    tg, lg = t_g.cpu().numpy(), l_g.cpu().numpy()
-
-    # subset, element by element
-    lp_err = np.abs(lg[subset][:, :, :n8] - l_o).max()
-    mism = int((tg[subset][:, :, :n8] != t_o).sum())
     seqs8 = [np.concatenate([arr[b, :lens[b]], t_o[i, j]]) for i, b in enumerate(subset) for j in range(k)]
     sarr, slens = padded(seqs8)
-    z_g = r.rlgen_debug_logits(pol, dev_i32(sarr), slens).cpu().numpy()
-    z_err = np.abs(z_g - z_o.reshape(len(seqs8), -1)).max()
-    report(f"config{ci}", logit_err=z_err, lp_err=lp_err, mismatches=mism, forced_fraction=(forced[subset, :, :n8] >= 0).mean(),
-           z_std=z_o.std(), prefill_ms=tm["prefill_ms"], decode_ms=tm["decode_ms"])
-    log(f"logit err {z_err:.4g}, logprob err {lp_err:.4g}, token mismatches {mism}")
-    assert mism == 0
+    full = np.full((B * k, int(lens.max()) + T), -1, np.int32)
+    flens = np.repeat(lens, k) + T
+    for b in range(B):
+        full[b * k:(b + 1) * k, :lens[b]] = arr[b, :lens[b]]
+
+    def run(mode_name, share, precise, strict):
+        """One context: the whole workload, compared with the oracle on the subset and through properties."""
+        tag = f"config{ci}{mode_name}"
+        log(f"GPU [{tag}]: building the context")
+        pol = _policy(r, m, W, B, k, T, lens, share=share, precise=precise)
+        try:
+            t_g, l_g = r.rlgen_generate(pol, d_arr, lens, k, T, w.temperature, d_u, d_forced)
+            torch.cuda.synchronize()
+            tm = r.rlgen_get_timings(pol)
+            log(f"GPU [{tag}] done: prefill {tm['prefill_ms']:.1f} ms, decode {tm['decode_ms']:.1f} ms")
+            assert r.rlgen_status(pol) == 0
+            tg, lg = t_g.cpu().numpy(), l_g.cpu().numpy()
+            # subset, element by element
+            lp_err = np.abs(lg[subset][:, :, :n8] - l_o).max()
+            mism = int((tg[subset][:, :, :n8] != t_o).sum())
+            z_g = r.rlgen_debug_logits(pol, dev_i32(sarr), slens).cpu().numpy()
+            z_err = np.abs(z_g - z_o.reshape(len(seqs8), -1)).max()
+            report(tag, logit_err=z_err, lp_err=lp_err, mismatches=mism, forced_fraction=(forced[subset, :, :n8] >= 0).mean(),
+                   z_std=z_o.std(), prefill_ms=tm["prefill_ms"], decode_ms=tm["decode_ms"])
+            log(f"[{tag}] logit err {z_err:.4g}, logprob err {lp_err:.4g}, token mismatches {mism}")
+            assert mism == 0
+            if strict:
+                assert lp_err < TOL_LOGPROB
+                assert z_err < TOL_LOGITS
+            else:
+                # the default formats on the Llama-8B-shaped model: outside the stated tolerances (see the module docstring);
+                # this only catches a gross error, it is not the parity claim
+                assert lp_err < 50 * TOL_LOGPROB and z_err < 50 * TOL_LOGITS
+            # everything else, through properties
+            assert ((tg >= 0) & (tg < m.vocab)).all()
+            assert np.isfinite(lg).all() and (lg < 0).all()
+            np.testing.assert_array_equal(tg[1, 0], tg[1, 1])
+            np.testing.assert_array_equal(lg[1, 0], lg[1, 1])
+            t_2, l_2 = r.rlgen_generate(pol, d_arr, lens, k, T, w.temperature, d_u, d_forced)
+            assert torch.equal(t_2, t_g) and torch.equal(l_2, l_g)
+            if strict:
+                # unforced: the GPU's own draws for the shortest prompt are valid under the oracle's CDF along the GPU's path
+                t_f, l_f = r.rlgen_generate(pol, d_arr, lens, k, T, w.temperature, d_u)
+                b0 = subset[0]
+                tf = t_f[b0, :, :n8].cpu().numpy()
+                buckets = np.zeros((k, n8, 2))
+                _, l_t, _ = O.generate(dec, arr[b0, :lens[b0]], k, n8, w.temperature, u[b0][:, :n8], forced=tf, buckets=buckets)
+                uu = u[b0][:, :n8]
+                slack = max(float((buckets[..., 0] - uu).max()), float((uu - buckets[..., 1]).max()))
+                report(tag + "-unforced", cdf_slack=slack, lp_err=np.abs(l_f[b0, :, :n8].cpu().numpy() - l_t).max(),
+                       same_as_forced=float((tf == t_o[0]).mean()))
+                assert (buckets[..., 0] - MARGIN <= uu).all() and (uu <= buckets[..., 1] + MARGIN).all()
+                assert np.abs(l_f[b0, :, :n8].cpu().numpy() - l_t).max() < TOL_LOGPROB
+                # scoring all generated sequences (prompt-pass kernels) reproduces generate's log-probs (decode kernels)
+                for b in range(B):
+                    for j in range(k):
+                        full[b * k + j, lens[b]:lens[b] + T] = tg[b, j]
+                sc = r.rlgen_score(pol, dev_i32(full), flens, w.temperature, np.repeat(lens, k))
+                torch.cuda.synchronize()
+                log(f"[{tag}] score done in {r.rlgen_get_timings(pol)['prefill_ms']:.1f} ms")
+                sc = sc.cpu().numpy()
+                worst = 0.0
+                for i in range(B * k):
+                    P = int(flens[i]) - T
+                    worst = max(worst, float(np.abs(sc[i, P:P + T] - lg.reshape(B * k, T)[i]).max()))
+                    assert (sc[i, :P] == 0).all() and (sc[i, P + T:] == 0).all()
+                report(tag + "-score-vs-generate", err=worst)
+                assert worst < TOL_LOGPROB
+                if not share:
+                    # the same with each prompt run once for its k completions
+                    r.rlgen_set_score_groups(pol, k)
+                    sg = r.rlgen_score(pol, dev_i32(full), flens, w.temperature, np.repeat(lens, k))
+                    torch.cuda.synchronize()
+                    log(f"[{tag}] grouped score done in {r.rlgen_get_timings(pol)['prefill_ms']:.1f} ms")
+                    r.rlgen_set_score_groups(pol, 1)
+                    assert r.rlgen_status(pol) == 0
+                    sg = sg.cpu().numpy()
+                    report(tag + "-grouped-score", vs_plain=np.abs(sg - sc).max())
+                    assert np.abs(sg - sc).max() < TOL_LOGPROB
+                    assert ((sg == 0) == (sc == 0)).all()
+                    # and against the oracle on the subset's 8-token sequences
+                    sc8 = r.rlgen_score(pol, dev_i32(sarr), slens, w.temperature, slens - n8).cpu().numpy()
+                    for i in range(len(seqs8)):
+                        assert np.abs(sc8[i, slens[i] - n8:slens[i]] - l_o.reshape(-1, n8)[i]).max() < TOL_LOGPROB
+        finally:
+            pol.close()
+
     if ci == 5:
-        # The N(0, 0.02) Llama-8B-shaped model amplifies 16-bit rounding of its activations and of the KV
-        # cache far more than the GPT-NeoX shapes do: a CPU emulation of exactly the library's rounding
-        # points (fp16 GEMM inputs, bf16 K/V) applied to the oracle reproduces the GPU's error to three
-        # digits (0.0148 at one layer, 0.028 at four, growing like sqrt(layers)), so the stated bound is
-        # out of reach of any 16-bit KV cache on this workload.  The bound asserted here is twice the
-        # measured error; the stated one is checked by test_workload5_stated_tolerance (expected to fail).
-        RESULTS[5] = (z_err, lp_err)
-        assert lp_err < 0.25 and z_err < 0.3
+        run("-precise", share=0, precise=1, strict=True)
+        run("-precise-shared", share=1, precise=1, strict=True)
+        run("", share=0, precise=0, strict=False)
+        run("-shared", share=1, precise=0, strict=False)
     else:
-        assert lp_err < TOL_LOGPROB
-        assert z_err < TOL_LOGITS
-
-    # everything else, through properties
-    assert ((tg >= 0) & (tg < m.vocab)).all()
-    assert np.isfinite(lg).all() and (lg < 0).all()
-    np.testing.assert_array_equal(tg[1, 0], tg[1, 1])
-    np.testing.assert_array_equal(lg[1, 0], lg[1, 1])
-    t_2, l_2 = r.rlgen_generate(pol, d_arr, lens, k, T, w.temperature, d_u, d_forced)
-    assert torch.equal(t_2, t_g) and torch.equal(l_2, l_g)
-    if ci in (2, 4):
-        log("GPU: scoring all generated sequences")
-        full = np.full((B * k, int(lens.max()) + T), -1, np.int32)
-        flens = np.repeat(lens, k) + T
-        for b in range(B):
-            for j in range(k):
-                full[b * k + j, :lens[b]] = arr[b, :lens[b]]
-                full[b * k + j, lens[b]:lens[b] + T] = tg[b, j]
-        sc = r.rlgen_score(pol, dev_i32(full), flens, w.temperature, np.repeat(lens, k))
-        torch.cuda.synchronize()
-        log(f"score done in {r.rlgen_get_timings(pol)['prefill_ms']:.1f} ms")
-        sc = sc.cpu().numpy()
-        worst = 0.0
-        for i in range(B * k):
-            P = int(flens[i]) - T
-            worst = max(worst, float(np.abs(sc[i, P:P + T] - lg.reshape(B * k, T)[i]).max()))
-            assert (sc[i, :P] == 0).all() and (sc[i, P + T:] == 0).all()
-        report(f"config{ci}-score-vs-generate", err=worst)
-        assert worst < TOL_LOGPROB
-        # the same with each prompt run once for its k completions
-        r.rlgen_set_score_groups(pol, k)
-        sg = r.rlgen_score(pol, dev_i32(full), flens, w.temperature, np.repeat(lens, k))
-        torch.cuda.synchronize()
-        log(f"grouped score done in {r.rlgen_get_timings(pol)['prefill_ms']:.1f} ms")
-        r.rlgen_set_score_groups(pol, 1)
-        assert r.rlgen_status(pol) == 0
-        sg = sg.cpu().numpy()
-        report(f"config{ci}-grouped-score", vs_plain=np.abs(sg - sc).max())
-        assert np.abs(sg - sc).max() < TOL_LOGPROB
-        assert ((sg == 0) == (sc == 0)).all()
-        # and against the oracle on the subset's 8-token sequences
-        sc8 = r.rlgen_score(pol, dev_i32(sarr), slens, w.temperature, slens - n8).cpu().numpy()
-        for i in range(len(seqs8)):
-            assert np.abs(sc8[i, slens[i] - n8:slens[i]] - l_o.reshape(-1, n8)[i]).max() < TOL_LOGPROB
-    pol.close()
-
-    # the same workload with the prompt cache shared by the k samples of a prompt
-    if ci in (2, 4, 5):
-        log("GPU: full workload, shared prompt cache")
-        r32 = lambda n: (int(n) + 31) // 32 * 32
-        cfg = r.make_cfg(m, weight_dtype=r.DTYPE_BF16, max_seqs=B * k, max_seq_len=int(lens.max()) + T,
-                         max_kv_tokens=int(sum(r32(n) + k * r32(T) for n in lens)), share_prompt_kv=1)
-        dev = r.upload_weights(W.tensors)
-        pol = r.Policy(cfg, dev)
-        del dev
-        torch.cuda.empty_cache()
-        t_s, l_s = r.rlgen_generate(pol, d_arr, lens, k, T, w.temperature, d_u, d_forced)
-        torch.cuda.synchronize()
-        tm = r.rlgen_get_timings(pol)
-        log(f"GPU done: prefill {tm['prefill_ms']:.1f} ms, decode {tm['decode_ms']:.1f} ms")
-        assert r.rlgen_status(pol) == 0
-        ts, ls = t_s.cpu().numpy(), l_s.cpu().numpy()
-        lp_err_s = np.abs(ls[subset][:, :, :n8] - l_o).max()
-        mism_s = int((ts[subset][:, :, :n8] != t_o).sum())
-        report(f"config{ci}-shared", lp_err=lp_err_s, mismatches=mism_s, prefill_ms=tm["prefill_ms"], decode_ms=tm["decode_ms"])
-        log(f"shared: logprob err {lp_err_s:.4g}, mismatches {mism_s}")
-        assert mism_s == 0
-        assert lp_err_s < (0.25 if ci == 5 else TOL_LOGPROB)
-        assert ((ts >= 0) & (ts < m.vocab)).all() and np.isfinite(ls).all() and (ls < 0).all()
-        np.testing.assert_array_equal(ls[1, 0], ls[1, 1])
+        run("", share=0, precise=0, strict=True)
         if ci in (2, 4):
-            # all sequences: the teacher-forced pass (per-sequence cache, prompt-pass kernels) reproduces the log-probs
-            for b in range(B):
-                for j in range(k):
-                    full[b * k + j, lens[b]:lens[b] + T] = ts[b, j]
-            sc = r.rlgen_score(pol, dev_i32(full), flens, w.temperature, np.repeat(lens, k)).cpu().numpy()
-            worst = max(float(np.abs(sc[i, flens[i] - T:flens[i]] - ls.reshape(B * k, T)[i]).max()) for i in range(B * k))
-            report(f"config{ci}-shared-score-vs-generate", err=worst)
-            assert worst < TOL_LOGPROB
-        np.testing.assert_array_equal(ts[1, 0], ts[1, 1])
-        pol.close()
-
-
-@pytest.mark.xfail(reason="16-bit activations and KV cache cannot reach 2e-2 / 1e-2 on the random Llama-8B-shaped model",
-                   strict=False)
-def test_workload5_stated_tolerance():
-    if 5 not in RESULTS:
-        pytest.skip("workload 5 did not run in this session")
-    z_err, lp_err = RESULTS[5]
-    assert z_err < TOL_LOGITS and lp_err < TOL_LOGPROB
+            run("-shared", share=1, precise=0, strict=True)
