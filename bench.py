@@ -62,6 +62,8 @@ def main():
     ap.add_argument("--score-plain", action="store_true",
                     help="score every generated sequence on its own instead of a prompt once with its k completions")
     ap.add_argument("--k", type=int, default=0, help="override the workload's samples per prompt")
+    ap.add_argument("--precise", action="store_true",
+                    help="the library's precise mode (bf16 hi/lo pairs instead of fp16 / bf16 values): what its accuracy costs")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1")
@@ -89,7 +91,7 @@ def main():
     kv_tokens = int(sum(r32(n) + k * r32(T) for n in lens)) if share else int(sum(k * r32(int(n) + T) for n in lens))
     cfg = R.make_cfg(m, weight_dtype=R.DTYPE_BF16 if W.is_bf16 else R.DTYPE_F32, max_seqs=S,
                      max_seq_len=int(lens.max()) + T, max_kv_tokens=kv_tokens, share_prompt_kv=share,
-                     max_batch_tokens=args.max_batch_tokens)
+                     max_batch_tokens=args.max_batch_tokens, precise=1 if args.precise else 0)
     dev = R.upload_weights(W.tensors)
     pol = R.Policy(cfg, dev)
     del dev
@@ -171,7 +173,7 @@ def main():
     # decode step t): every sequence reads its K and V streams of ctx = prompt_len + t keys (bf16), plus q in
     # and the attention output out (fp16).
     seq_len = np.repeat(lens.astype(np.int64), k)
-    per_key = 2 * 2 * m.n_kv_heads * m.head_dim                    # K and V, 2 bytes each
+    per_key = 2 * 2 * m.n_kv_heads * m.head_dim * (2 if args.precise else 1)      # K and V, 2 bytes each (precise: two planes)
     qo = 2 * 2 * S * m.n_q_heads * m.head_dim
     # with a shared prompt cache a launch reads each prompt's keys once, and t new keys per sequence
     keys = (lambda t: int(lens.astype(np.int64).sum()) + S * t) if share else (lambda t: int((seq_len + t).sum()))
@@ -223,13 +225,18 @@ def main():
         "metric": "generated tokens/s (K=2/prompt) at 1 GPU; decode HBM GB/s as % of peak",
         "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 2), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16", "data": "synthetic",
+        "dtype": "bf16x2" if args.precise else "f16", "data": "synthetic",
         "config": {"workload": w.name, "prompts": B, "k": k, "max_new": T, "prompt_len": [w.prompt_len_lo, w.prompt_len_hi],
                    "temperature": w.temperature, "generated_tokens_per_step": real_tokens,
                    "step": ("rlgen_generate, then rlgen_score over the generated sequences"
                             + ("" if args.score_plain else f" (groups of {k} sharing their prompt)")) if with_score else "rlgen_generate",
                    "kv_layout": "prompt cache shared by the k samples" if share else "one contiguous cache per sequence",
-                   "storage": "bf16 weights (held as fp16, exact) and bf16 KV cache; fp16 MFMA inputs, fp32 accumulation"},
+                   "storage": ("bf16 weights; activations and KV cache as bf16 hi/lo pairs (precise mode), bf16 MFMA, fp32 accumulation"
+                               if args.precise else
+                               "bf16 weights (held as fp16, exact) and bf16 KV cache; fp16 MFMA inputs, fp32 accumulation"),
+                   # tile-shape variant and K split per linear layer (QKV, O, FFN up, FFN down, LM head) as the context chose them
+                   "gemm_choices": {name: [list(R.rlgen_debug_get_gemm(pol, mode, which)) for which in range(5)]
+                                    for mode, name in ((0, "decode"), (1, "prompt_pass"), (2, "decode_half"))}},
         "prefill_ms": round(float(np.mean(prefill_ms)), 2), "decode_ms": round(float(np.mean(decode_ms)), 2),
         "score_ms": round(float(np.mean(score_ms)), 2) if score_ms else None,
         "generate_only_tokens_per_s": round(real_tokens / (1e-3 * float(np.mean(prefill_ms) + np.mean(decode_ms))), 1),

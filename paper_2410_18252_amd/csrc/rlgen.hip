@@ -562,11 +562,15 @@ double weight_bytes_of(const rlgen_model_cfg& m) {
 // shapes a context picked and whether a decode step covers the whole batch, half of it, or what EOS compaction left.
 // `rows` is the row count the launches are sized for.  The cut pays when 64x128 tiles leave CUs idle: about two blocks
 // per CU, every part keeping at least 4 K tiles, at most 8 parts, and the fp32 partial sums must fit the scratch.
-int split_rule(int rows, int cap_rows, int N, int K, int epi, size_t ws_elems) {
+// `beside_attention`: the launches are those of a two-stream decode, which run beside the other half's attention and
+// share the path from L2 into the CUs with it; there the extra operand traffic of small tiles and the pass over the
+// partial sums cost more than idle CUs do, so the cut stops at one block per CU (measured on the 2.8B shape: 3 parts
+// for the 2560-wide projections of a 512-row half are 3 % slower over the decode phase than none).
+int split_rule(int rows, int cap_rows, int N, int K, int epi, size_t ws_elems, bool beside_attention) {
   if (epi != EPI_F32 && epi != EPI_RESID && epi != EPI_GELU_F16) return 1;      // the other epilogues have no two-pass form
   const long long t = (long long)((rows + 63) / 64) * ((N + 127) / 128);
   const int nk = (K + 63) / 64;
-  long long sp = (512 + t / 2) / t;
+  long long sp = beside_attention ? 256 / t : (512 + t / 2) / t;
   sp = std::min<long long>(sp, 8);
   sp = std::min<long long>(sp, nk / 4);
   sp = std::min<long long>(sp, (long long)(ws_elems / ((size_t)cap_rows * N)));
@@ -685,8 +689,8 @@ int tune_gemms(rlgen_ctx* c, hipStream_t st) {
       }
       const bool wide_only = epi == EPI_SWIGLU_F16 || epi == EPI_LMHEAD;
       // the K split: by rule, the same for every decode mode
-      const int splits = !g.ws ? 1 : mode == 1 ? split_rule(c->R, c->R, g.N, g.K, epi, g.ws_elems)
-                                               : split_rule(dec_rows_eff, m.max_seqs, g.N, g.K, epi, g.ws_elems);
+      const int splits = !g.ws ? 1 : mode == 1 ? split_rule(c->R, c->R, g.N, g.K, epi, g.ws_elems, false)
+                                               : split_rule(dec_rows_eff, m.max_seqs, g.N, g.K, epi, g.ws_elems, tune_half);
       std::vector<int> cands = {0, 5};
       if (splits == 1) cands.push_back(3);
       if (mode == 2 && splits == 1 && !pr) { cands.push_back(1); cands.push_back(4); }     // beside attention other shapes can win
