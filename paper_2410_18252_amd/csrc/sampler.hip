@@ -2,7 +2,7 @@
 // row and per group of 64 vocabulary columns, the max and the sum of exp of the tempered logits --
 // never the logits or the probabilities.  Here one wave per row combines them into log Z, walks
 // the group sums in ascending vocabulary order (fp64) to find the group in which the CDF crosses
-// u, recomputes that group's 64 logits (one column per lane) and finishes the scan inside it.
+// u, recomputes that group's 64 logits and finishes the scan inside it (one column per lane).
 #include "kernels.h"
 
 namespace {
@@ -98,35 +98,65 @@ __global__ __launch_bounds__(256) void sample_kernel(SampleArgs a) {
   }
   if (forced >= 0) gmin = forced >> 6;
 
-  // recompute the 64 tempered logits of group gmin: lane j <-> column 64 gmin + j
-  const int col = gmin * 64 + lane;
-  float logit = -INFINITY;
-  if (col < a.vocab) {
-    float acc = 0.f;
-    if (a.precise) {
-      // bf16 weights; the normalised row as bf16 hi/lo pairs (their sum is formed in fp32, where it is exact)
-      for (int k = 0; k < a.d; k += 8) {
-        const u32x4 wv = *(const u32x4*)(a.lm_head + kblk_off(col, k, a.vocab));
-        const u32x4 hh = *(const u32x4*)(a.hfin + kblk_off(row, k, a.R));
-        const u32x4 hl = *(const u32x4*)(a.hfin + a.hfin_lo_off + kblk_off(row, k, a.R));
+  // Recompute the 64 tempered logits of group gmin.  Both operands are K-block major (a column's 64 K values are one
+  // 128-byte line), so the lanes work in groups of eight: lane l reads the 16-byte chunk l % 8 of the lines of columns
+  // l / 8 + 8 j, j = 0..7 -- every wave-wide load is eight whole lines -- and the eight partial sums of a column are
+  // added across its lane group at the end.
+  const int chunk = lane & 7, cgroup = lane >> 3;
+  float part[8];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          acc += __uint_as_float(wv[e] << 16) * (__uint_as_float(hh[e] << 16) + __uint_as_float(hl[e] << 16));
-          acc += __uint_as_float(wv[e] & 0xffff0000u) * (__uint_as_float(hh[e] & 0xffff0000u) + __uint_as_float(hl[e] & 0xffff0000u));
-        }
+  for (int j = 0; j < 8; ++j) part[j] = 0.f;
+  for (int kb = 0; kb < a.d; kb += 64) {
+    const int k = kb + 8 * chunk;
+    if (k >= a.d) continue;                 // d is a multiple of 32: the last K block may be half full
+    float h[8];
+    if (a.precise) {
+      // the normalised row as bf16 hi/lo pairs: their sum is formed in fp32, where it is exact
+      const u32x4 hh = *(const u32x4*)(a.hfin + kblk_off(row, k, a.R));
+      const u32x4 hl = *(const u32x4*)(a.hfin + a.hfin_lo_off + kblk_off(row, k, a.R));
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        h[2 * e] = __uint_as_float(hh[e] << 16) + __uint_as_float(hl[e] << 16);
+        h[2 * e + 1] = __uint_as_float(hh[e] & 0xffff0000u) + __uint_as_float(hl[e] & 0xffff0000u);
       }
-    } else
-    for (int k = 0; k < a.d; k += 8) {      // both operands are K-block major: 64 lanes read 8 KB contiguous per K block
-      const u32x4 wv = *(const u32x4*)(a.lm_head + kblk_off(col, k, a.vocab));
+    } else {
       const u32x4 hv = *(const u32x4*)(a.hfin + kblk_off(row, k, a.R));
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        acc += f16_bits_to_f32((uint16_t)(wv[e] & 0xffffu)) * f16_bits_to_f32((uint16_t)(hv[e] & 0xffffu));
-        acc += f16_bits_to_f32((uint16_t)(wv[e] >> 16)) * f16_bits_to_f32((uint16_t)(hv[e] >> 16));
+        h[2 * e] = f16_bits_to_f32((uint16_t)(hv[e] & 0xffffu));
+        h[2 * e + 1] = f16_bits_to_f32((uint16_t)(hv[e] >> 16));
       }
     }
-    logit = acc / a.temperature;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int c = gmin * 64 + cgroup + 8 * j;
+      if (c >= a.vocab) continue;
+      const u32x4 wv = *(const u32x4*)(a.lm_head + kblk_off(c, k, a.vocab));
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        if (a.precise) {                    // bf16 weights
+          part[j] += __uint_as_float(wv[e] << 16) * h[2 * e];
+          part[j] += __uint_as_float(wv[e] & 0xffff0000u) * h[2 * e + 1];
+        } else {
+          part[j] += f16_bits_to_f32((uint16_t)(wv[e] & 0xffffu)) * h[2 * e];
+          part[j] += f16_bits_to_f32((uint16_t)(wv[e] >> 16)) * h[2 * e + 1];
+        }
+      }
+    }
   }
+  // lane L ends up with column 64 gmin + L = cgroup' + 8 j' for cgroup' = L % 8, j' = L / 8: the sum of lane group cgroup'
+  float acc = 0.f;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    float v = part[j];
+    v += __shfl_xor(v, 1, WAVE);
+    v += __shfl_xor(v, 2, WAVE);
+    v += __shfl_xor(v, 4, WAVE);
+    const float t = __shfl(v, 8 * (lane & 7), WAVE);
+    if ((lane >> 3) == j) acc = t;
+  }
+  const int col = gmin * 64 + lane;
+  const float logit = col < a.vocab ? acc / a.temperature : -INFINITY;
   int tok;
   if (forced >= 0) {
     tok = forced;

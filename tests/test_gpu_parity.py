@@ -265,7 +265,6 @@ def test_sampler_group_search_at_full_vocabulary(V):
 # an FFN wide enough (K = 1024 for the down projection) that the K split of the decode GEMMs is more than one part
 WIDE_FFN = ModelShape(0, 2, 64, 4, 4, 16, 1024, 200, rotary_dim=4)
 
-
 @pytest.mark.parametrize("name", ["neox-h80", "llama-gqa4-h16", "neox-wide-ffn", "llama-gqa4-h16/precise", "neox-wide-ffn/precise"])
 def test_results_do_not_depend_on_the_tile_shapes_a_context_picked(name):
     """A context chooses its GEMM tile shapes by timing them, so two contexts may choose differently; how a sum over the
