@@ -106,40 +106,58 @@ __global__ __launch_bounds__(256) void sample_kernel(SampleArgs a) {
   float part[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) part[j] = 0.f;
-  for (int kb = 0; kb < a.d; kb += 64) {
-    const int k = kb + 8 * chunk;
-    if (k >= a.d) continue;                 // d is a multiple of 32: the last K block may be half full
-    float h[8];
-    if (a.precise) {
-      // the normalised row as bf16 hi/lo pairs: their sum is formed in fp32, where it is exact
-      const u32x4 hh = *(const u32x4*)(a.hfin + kblk_off(row, k, a.R));
-      const u32x4 hl = *(const u32x4*)(a.hfin + a.hfin_lo_off + kblk_off(row, k, a.R));
+  // Two K blocks per trip: their 18 loads are requested before the first product, so a trip waits for memory once.
+  // (One block per trip left the wave waiting out a memory latency 40-64 times; four per trip are faster still for this
+  // kernel alone but measured slower over the two-stream decode phase, beside the other half's attention.)  The products
+  // are added in the same order whatever the trip length.
+  constexpr int KB = 2;
+  for (int kb = 0; kb < a.d; kb += 64 * KB) {
+    u32x4 hv[KB], hl[KB], wv[KB][8];
+    bool live[KB];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        h[2 * e] = __uint_as_float(hh[e] << 16) + __uint_as_float(hl[e] << 16);
-        h[2 * e + 1] = __uint_as_float(hh[e] & 0xffff0000u) + __uint_as_float(hl[e] & 0xffff0000u);
-      }
-    } else {
-      const u32x4 hv = *(const u32x4*)(a.hfin + kblk_off(row, k, a.R));
+    for (int q = 0; q < KB; ++q) {
+      const int k = kb + 64 * q + 8 * chunk;
+      live[q] = k < a.d;                   // d is a multiple of 32: the last K block may be half full
+      if (!live[q]) continue;
+      hv[q] = *(const u32x4*)(a.hfin + kblk_off(row, k, a.R));
+      if (a.precise) hl[q] = *(const u32x4*)(a.hfin + a.hfin_lo_off + kblk_off(row, k, a.R));
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        h[2 * e] = f16_bits_to_f32((uint16_t)(hv[e] & 0xffffu));
-        h[2 * e + 1] = f16_bits_to_f32((uint16_t)(hv[e] >> 16));
+      for (int j = 0; j < 8; ++j) {
+        const int c = gmin * 64 + cgroup + 8 * j;
+        if (c < a.vocab) wv[q][j] = *(const u32x4*)(a.lm_head + kblk_off(c, k, a.vocab));
       }
     }
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int c = gmin * 64 + cgroup + 8 * j;
-      if (c >= a.vocab) continue;
-      const u32x4 wv = *(const u32x4*)(a.lm_head + kblk_off(c, k, a.vocab));
+    for (int q = 0; q < KB; ++q) {
+      if (!live[q]) continue;
+      float h[8];
+      if (a.precise) {
+        // the normalised row as bf16 hi/lo pairs: their sum is formed in fp32, where it is exact
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        if (a.precise) {                    // bf16 weights
-          part[j] += __uint_as_float(wv[e] << 16) * h[2 * e];
-          part[j] += __uint_as_float(wv[e] & 0xffff0000u) * h[2 * e + 1];
-        } else {
-          part[j] += f16_bits_to_f32((uint16_t)(wv[e] & 0xffffu)) * h[2 * e];
-          part[j] += f16_bits_to_f32((uint16_t)(wv[e] >> 16)) * h[2 * e + 1];
+        for (int e = 0; e < 4; ++e) {
+          h[2 * e] = __uint_as_float(hv[q][e] << 16) + __uint_as_float(hl[q][e] << 16);
+          h[2 * e + 1] = __uint_as_float(hv[q][e] & 0xffff0000u) + __uint_as_float(hl[q][e] & 0xffff0000u);
+        }
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          h[2 * e] = f16_bits_to_f32((uint16_t)(hv[q][e] & 0xffffu));
+          h[2 * e + 1] = f16_bits_to_f32((uint16_t)(hv[q][e] >> 16));
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int c = gmin * 64 + cgroup + 8 * j;
+        if (c >= a.vocab) continue;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          if (a.precise) {                    // bf16 weights
+            part[j] += __uint_as_float(wv[q][j][e] << 16) * h[2 * e];
+            part[j] += __uint_as_float(wv[q][j][e] & 0xffff0000u) * h[2 * e + 1];
+          } else {
+            part[j] += f16_bits_to_f32((uint16_t)(wv[q][j][e] & 0xffffu)) * h[2 * e];
+            part[j] += f16_bits_to_f32((uint16_t)(wv[q][j][e] >> 16)) * h[2 * e + 1];
+          }
         }
       }
     }
