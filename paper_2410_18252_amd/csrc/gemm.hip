@@ -66,8 +66,8 @@ __device__ __forceinline__ void wait_loads_then_barrier() {
 
 // NS = 0: tiles travel global -> registers -> LDS (two LDS stages).  NS >= 2: NS LDS stages filled by direct
 // global -> LDS loads, issued NS - 1 K steps ahead (needs K % 64 == 0).
-// PR: precise mode (see GemmArgs): bf16 operands, A as hi/lo pairs, the K loop runs over the hi blocks and then the
-// lo blocks of A against the same blocks of W.
+// PR: precise mode (see GemmArgs): bf16 operands, A as hi/lo pairs; every K block of W meets the hi and then the lo
+// block of A in two consecutive steps of the K loop.
 template <int BM, int BN, int WM, int WN, int EPI, bool KTAIL, int NS = 0, bool PR = false>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_f16_kernel(GemmArgs g) {
   constexpr int NT = WM * WN * 64;               // threads
@@ -111,18 +111,21 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f16_kernel(GemmArgs g) {
   }
   const size_t ka = (size_t)g.M * 64, kw = (size_t)g.N * 64;    // elements between K tiles
   const int nkb = (g.K + BK - 1) / BK;                          // K blocks of W (and of each half of a hi/lo A)
-  // K tile kt of the loop reads block kt of A and block wk(kt) of W
-  auto wk = [&](int kt) { return PR && kt >= nkb ? kt - nkb : kt; };
+  // K tile kt of the loop reads block ak(kt) of A and block wk(kt) of W.  Precise mode takes the hi and the lo block of A
+  // against the same block of W in consecutive steps (A holds its nkb hi blocks, then its nkb lo blocks): the second
+  // request for the W block finds it in L2, so the weights cross HBM once
+  auto wk = [&](int kt) { return PR ? kt >> 1 : kt; };
+  auto ak = [&](int kt) { return PR ? (kt >> 1) + (kt & 1) * nkb : kt; };
   auto load_global = [&](int kt) {
     if constexpr (KTAIL) {     // K is not a multiple of BK: chunks beyond K read as zero
       const bool ok = wk(kt) * BK + ld_chunk * 8 < g.K;
 #pragma unroll
-      for (int i = 0; i < PA; ++i) ra[i] = ok ? *(const u32x4*)(pa[i] + kt * ka) : u32x4{0, 0, 0, 0};
+      for (int i = 0; i < PA; ++i) ra[i] = ok ? *(const u32x4*)(pa[i] + ak(kt) * ka) : u32x4{0, 0, 0, 0};
 #pragma unroll
       for (int i = 0; i < PB; ++i) rb[i] = ok ? *(const u32x4*)(pb[i] + wk(kt) * kw) : u32x4{0, 0, 0, 0};
     } else {
 #pragma unroll
-      for (int i = 0; i < PA; ++i) ra[i] = *(const u32x4*)(pa[i] + kt * ka);
+      for (int i = 0; i < PA; ++i) ra[i] = *(const u32x4*)(pa[i] + ak(kt) * ka);
 #pragma unroll
       for (int i = 0; i < PB; ++i) rb[i] = *(const u32x4*)(pb[i] + wk(kt) * kw);
     }
@@ -222,7 +225,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_f16_kernel(GemmArgs g) {
       uint16_t* la = lds + buf * STAGE + wave_u * 8 * BK;
 #pragma unroll
       for (int i = 0; i < PA; ++i)
-        __builtin_amdgcn_global_load_lds((gptr_t)(qa[i] + kt * ka), (lptr_t)(la + i * RPP * BK), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((gptr_t)(qa[i] + ak(kt) * ka), (lptr_t)(la + i * RPP * BK), 16, 0, 0);
 #pragma unroll
       for (int i = 0; i < PB; ++i)
         __builtin_amdgcn_global_load_lds((gptr_t)(qb[i] + wk(kt) * kw), (lptr_t)(la + (BM + i * RPP) * BK), 16, 0, 0);
