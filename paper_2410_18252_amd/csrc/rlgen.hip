@@ -697,7 +697,7 @@ int tune_gemms(rlgen_ctx* c, hipStream_t st) {
       if (!wide_only) {
         cands.push_back(7);
         // deeper load pipeline: pays on a long K with few tiles (precise mode is compiled for four tile shapes only)
-        if (g.K % 64 == 0 && g.K >= 2048 * splits && g.M <= 2048 && !pr) cands.push_back(8);
+        if (g.K % 64 == 0 && g.K >= 2048 * splits && g.M <= 2048 && !pr) { cands.push_back(8); cands.push_back(9); }
       }
       // clocks drift with load, so the candidates take turns: one warm-up each, then three rounds in which
       // every candidate is timed over two launches; the smallest total wins
@@ -1421,7 +1421,7 @@ int rlgen_debug_get_gemm(rlgen_ctx* c, int32_t mode, int32_t which, int32_t* var
 
 int rlgen_debug_set_gemm(rlgen_ctx* c, int32_t mode, int32_t which, int32_t variant) {
   if (!c) return RLGEN_ERR_NULL;
-  if (mode < 0 || mode > 2 || which < 0 || which > 4 || variant < -1 || variant > 8) return RLGEN_ERR_BAD_ARG;
+  if (mode < 0 || mode > 2 || which < 0 || which > 4 || variant < -1 || variant > 9) return RLGEN_ERR_BAD_ARG;
   // the fused gate/up and LM-head epilogues need a wave to own 64 columns: not the 64-column-per-wave-pair shapes
   const bool wide_only = which == G_LMHEAD || (which == G_UP && c->cfg.arch == RLGEN_ARCH_LLAMA);
   if (wide_only && variant >= 6) return RLGEN_ERR_BAD_ARG;
