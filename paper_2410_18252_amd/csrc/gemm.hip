@@ -636,6 +636,10 @@ hipError_t launch_variant(const GemmArgs& g, int variant, hipStream_t s) {
                  // fragments and for the stage barrier (12-15 % faster than four waves on long-K shapes with few tiles)
       if constexpr (EPI != EPI_SWIGLU_F16 && EPI != EPI_LMHEAD) return launch<64, 128, 2, 4, EPI, 4>(g, s);
       else return hipErrorInvalidValue;
+    case 10:     // the largest tile on sixteen waves of 64x64: four waves per SIMD hide more of each other's waits than two,
+                 // for a third more LDS fragment traffic (a ragged K takes the eight-wave form: its register staging does
+                 // not fit 128 registers per lane)
+      return g.K % BK == 0 ? launch_k<256, 256, 4, 4, EPI, false, 2, false>(g, s) : launch_k<256, 256, 4, 2, EPI, true, 0, false>(g, s);
   }
   return hipErrorInvalidValue;
 }

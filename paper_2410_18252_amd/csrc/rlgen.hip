@@ -692,7 +692,7 @@ int tune_gemms(rlgen_ctx* c, hipStream_t st) {
       const int splits = !g.ws ? 1 : mode == 1 ? split_rule(c->R, c->R, g.N, g.K, epi, g.ws_elems, false)
                                                : split_rule(dec_rows_eff, m.max_seqs, g.N, g.K, epi, g.ws_elems, tune_half);
       std::vector<int> cands = {0, 5};
-      if (splits == 1) cands.push_back(3);
+      if (splits == 1) { cands.push_back(3); if (!pr) cands.push_back(10); }
       if (mode == 2 && splits == 1 && !pr) { cands.push_back(1); cands.push_back(4); }     // beside attention other shapes can win
       if (!wide_only) {
         cands.push_back(7);
@@ -1421,10 +1421,10 @@ int rlgen_debug_get_gemm(rlgen_ctx* c, int32_t mode, int32_t which, int32_t* var
 
 int rlgen_debug_set_gemm(rlgen_ctx* c, int32_t mode, int32_t which, int32_t variant) {
   if (!c) return RLGEN_ERR_NULL;
-  if (mode < 0 || mode > 2 || which < 0 || which > 4 || variant < -1 || variant > 9) return RLGEN_ERR_BAD_ARG;
+  if (mode < 0 || mode > 2 || which < 0 || which > 4 || variant < -1 || variant > 10) return RLGEN_ERR_BAD_ARG;
   // the fused gate/up and LM-head epilogues need a wave to own 64 columns: not the 64-column-per-wave-pair shapes
   const bool wide_only = which == G_LMHEAD || (which == G_UP && c->cfg.arch == RLGEN_ARCH_LLAMA);
-  if (wide_only && variant >= 6) return RLGEN_ERR_BAD_ARG;
+  if (wide_only && variant >= 6 && variant <= 9) return RLGEN_ERR_BAD_ARG;
   if (c->cfg.precise && variant != -1 && variant != 0 && variant != 3 && variant != 5 && variant != 7) return RLGEN_ERR_BAD_ARG;
   c->tuned[mode][which].variant = variant;
   return RLGEN_OK;

@@ -281,8 +281,8 @@ def test_results_do_not_depend_on_the_tile_shapes_a_context_picked(name):
     u = rng.random((5, 2, 7), dtype=np.float32)
     outs, picks = [], []
     # contexts 0-2: the measured choice, and that choice moved on by one and by two in the list of legal shapes; then
-    # (default formats) every layer that may take it forced onto the eight-wave small tile
-    for shift in (0, 1, 2) if precise else (0, 1, 2, -9):
+    # (default formats) every layer that may take it forced onto the eight-wave small tile, and onto the sixteen-wave large one
+    for shift in (0, 1, 2) if precise else (0, 1, 2, -9, -10):
         pol = make_policy(W, max_seqs=12, max_seq_len=80, max_batch_tokens=80, precise=precise)
         try:
             r.rlgen_set_decode_split_min(pol, 2 if shift == 2 else 0)      # the third context also decodes as two halves
@@ -291,7 +291,7 @@ def test_results_do_not_depend_on_the_tile_shapes_a_context_picked(name):
                 for which in range(5):
                     v0, sp = r.rlgen_debug_get_gemm(pol, mode, which)
                     wide_only = which == 4 or (which == 2 and m.arch == 1)
-                    legal = [0, 3, 5] + ([] if wide_only else [7]) if precise else list(range(6 if wide_only else 10))
+                    legal = [0, 3, 5] + ([] if wide_only else [7]) if precise else (list(range(6)) + [10] if wide_only else list(range(11)))
                     if shift < 0:
                         v = -shift if -shift in legal else v0
                     else:
